@@ -1,0 +1,160 @@
+/*
+ * libsvf - sparse verification attention for speculative decoding on AMD MI355X (gfx950).
+ *
+ * C ABI of the verification-attention path of "Accelerate Speculative Decoding with
+ * Sparse Computation in Verification" (Sec. 3.1 Sparse Attention, Sec. 3.2 Piecewise
+ * Budget Control, Sec. 3.3 Inter-layer Retrieval Reuse).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - `const svf_shape_t*` is a HOST pointer.  Every other pointer is a DEVICE pointer
+ *    owned by the caller; the library never allocates, frees or synchronises.
+ *  - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null
+ *    stream) and the call returns immediately.
+ *  - Return value: 0 on success, a negative SVF_ERR_* code otherwise.  All argument
+ *    checks happen before any kernel launch; on error nothing has been enqueued.
+ *  - Inputs must be finite.  NaN / Inf in q, K, V give unspecified results.
+ *  - Tensor layouts (last index fastest):
+ *      q, out          [B][gamma][Hq][d]          element type = shape.dtype
+ *      k_draft,v_draft [B][gamma][Hkv][d]         element type = shape.dtype
+ *      K, V            cache pool, element type = shape.dtype, addressed as
+ *                        pool + page*kv_stride_page + slot*kv_stride_tok + h*kv_stride_head + c
+ *                      (strides in elements, c in [0,d) contiguous).  With page_size > 0
+ *                      token t of sequence b sits in page block_table[b][t / page_size],
+ *                      slot t % page_size.  With page_size == 0 the cache is contiguous:
+ *                      page = b, slot = t, block_table is ignored (may be NULL).
+ *      block_table     int32 [B][max_pages_per_seq]
+ *      seq_lens        int32 [B]   prefix length per sequence, drafts excluded, 1..max_seq_len
+ *      reps            fp32  [B][Hkv][nb_max][d],  nb_max = ceil(max_seq_len / block_size)
+ *      scores          fp32  [B][Hkv][nb_max]
+ *      sel_idx         int32 [B][Hkv][k_blocks]   ascending block ids, padded with -1
+ *      sel_cnt         int32 [B][Hkv]             = min(k_blocks, ceil(seq_len/block_size))
+ *      draft_mask      uint64 [gamma] (or [B][gamma] when mask_per_batch): bit t of entry i
+ *                      set = draft i attends draft t; bit i must be set.  NULL = linear
+ *                      causal drafts (bits 0..i).
+ *      lse             fp32  [B][gamma][Hq]       natural log of sum(exp(scaled logits))
+ *  - Query head j belongs to KV head j / (Hq/Hkv).
+ */
+#ifndef SVF_H_
+#define SVF_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { SVF_F32 = 0, SVF_BF16 = 1 };
+
+enum {
+  SVF_OK = 0,
+  SVF_ERR_NULL = -1,      /* a required pointer is NULL                                    */
+  SVF_ERR_SHAPE = -2,     /* B/gamma/Hq/Hkv/d/block_size/max_seq_len/strides out of range  */
+  SVF_ERR_DTYPE = -3,     /* dtype not SVF_F32 / SVF_BF16                                  */
+  SVF_ERR_PAGING = -4,    /* page_size and block_size not multiples of one another, or
+                             max_pages_per_seq too small for max_seq_len                   */
+  SVF_ERR_BUDGET = -5,    /* k_blocks < 1, or n_sink + n_local > k_blocks                  */
+  SVF_ERR_WORKSPACE = -6, /* workspace NULL, misaligned (256 B) or smaller than required   */
+  SVF_ERR_HIP = -7        /* the HIP runtime refused a launch                              */
+};
+
+typedef struct svf_shape {
+  int32_t B;                 /* sequences in the batch, >= 1                                 */
+  int32_t gamma;             /* draft tokens (or draft-tree nodes) per sequence, 1..64       */
+  int32_t Hq, Hkv;           /* query heads, KV heads; Hq % Hkv == 0                         */
+  int32_t d;                 /* head dimension: 64 or 128                                    */
+  int32_t dtype;             /* SVF_F32 or SVF_BF16                                          */
+  int32_t block_size;        /* Bs: tokens per retrieval block (Sec. 3.1), >= 1              */
+  int32_t page_size;         /* tokens per physical page; 0 = contiguous cache               */
+  int32_t max_pages_per_seq; /* row length of block_table (unused when page_size == 0)       */
+  int32_t max_seq_len;       /* largest prefix length any sequence may have                  */
+  int64_t kv_stride_page;    /* elements between pages (contiguous: between sequences)       */
+  int64_t kv_stride_tok;     /* elements between tokens of a page                            */
+  int64_t kv_stride_head;    /* elements between KV heads of a token                         */
+  int32_t k_blocks;          /* retrieval budget per (sequence, KV head), in blocks          */
+  int32_t n_sink, n_local;   /* first / last blocks that are never evicted (inside k_blocks) */
+  int32_t mask_per_batch;    /* 0: draft_mask is [gamma]; 1: [B][gamma]                      */
+  float sm_scale;            /* softmax scale; <= 0 selects 1/sqrt(d)                        */
+} svf_shape_t;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int svf_version(void);
+
+/* Static text for an SVF_ERR_* code. */
+const char* svf_strerror(int code);
+
+/*
+ * Piecewise budget control, Sec. 3.2, Eq. 6, expressed per KV head and in blocks.
+ * L <= L0: no eviction, returns ceil(L/block_size) and sets *dense = 1.
+ * L  > L0: returns ceil(((L - L0) * rho + L0) / block_size) clamped to [1, ceil(L/block_size)],
+ *          *dense = 0.  `dense` may be NULL.  Host-only arithmetic; returns a negative
+ *          SVF_ERR_SHAPE for L < 1, L0 < 0, block_size < 1 or rho outside (0, 1).
+ */
+int32_t svf_budget_blocks(int64_t L, int64_t L0, double rho, int32_t block_size, int32_t* dense);
+
+/*
+ * Bytes of device workspace the calls below need for `shape` (always a multiple of 256;
+ * 0 if the shape is invalid).  The workspace must be 256-byte aligned and must have been
+ * cleared to zero once (svf_workspace_init) before its first use; the library leaves it
+ * in a reusable state after every call.  Calls that share one workspace must be ordered
+ * on one stream.
+ */
+size_t svf_workspace_bytes(const svf_shape_t* shape);
+
+/* Enqueue the one-time clearing of a workspace (a fill kernel; safe under graph capture). */
+int svf_workspace_init(void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Block representatives (Sec. 3.1: the cache is partitioned per KV head into blocks of
+ * block_size consecutive tokens, Eq. 4; the block term of Eq. 5 is the mean of its keys).
+ *   reps[b][h][j][:] = mean over tokens t of block j of K[b][t][h][:],  fp32,
+ * for blocks first_block <= j < first_block + n_blocks that exist in sequence b
+ * (n_blocks = -1: all blocks).  The last block of a sequence averages the tokens it has.
+ * Rows of blocks that do not exist are left untouched.
+ */
+int svf_block_reps(const svf_shape_t* shape, const void* K, const int32_t* block_table,
+                   const int32_t* seq_lens, int32_t first_block, int32_t n_blocks,
+                   float* reps, void* stream);
+
+/*
+ * Block scores and the shared block set (Sec. 3.1, Eq. 5 and the top-N rule; Sec. 2.2: the
+ * first draft token retrieves for all draft tokens).
+ *   q0[b][h][:]  = mean over the Hq/Hkv query heads of KV head h of q[b][0][.][:]
+ *   s[b][h][j]   = q0[b][h] . reps[b][h][j]                       (fp32, unscaled)
+ *   kept blocks  = first n_sink and last n_local blocks, then the highest scores until
+ *                  min(k_blocks, nb_b) blocks are kept; equal scores: lowest block id first.
+ * Writes sel_idx (ascending, -1 padded), sel_cnt and, if scores_or_null is given, s.
+ */
+int svf_score_select(const svf_shape_t* shape, const void* q, const float* reps,
+                     const int32_t* seq_lens, int32_t* sel_idx, int32_t* sel_cnt,
+                     float* scores_or_null, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Verification attention (Sec. 3.1 / 3.3: only the retrieved blocks participate): every
+ * draft query (b, i, j) attends to all tokens of the blocks sel_idx[b][j / G][0..sel_cnt)
+ * that lie below seq_lens[b], and to the drafts t allowed by its mask, under one softmax
+ * with scale sm_scale; out = sum of softmax weights times values.  lse_or_null is optional.
+ */
+int svf_verify_attn(const svf_shape_t* shape, const void* q, const void* K, const void* V,
+                    const int32_t* block_table, const int32_t* seq_lens,
+                    const void* k_draft, const void* v_draft, const uint64_t* draft_mask_or_null,
+                    const int32_t* sel_idx, const int32_t* sel_cnt,
+                    void* out, float* lse_or_null, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * One layer of one verification step with inter-layer retrieval reuse (Sec. 3.3, Eq. 9).
+ * do_select != 0 (anchor layer): svf_score_select into sel_idx / sel_cnt, then svf_verify_attn.
+ * do_select == 0: svf_verify_attn with the sel_idx / sel_cnt the caller kept from the nearest
+ * preceding anchor layer (reps may then be NULL).  KV head h reuses KV head h's set.
+ */
+int svf_verify_step(const svf_shape_t* shape, int do_select, const void* q, const float* reps,
+                    const void* K, const void* V, const int32_t* block_table,
+                    const int32_t* seq_lens, const void* k_draft, const void* v_draft,
+                    const uint64_t* draft_mask_or_null, int32_t* sel_idx, int32_t* sel_cnt,
+                    void* out, float* lse_or_null, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SVF_H_ */

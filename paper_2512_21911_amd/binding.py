@@ -1,0 +1,162 @@
+"""ctypes binding of libsvf: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (include/svf.h) and does no
+arithmetic of its own.  Tensors are torch CUDA tensors used purely as device memory; work is
+enqueued on torch's current stream.  A missing library is an error: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+from .build import LIB_PATH
+
+SVF_F32, SVF_BF16 = 0, 1
+
+ERR_NAMES = {0: "SVF_OK", -1: "SVF_ERR_NULL", -2: "SVF_ERR_SHAPE", -3: "SVF_ERR_DTYPE", -4: "SVF_ERR_PAGING",
+             -5: "SVF_ERR_BUDGET", -6: "SVF_ERR_WORKSPACE", -7: "SVF_ERR_HIP"}
+
+
+class SvfShape(ctypes.Structure):
+    """Mirror of svf_shape_t."""
+    _fields_ = [
+        ("B", ctypes.c_int32), ("gamma", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+        ("d", ctypes.c_int32), ("dtype", ctypes.c_int32), ("block_size", ctypes.c_int32),
+        ("page_size", ctypes.c_int32), ("max_pages_per_seq", ctypes.c_int32), ("max_seq_len", ctypes.c_int32),
+        ("kv_stride_page", ctypes.c_int64), ("kv_stride_tok", ctypes.c_int64), ("kv_stride_head", ctypes.c_int64),
+        ("k_blocks", ctypes.c_int32), ("n_sink", ctypes.c_int32), ("n_local", ctypes.c_int32),
+        ("mask_per_batch", ctypes.c_int32), ("sm_scale", ctypes.c_float),
+    ]
+
+
+class SvfError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {ERR_NAMES.get(code, code)} ({strerror(code)})")
+
+
+_lib = None
+
+EXPORTS = ["svf_version", "svf_strerror", "svf_budget_blocks", "svf_workspace_bytes", "svf_workspace_init",
+           "svf_block_reps", "svf_score_select", "svf_verify_attn", "svf_verify_step"]
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built (python -m paper_2512_21911_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
+                               "or `python -m paper_2512_21911_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        shp = ctypes.POINTER(SvfShape)
+        L.svf_version.restype = ctypes.c_int
+        L.svf_version.argtypes = []
+        L.svf_strerror.restype = ctypes.c_char_p
+        L.svf_strerror.argtypes = [ctypes.c_int]
+        L.svf_budget_blocks.restype = i32
+        L.svf_budget_blocks.argtypes = [i64, i64, ctypes.c_double, i32, ctypes.POINTER(i32)]
+        L.svf_workspace_bytes.restype = ctypes.c_size_t
+        L.svf_workspace_bytes.argtypes = [shp]
+        L.svf_workspace_init.restype = ctypes.c_int
+        L.svf_workspace_init.argtypes = [vp, ctypes.c_size_t, vp]
+        L.svf_block_reps.restype = ctypes.c_int
+        L.svf_block_reps.argtypes = [shp, vp, vp, vp, i32, i32, vp, vp]
+        L.svf_score_select.restype = ctypes.c_int
+        L.svf_score_select.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.svf_verify_attn.restype = ctypes.c_int
+        L.svf_verify_attn.argtypes = [shp] + [vp] * 13 + [ctypes.c_size_t, vp]
+        L.svf_verify_step.restype = ctypes.c_int
+        L.svf_verify_step.argtypes = [shp, ctypes.c_int] + [vp] * 14 + [ctypes.c_size_t, vp]
+        _lib = L
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise SvfError(rc, where)
+
+
+def svf_version() -> int:
+    return lib().svf_version()
+
+
+def strerror(code: int) -> str:
+    return lib().svf_strerror(code).decode()
+
+
+def svf_budget_blocks(L: int, L0: int, rho: float, block_size: int):
+    dense = ctypes.c_int32(0)
+    k = lib().svf_budget_blocks(L, L0, rho, block_size, ctypes.byref(dense))
+    if k < 0:
+        raise SvfError(k, "svf_budget_blocks")
+    return k, bool(dense.value)
+
+
+def make_shape(*, B, gamma, Hq, Hkv, d, dtype, block_size, max_seq_len, k_blocks, k_pool: Optional[torch.Tensor] = None,
+               page_size=0, max_pages_per_seq=0, n_sink=0, n_local=0, mask_per_batch=0, sm_scale=0.0,
+               kv_strides=None) -> SvfShape:
+    """Fill an svf_shape_t.  Strides come from `kv_strides` = (page, token, head) in elements, or
+    from a pool tensor laid out [page][slot][Hkv][d]."""
+    if kv_strides is None:
+        kv_strides = (k_pool.stride(0), k_pool.stride(1), k_pool.stride(2))
+    code = {torch.float32: SVF_F32, torch.bfloat16: SVF_BF16, "f32": SVF_F32, "bf16": SVF_BF16}.get(dtype, dtype)
+    return SvfShape(B, gamma, Hq, Hkv, d, code, block_size, page_size, max_pages_per_seq, max_seq_len,
+                    kv_strides[0], kv_strides[1], kv_strides[2], k_blocks, n_sink, n_local, mask_per_batch, sm_scale)
+
+
+def svf_workspace_bytes(shape: SvfShape) -> int:
+    return lib().svf_workspace_bytes(ctypes.byref(shape))
+
+
+def svf_workspace_init(ws: torch.Tensor):
+    _check(lib().svf_workspace_init(_ptr(ws), ws.numel() * ws.element_size(), _stream()), "svf_workspace_init")
+
+
+def new_workspace(shape: SvfShape, device="cuda") -> torch.Tensor:
+    """Allocate (through torch) and clear a workspace for `shape`."""
+    n = svf_workspace_bytes(shape)
+    if n == 0:
+        raise SvfError(-2, "svf_workspace_bytes")
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    svf_workspace_init(ws)
+    return ws
+
+
+def svf_block_reps(shape, K, block_table, seq_lens, reps, first_block=0, n_blocks=-1):
+    _check(lib().svf_block_reps(ctypes.byref(shape), _ptr(K), _ptr(block_table), _ptr(seq_lens),
+                                first_block, n_blocks, _ptr(reps), _stream()), "svf_block_reps")
+
+
+def svf_score_select(shape, q, reps, seq_lens, sel_idx, sel_cnt, ws, scores=None):
+    _check(lib().svf_score_select(ctypes.byref(shape), _ptr(q), _ptr(reps), _ptr(seq_lens), _ptr(sel_idx),
+                                  _ptr(sel_cnt), _ptr(scores), _ptr(ws), ws.numel(), _stream()),
+           "svf_score_select")
+
+
+def svf_verify_attn(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask, sel_idx, sel_cnt,
+                    out, ws, lse=None):
+    _check(lib().svf_verify_attn(ctypes.byref(shape), _ptr(q), _ptr(K), _ptr(V), _ptr(block_table),
+                                 _ptr(seq_lens), _ptr(k_draft), _ptr(v_draft), _ptr(draft_mask),
+                                 _ptr(sel_idx), _ptr(sel_cnt), _ptr(out), _ptr(lse), _ptr(ws), ws.numel(),
+                                 _stream()), "svf_verify_attn")
+
+
+def svf_verify_step(shape, do_select, q, reps, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask,
+                    sel_idx, sel_cnt, out, ws, lse=None):
+    _check(lib().svf_verify_step(ctypes.byref(shape), int(bool(do_select)), _ptr(q), _ptr(reps), _ptr(K), _ptr(V),
+                                 _ptr(block_table), _ptr(seq_lens), _ptr(k_draft), _ptr(v_draft),
+                                 _ptr(draft_mask), _ptr(sel_idx), _ptr(sel_cnt), _ptr(out), _ptr(lse),
+                                 _ptr(ws), ws.numel(), _stream()), "svf_verify_step")

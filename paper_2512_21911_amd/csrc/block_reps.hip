@@ -1,0 +1,126 @@
+// Block representatives: the mean key of every retrieval block (Sec. 3.1; block term of Eq. 5).
+//
+// HBM-bound streaming reduction: K is read exactly once with 16-byte loads, fp32 accumulation
+// in a fixed (logical-token) order, fp32 representatives written once.  One workgroup per
+// (sequence, block); a thread owns one 16-byte column chunk of one KV head and walks the
+// block's tokens with a stride of TOK_PAR tokens, TOK_PAR thread groups cover the tokens in
+// parallel and are combined through LDS in a fixed order, so the result does not depend on
+// the physical page order.
+#include <hip/hip_bf16.h>
+
+#include "svf_device.h"
+
+namespace svf {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+template <typename T>
+struct Vec16;
+template <>
+struct Vec16<float> {
+  static constexpr int N = 4;
+  __device__ static void load(const float* p, float (&v)[4]) {
+    const float4 x = *reinterpret_cast<const float4*>(p);
+    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+  }
+};
+template <>
+struct Vec16<__hip_bfloat16> {
+  static constexpr int N = 8;
+  __device__ static void load(const __hip_bfloat16* p, float (&v)[8]) {
+    const uint4 x = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(w[i] << 16);
+      v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
+
+// grid: (blocks in range, B, column groups); block: kThreads
+template <typename T>
+__global__ __launch_bounds__(kThreads) void block_reps_kernel(RepsParams p, int cols, int cpb, int tok_par) {
+  constexpr int N = Vec16<T>::N;
+  __shared__ float red[kThreads * N];
+
+  const int b = blockIdx.y;
+  const int j = p.first_block + blockIdx.x;
+  const int L = clamped_len(p.seq_lens, b, p.max_seq_len);
+  const int t0 = j * p.block_size;
+  if (t0 >= L) return;                                  // block does not exist in this sequence
+  const int n_tok = min(p.block_size, L - t0);
+
+  const int tid = threadIdx.x;
+  const int tl = tid / cpb;                             // token lane
+  const int col = blockIdx.z * cpb + (tid - tl * cpb);  // 16-byte column chunk over (head, channel)
+  const bool active = tl < tok_par && col < cols;
+  const int chunks_per_head = p.d / N;
+  const int h = col / chunks_per_head;
+  const int c = (col - h * chunks_per_head) * N;
+
+  float acc[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) acc[i] = 0.f;
+
+  if (active) {
+    const T* K = static_cast<const T*>(p.K) + (int64_t)h * p.kv.stride_head + c;
+    int t = tl;
+    // four independent loads in flight per iteration
+    for (; t + 3 * tok_par < n_tok; t += 4 * tok_par) {
+      float v[4][N];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        Vec16<T>::load(K + token_offset(p.kv, p.table, b, t0 + t + u * tok_par), v[u]);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] += v[u][i];
+    }
+    for (; t < n_tok; t += tok_par) {
+      float v[N];
+      Vec16<T>::load(K + token_offset(p.kv, p.table, b, t0 + t), v);
+#pragma unroll
+      for (int i = 0; i < N; ++i) acc[i] += v[i];
+    }
+  }
+
+  if (tok_par > 1) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) red[tid * N + i] = acc[i];
+    __syncthreads();
+    if (active && tl == 0) {
+      for (int u = 1; u < tok_par; ++u)
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] += red[(u * cpb + tid) * N + i];
+    }
+  }
+  if (active && tl == 0) {
+    const float inv = 1.0f / (float)n_tok;
+    float* r = p.reps + (((int64_t)b * p.Hkv + h) * p.nb_max + j) * p.d + c;
+#pragma unroll
+    for (int i = 0; i < N; i += 4)
+      *reinterpret_cast<float4*>(r + i) =
+          make_float4(acc[i] * inv, acc[i + 1] * inv, acc[i + 2] * inv, acc[i + 3] * inv);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_block_reps(const RepsParams& p, int dtype, int B, hipStream_t st) {
+  if (p.n_blocks <= 0) return hipSuccess;
+  const int N = dtype == SVF_F32 ? 4 : 8;
+  const int cols = p.Hkv * p.d / N;
+  const int cpb = cols < kThreads ? cols : kThreads;
+  const int tok_par = kThreads / cpb;
+  dim3 grid(p.n_blocks, B, (cols + cpb - 1) / cpb);
+  if (dtype == SVF_F32)
+    hipLaunchKernelGGL(block_reps_kernel<float>, grid, dim3(kThreads), 0, st, p, cols, cpb, tok_par);
+  else
+    hipLaunchKernelGGL(block_reps_kernel<__hip_bfloat16>, grid, dim3(kThreads), 0, st, p, cols, cpb, tok_par);
+  return hipGetLastError();
+}
+
+}  // namespace svf

@@ -1,0 +1,183 @@
+// Block scores and the shared top-N block set (Sec. 3.1, Eq. 5 and the selection rule;
+// Sec. 2.2: the first draft token's query retrieves for every draft token).
+//
+// Two kernels.
+//   scores:  wide, HBM-bound pass over the fp32 representatives.  A group of d/4 lanes owns
+//            one block: float4 loads, fp32 dot with the group-mean first-draft query,
+//            butterfly reduction inside the lane group.
+//   select:  one workgroup per (sequence, KV head).  Scores become order-preserving 32-bit
+//            keys (forced sink/local blocks get the maximum key); a 4-pass radix select over
+//            LDS histograms finds the key of the weakest kept block, and a final ascending
+//            sweep keeps every block above it plus the lowest-indexed blocks equal to it,
+//            using wavefront ballots for the ordered compaction.  Output is ascending.
+#include <hip/hip_bf16.h>
+
+#include "svf_device.h"
+
+namespace svf {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int kPasses = 4;              // blocks scored per lane group in the scores kernel
+
+template <typename T>
+__device__ __forceinline__ float to_float(T x);
+template <>
+__device__ __forceinline__ float to_float<float>(float x) { return x; }
+template <>
+__device__ __forceinline__ float to_float<__hip_bfloat16>(__hip_bfloat16 x) { return __bfloat162float(x); }
+
+// grid: (ceil(nb_max / (kPasses * blocks per pass)), Hkv, B)
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void block_scores_kernel(SelectParams p) {
+  constexpr int LPB = D / 4;                 // lanes per block
+  constexpr int BPW = kThreads / LPB;        // blocks per workgroup pass
+  __shared__ float q0[D];
+
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int G = p.Hq / p.Hkv;
+  const int L = clamped_len(p.seq_lens, b, p.max_seq_len);
+  const int nb = (L + p.block_size - 1) / p.block_size;
+
+  // first draft token's query, averaged over the query heads of this KV head
+  if (threadIdx.x < D) {
+    const T* q = static_cast<const T*>(p.q) + ((int64_t)b * p.gamma * p.Hq + (int64_t)h * G) * D + threadIdx.x;
+    float s = 0.f;
+    for (int g = 0; g < G; ++g) s += to_float<T>(q[(int64_t)g * D]);
+    q0[threadIdx.x] = s / (float)G;
+  }
+  __syncthreads();
+
+  const int sub = threadIdx.x % LPB;
+  const float4 qv = make_float4(q0[sub * 4], q0[sub * 4 + 1], q0[sub * 4 + 2], q0[sub * 4 + 3]);
+  float dot[kPasses];
+  int jj[kPasses];
+#pragma unroll
+  for (int u = 0; u < kPasses; ++u) {
+    const int j = (blockIdx.x * kPasses + u) * BPW + threadIdx.x / LPB;
+    jj[u] = j;
+    dot[u] = 0.f;
+    if (j < nb) {
+      const float4 r = *reinterpret_cast<const float4*>(
+          p.reps + (((int64_t)b * p.Hkv + h) * p.nb_max + j) * D + sub * 4);
+      dot[u] = r.x * qv.x + r.y * qv.y + r.z * qv.z + r.w * qv.w;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kPasses; ++u) {
+    float v = dot[u];
+#pragma unroll
+    for (int o = LPB / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    if (sub == 0 && jj[u] < p.nb_max)
+      p.scores[((int64_t)b * p.Hkv + h) * p.nb_max + jj[u]] = jj[u] < nb ? v + 0.0f : 0.0f;
+  }
+}
+
+// Larger score <=> larger key; -0 and +0 map to the same key.
+__device__ __forceinline__ uint32_t score_key(float s) {
+  uint32_t u = __float_as_uint(s + 0.0f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// grid: (Hkv, B)
+__global__ __launch_bounds__(kThreads) void select_kernel(SelectParams p) {
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t sh_prefix, sh_need;
+  __shared__ uint32_t wave_eq[kWaves], wave_sel[kWaves];
+  __shared__ uint32_t base_eq, base_sel;
+
+  const int b = blockIdx.y, h = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int L = clamped_len(p.seq_lens, b, p.max_seq_len);
+  const int nb = (L + p.block_size - 1) / p.block_size;
+  const int cnt = min(p.k_blocks, nb);
+  const float* sc = p.scores + ((int64_t)b * p.Hkv + h) * p.nb_max;
+  int32_t* out = p.sel_idx + ((int64_t)b * p.Hkv + h) * p.k_blocks;
+
+  auto key_of = [&](int j) -> uint32_t {
+    if (j < p.n_sink || j >= nb - p.n_local) return 0xffffffffu;
+    return score_key(sc[j]);
+  };
+
+  // radix select: key of the cnt-th largest element
+  if (tid == 0) { sh_prefix = 0; sh_need = (uint32_t)cnt; }
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    hist[tid] = 0;
+    __syncthreads();
+    const uint32_t prefix = sh_prefix;
+    const uint32_t hi_mask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
+    for (int j = tid; j < nb; j += kThreads) {
+      const uint32_t k = key_of(j);
+      if ((k & hi_mask) == prefix) atomicAdd(&hist[(k >> shift) & 0xff], 1u);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      uint32_t need = sh_need, cum = 0;
+      int bin = 255;
+      for (; bin > 0; --bin) {
+        if (cum + hist[bin] >= need) break;
+        cum += hist[bin];
+      }
+      sh_need = need - cum;                 // how many are still wanted from inside this bin
+      sh_prefix = prefix | ((uint32_t)bin << shift);
+    }
+    __syncthreads();
+  }
+  const uint32_t tau = sh_prefix;           // key of the weakest kept block
+  const uint32_t need_eq = sh_need;         // blocks equal to tau that are kept (lowest ids first)
+
+  if (tid == 0) { base_eq = 0; base_sel = 0; }
+  __syncthreads();
+  for (int j0 = 0; j0 < nb; j0 += kThreads) {
+    const int j = j0 + tid;
+    const uint32_t k = j < nb ? key_of(j) : 0u;
+    const bool is_eq = j < nb && k == tau;
+    const bool is_gt = j < nb && k > tau;
+    const uint64_t m_eq = __ballot(is_eq);
+    if (lane == 0) wave_eq[wave] = (uint32_t)__popcll(m_eq);
+    __syncthreads();
+    uint32_t eq_rank = base_eq + (uint32_t)__popcll(m_eq & ((1ull << lane) - 1ull));
+    for (int w = 0; w < wave; ++w) eq_rank += wave_eq[w];
+    const bool keep = is_gt || (is_eq && eq_rank < need_eq);
+    const uint64_t m_sel = __ballot(keep);
+    if (lane == 0) wave_sel[wave] = (uint32_t)__popcll(m_sel);
+    __syncthreads();
+    uint32_t pos = base_sel + (uint32_t)__popcll(m_sel & ((1ull << lane) - 1ull));
+    for (int w = 0; w < wave; ++w) pos += wave_sel[w];
+    if (keep) out[pos] = j;
+    __syncthreads();
+    if (tid == 0) {
+      uint32_t e = 0, s = 0;
+      for (int w = 0; w < kWaves; ++w) { e += wave_eq[w]; s += wave_sel[w]; }
+      base_eq += e;
+      base_sel += s;
+    }
+    __syncthreads();
+  }
+  for (int i = cnt + tid; i < p.k_blocks; i += kThreads) out[i] = -1;
+  if (tid == 0) p.sel_cnt[(int64_t)b * p.Hkv + h] = cnt;
+}
+
+}  // namespace
+
+hipError_t launch_score_select(const SelectParams& p, int dtype, hipStream_t st) {
+  const int lpb = p.d / 4;
+  const int bpw = kPasses * (kThreads / lpb);
+  dim3 g1((p.nb_max + bpw - 1) / bpw, p.Hkv, p.B);
+  if (dtype == SVF_F32) {
+    if (p.d == 64) hipLaunchKernelGGL((block_scores_kernel<float, 64>), g1, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((block_scores_kernel<float, 128>), g1, dim3(kThreads), 0, st, p);
+  } else {
+    if (p.d == 64) hipLaunchKernelGGL((block_scores_kernel<__hip_bfloat16, 64>), g1, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((block_scores_kernel<__hip_bfloat16, 128>), g1, dim3(kThreads), 0, st, p);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(select_kernel, dim3(p.Hkv, p.B), dim3(kThreads), 0, st, p);
+  return hipGetLastError();
+}
+
+}  // namespace svf

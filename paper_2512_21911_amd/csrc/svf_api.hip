@@ -1,0 +1,314 @@
+// C ABI of libsvf: argument validation, workspace planning, kernel dispatch.
+// Every check runs before the first launch; on error nothing has been enqueued.
+#include <math.h>
+#include <string.h>
+
+#include "svf_device.h"
+
+namespace svf {
+
+hipError_t launch_verify_attn_valu(const AttnParams& p, int dtype, hipStream_t st);
+hipError_t launch_verify_attn_mfma(const AttnParams& p, hipStream_t st);
+bool mfma_supported(const svf_shape_t& s);
+int mfma_splits(const svf_shape_t& s);
+
+namespace {
+
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+int elem_bytes(int dtype) { return dtype == SVF_F32 ? 4 : 2; }
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int check_shape(const svf_shape_t* s) {
+  if (!s) return SVF_ERR_NULL;
+  if (s->dtype != SVF_F32 && s->dtype != SVF_BF16) return SVF_ERR_DTYPE;
+  if (s->B < 1 || s->gamma < 1 || s->gamma > 64 || s->Hq < 1 || s->Hkv < 1 || s->Hq % s->Hkv != 0)
+    return SVF_ERR_SHAPE;
+  if (s->d != 64 && s->d != 128) return SVF_ERR_SHAPE;
+  if (s->block_size < 1 || s->max_seq_len < 1 || s->page_size < 0) return SVF_ERR_SHAPE;
+  const int vec = 16 / elem_bytes(s->dtype);
+  if (s->kv_stride_tok < s->d || s->kv_stride_head < s->d || s->kv_stride_page < s->d) return SVF_ERR_SHAPE;
+  if (s->kv_stride_tok % vec || s->kv_stride_head % vec || s->kv_stride_page % vec) return SVF_ERR_SHAPE;
+  if (s->page_size > 0) {
+    if (s->block_size % s->page_size != 0 && s->page_size % s->block_size != 0) return SVF_ERR_PAGING;
+    if (s->max_pages_per_seq < 1 ||
+        (int64_t)s->max_pages_per_seq * s->page_size < (int64_t)s->max_seq_len) return SVF_ERR_PAGING;
+  }
+  if (s->k_blocks < 1 || s->n_sink < 0 || s->n_local < 0 ||
+      (int64_t)s->n_sink + s->n_local > s->k_blocks) return SVF_ERR_BUDGET;
+  if ((int64_t)s->k_blocks * s->block_size > (int64_t)1 << 30) return SVF_ERR_BUDGET;
+  return SVF_OK;
+}
+
+int nb_max_of(const svf_shape_t& s) { return (s.max_seq_len + s.block_size - 1) / s.block_size; }
+
+KvLayout layout_of(const svf_shape_t& s) {
+  KvLayout kv;
+  kv.stride_page = s.kv_stride_page;
+  kv.stride_tok = s.kv_stride_tok;
+  kv.stride_head = s.kv_stride_head;
+  kv.page_size = s.page_size;
+  kv.page_shift = -1;
+  if (s.page_size > 0 && (s.page_size & (s.page_size - 1)) == 0) {
+    int sh = 0;
+    while ((1 << sh) < s.page_size) ++sh;
+    kv.page_shift = sh;
+  }
+  kv.max_pages = s.max_pages_per_seq;
+  return kv;
+}
+
+size_t scores_bytes(const svf_shape_t& s) {
+  return align_up((size_t)s.B * s.Hkv * nb_max_of(s) * sizeof(float));
+}
+
+int check_ws(const svf_shape_t* s, const void* ws, size_t ws_bytes) {
+  if (!ws) return SVF_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) % kAlign) return SVF_ERR_WORKSPACE;
+  if (ws_bytes < svf_workspace_bytes(s)) return SVF_ERR_WORKSPACE;
+  return SVF_OK;
+}
+
+int hip_code(hipError_t e) { return e == hipSuccess ? SVF_OK : SVF_ERR_HIP; }
+
+}  // namespace
+
+// Workspace layout: [tickets | partial o | partial m | partial l | scores]
+AttnPlan plan_attn(const svf_shape_t& s) {
+  AttnPlan pl;
+  const int G = s.Hq / s.Hkv;
+  pl.M = s.gamma * G;
+  pl.Mpad = (pl.M + 31) / 32 * 32;
+  pl.mfma = mfma_supported(s);
+  if (pl.mfma) {
+    pl.n_splits = mfma_splits(s);
+  } else {
+    const int64_t tiles = ((int64_t)s.k_blocks * s.block_size + 31) / 32 + (s.gamma + 31) / 32;
+    const int64_t groups = (int64_t)s.B * s.Hkv * (pl.Mpad / 32);
+    int64_t want = (512 + groups - 1) / groups;          // aim at ~2 workgroups per compute unit
+    if (want > tiles) want = tiles;
+    if (want < 1) want = 1;
+    pl.n_splits = (int)want;
+  }
+  const size_t pairs = (size_t)s.B * s.Hkv;
+  size_t off = 0;
+  pl.off_tickets = off;
+  off += align_up(pairs * sizeof(uint32_t));
+  pl.off_o = off;
+  off += align_up(pairs * pl.n_splits * pl.Mpad * s.d * sizeof(float));
+  pl.off_m = off;
+  off += align_up(pairs * pl.n_splits * pl.Mpad * sizeof(float));
+  pl.off_l = off;
+  off += align_up(pairs * pl.n_splits * pl.Mpad * sizeof(float));
+  pl.bytes = off;
+  return pl;
+}
+
+namespace {
+
+__global__ void fill_zero_kernel(uint4* p, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+    p[i] = make_uint4(0, 0, 0, 0);
+}
+
+}  // namespace
+
+hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st) {
+  const size_t n16 = bytes / 16;
+  if (n16 == 0) return hipSuccess;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<uint4*>(ptr), n16);
+  return hipGetLastError();
+}
+
+}  // namespace svf
+
+using namespace svf;
+
+extern "C" {
+
+int svf_version(void) { return 100; }
+
+const char* svf_strerror(int code) {
+  switch (code) {
+    case SVF_OK: return "success";
+    case SVF_ERR_NULL: return "a required pointer is NULL";
+    case SVF_ERR_SHAPE: return "shape, stride or alignment out of range";
+    case SVF_ERR_DTYPE: return "unsupported dtype";
+    case SVF_ERR_PAGING: return "page size / block size / page table mismatch";
+    case SVF_ERR_BUDGET: return "invalid block budget";
+    case SVF_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SVF_ERR_HIP: return "HIP launch failed";
+    default: return "unknown error code";
+  }
+}
+
+int32_t svf_budget_blocks(int64_t L, int64_t L0, double rho, int32_t block_size, int32_t* dense) {
+  if (L < 1 || L0 < 0 || block_size < 1 || !(rho > 0.0 && rho < 1.0)) return SVF_ERR_SHAPE;
+  const int64_t nb = (L + block_size - 1) / block_size;
+  if (nb > INT32_MAX) return SVF_ERR_SHAPE;
+  if (L <= L0) {
+    if (dense) *dense = 1;
+    return (int32_t)nb;
+  }
+  if (dense) *dense = 0;
+  const double kept_tokens = (double)(L - L0) * rho + (double)L0;
+  int64_t k = (int64_t)ceil(kept_tokens / (double)block_size - 1e-12);
+  if (k < 1) k = 1;
+  if (k > nb) k = nb;
+  return (int32_t)k;
+}
+
+size_t svf_workspace_bytes(const svf_shape_t* shape) {
+  if (check_shape(shape) != SVF_OK) return 0;
+  return plan_attn(*shape).bytes + scores_bytes(*shape);
+}
+
+int svf_workspace_init(void* ws, size_t ws_bytes, void* stream) {
+  if (!ws) return SVF_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(ws) % kAlign || ws_bytes % 16) return SVF_ERR_WORKSPACE;
+  return hip_code(launch_fill_zero(ws, ws_bytes, static_cast<hipStream_t>(stream)));
+}
+
+int svf_block_reps(const svf_shape_t* shape, const void* K, const int32_t* block_table,
+                   const int32_t* seq_lens, int32_t first_block, int32_t n_blocks, float* reps,
+                   void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!K || !seq_lens || !reps || (shape->page_size > 0 && !block_table)) return SVF_ERR_NULL;
+  if (misaligned(K) || misaligned(reps)) return SVF_ERR_SHAPE;
+  const int nb_max = nb_max_of(*shape);
+  if (first_block < 0 || first_block > nb_max || n_blocks < -1) return SVF_ERR_SHAPE;
+  if (n_blocks == -1 || first_block + (int64_t)n_blocks > nb_max) n_blocks = nb_max - first_block;
+  RepsParams p;
+  p.kv = layout_of(*shape);
+  p.K = K;
+  p.table = block_table;
+  p.seq_lens = seq_lens;
+  p.reps = reps;
+  p.Hkv = shape->Hkv;
+  p.d = shape->d;
+  p.block_size = shape->block_size;
+  p.nb_max = nb_max;
+  p.first_block = first_block;
+  p.max_seq_len = shape->max_seq_len;
+  p.n_blocks = n_blocks;
+  return hip_code(launch_block_reps(p, shape->dtype, shape->B, static_cast<hipStream_t>(stream)));
+}
+
+int svf_score_select(const svf_shape_t* shape, const void* q, const float* reps,
+                     const int32_t* seq_lens, int32_t* sel_idx, int32_t* sel_cnt,
+                     float* scores_or_null, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!q || !reps || !seq_lens || !sel_idx || !sel_cnt) return SVF_ERR_NULL;
+  if (misaligned(q) || misaligned(reps)) return SVF_ERR_SHAPE;
+  rc = check_ws(shape, ws, ws_bytes);
+  if (rc) return rc;
+  SelectParams p;
+  p.q = q;
+  p.reps = reps;
+  p.seq_lens = seq_lens;
+  p.scores = scores_or_null ? scores_or_null
+                            : reinterpret_cast<float*>(static_cast<char*>(ws) + plan_attn(*shape).bytes);
+  p.sel_idx = sel_idx;
+  p.sel_cnt = sel_cnt;
+  p.B = shape->B;
+  p.gamma = shape->gamma;
+  p.Hq = shape->Hq;
+  p.Hkv = shape->Hkv;
+  p.d = shape->d;
+  p.block_size = shape->block_size;
+  p.nb_max = nb_max_of(*shape);
+  p.k_blocks = shape->k_blocks;
+  p.n_sink = shape->n_sink;
+  p.n_local = shape->n_local;
+  p.max_seq_len = shape->max_seq_len;
+  return hip_code(launch_score_select(p, shape->dtype, static_cast<hipStream_t>(stream)));
+}
+
+int svf_verify_attn(const svf_shape_t* shape, const void* q, const void* K, const void* V,
+                    const int32_t* block_table, const int32_t* seq_lens, const void* k_draft,
+                    const void* v_draft, const uint64_t* draft_mask_or_null, const int32_t* sel_idx,
+                    const int32_t* sel_cnt, void* out, float* lse_or_null, void* ws, size_t ws_bytes,
+                    void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!q || !K || !V || !seq_lens || !k_draft || !v_draft || !sel_idx || !sel_cnt || !out ||
+      (shape->page_size > 0 && !block_table))
+    return SVF_ERR_NULL;
+  if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(k_draft) || misaligned(v_draft) ||
+      misaligned(out))
+    return SVF_ERR_SHAPE;
+  rc = check_ws(shape, ws, ws_bytes);
+  if (rc) return rc;
+  const AttnPlan pl = plan_attn(*shape);
+  char* w = static_cast<char*>(ws);
+  AttnParams p;
+  p.kv = layout_of(*shape);
+  p.q = q;
+  p.K = K;
+  p.V = V;
+  p.table = block_table;
+  p.seq_lens = seq_lens;
+  p.k_draft = k_draft;
+  p.v_draft = v_draft;
+  p.draft_mask = draft_mask_or_null;
+  p.sel_idx = sel_idx;
+  p.sel_cnt = sel_cnt;
+  p.out = out;
+  p.lse = lse_or_null;
+  p.tickets = reinterpret_cast<uint32_t*>(w + pl.off_tickets);
+  p.part_o = reinterpret_cast<float*>(w + pl.off_o);
+  p.part_m = reinterpret_cast<float*>(w + pl.off_m);
+  p.part_l = reinterpret_cast<float*>(w + pl.off_l);
+  p.B = shape->B;
+  p.gamma = shape->gamma;
+  p.Hq = shape->Hq;
+  p.Hkv = shape->Hkv;
+  p.G = shape->Hq / shape->Hkv;
+  p.d = shape->d;
+  p.M = pl.M;
+  p.Mpad = pl.Mpad;
+  p.block_size = shape->block_size;
+  p.k_blocks = shape->k_blocks;
+  p.n_splits = pl.n_splits;
+  p.mask_per_batch = shape->mask_per_batch;
+  p.max_seq_len = shape->max_seq_len;
+  const float scale = shape->sm_scale > 0.f ? shape->sm_scale : 1.0f / sqrtf((float)shape->d);
+  p.scale_log2 = scale * 1.4426950408889634f;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (pl.mfma) return hip_code(launch_verify_attn_mfma(p, st));
+  return hip_code(launch_verify_attn_valu(p, shape->dtype, st));
+}
+
+int svf_verify_step(const svf_shape_t* shape, int do_select, const void* q, const float* reps,
+                    const void* K, const void* V, const int32_t* block_table, const int32_t* seq_lens,
+                    const void* k_draft, const void* v_draft, const uint64_t* draft_mask_or_null,
+                    int32_t* sel_idx, int32_t* sel_cnt, void* out, float* lse_or_null, void* ws,
+                    size_t ws_bytes, void* stream) {
+  // validate everything both halves need before enqueuing the first one
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!q || !K || !V || !seq_lens || !k_draft || !v_draft || !sel_idx || !sel_cnt || !out ||
+      (shape->page_size > 0 && !block_table) || (do_select && !reps))
+    return SVF_ERR_NULL;
+  if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(k_draft) || misaligned(v_draft) ||
+      misaligned(out) || (do_select && misaligned(reps)))
+    return SVF_ERR_SHAPE;
+  rc = check_ws(shape, ws, ws_bytes);
+  if (rc) return rc;
+  if (do_select) {
+    rc = svf_score_select(shape, q, reps, seq_lens, sel_idx, sel_cnt, nullptr, ws, ws_bytes, stream);
+    if (rc) return rc;
+  }
+  return svf_verify_attn(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask_or_null,
+                         sel_idx, sel_cnt, out, lse_or_null, ws, ws_bytes, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,106 @@
+"""CPU-side checks of the C ABI: the library loads, exports every declared symbol, and rejects bad
+arguments before touching the GPU (none of these calls launches anything)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2512_21911_amd as S
+from oracle import svf_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "svf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(svf_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = S.lib()
+    names = declared_symbols()
+    assert {"svf_block_reps", "svf_score_select", "svf_verify_attn", "svf_verify_step"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def good_shape(**kw):
+    base = dict(B=2, gamma=4, Hq=8, Hkv=2, d=128, dtype="bf16", block_size=64, max_seq_len=1024, k_blocks=4,
+                page_size=16, max_pages_per_seq=64, kv_strides=(16 * 2 * 128, 2 * 128, 128))
+    base.update(kw)
+    return S.make_shape(**base)
+
+
+def test_version_and_strerror():
+    assert S.svf_version() >= 100
+    for code in range(0, -8, -1):
+        assert S.strerror(code) and "unknown" not in S.strerror(code)
+    assert "unknown" in S.strerror(-99)
+
+
+def test_budget_blocks_host_helper():
+    assert S.svf_budget_blocks(32768, 4096, 0.1, 64) == O.budget_blocks(32768, 4096, 0.1, 64)
+    assert S.svf_budget_blocks(4096, 4096, 0.1, 64) == (64, True)
+    assert S.svf_budget_blocks(100000, 1024, 0.1, 16) == O.budget_blocks(100000, 1024, 0.1, 16)
+    for bad in [(0, 10, 0.1, 16), (10, -1, 0.1, 16), (10, 5, 0.0, 16), (10, 5, 1.0, 16), (10, 5, 0.1, 0)]:
+        with pytest.raises(S.SvfError):
+            S.svf_budget_blocks(*bad)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(dtype=7), -3),
+    (dict(gamma=0), -2), (dict(gamma=65), -2), (dict(Hq=7), -2), (dict(d=96), -2), (dict(block_size=0), -2),
+    (dict(kv_strides=(4096, 100, 128)), -2), (dict(kv_strides=(4096, 256, 64)), -2),
+    (dict(page_size=48), -4), (dict(max_pages_per_seq=8), -4),
+    (dict(k_blocks=0), -5), (dict(n_sink=3, n_local=2), -5),
+])
+def test_shape_validation(kw, code):
+    sh = good_shape(**kw)
+    assert S.svf_workspace_bytes(sh) == 0
+    fake = ctypes.c_void_p(0x1000)
+    rc = S.lib().svf_block_reps(ctypes.byref(sh), fake, fake, fake, 0, -1, fake, None)
+    assert rc == code
+    rc = S.lib().svf_verify_attn(ctypes.byref(sh), *([fake] * 13), 1 << 30, None)
+    assert rc == code
+
+
+def test_null_alignment_and_workspace_checks():
+    sh = good_shape()
+    need = S.svf_workspace_bytes(sh)
+    assert need > 0 and need % 256 == 0
+    L = S.lib()
+    ok, null = ctypes.c_void_p(0x10000), None
+    assert L.svf_block_reps(ctypes.byref(sh), null, ok, ok, 0, -1, ok, None) == -1
+    assert L.svf_block_reps(ctypes.byref(sh), ok, null, ok, 0, -1, ok, None) == -1          # paged needs a table
+    assert L.svf_block_reps(ctypes.byref(sh), ctypes.c_void_p(0x10004), ok, ok, 0, -1, ok, None) == -2
+    assert L.svf_block_reps(ctypes.byref(sh), ok, ok, ok, -1, -1, ok, None) == -2
+    assert L.svf_block_reps(None, ok, ok, ok, 0, -1, ok, None) == -1
+    args = [ok] * 13
+    assert L.svf_verify_attn(ctypes.byref(sh), *args, need - 1, None) == -6
+    args[12] = null
+    assert L.svf_verify_attn(ctypes.byref(sh), *args, need, None) == -6
+    args[12] = ctypes.c_void_p(0x10010)
+    assert L.svf_verify_attn(ctypes.byref(sh), *args, need, None) == -6                     # misaligned workspace
+    args = [ok] * 13
+    args[7] = null                                                                           # draft mask may be NULL...
+    args[11] = null                                                                          # ...and so may lse
+    args[0] = null                                                                           # but q may not
+    assert L.svf_verify_attn(ctypes.byref(sh), *args, need, None) == -1
+    sargs = [ok] * 14
+    sargs[1] = null                                                                          # reps required when selecting
+    assert L.svf_verify_step(ctypes.byref(sh), 1, *sargs, need, None) == -1
+    assert L.svf_score_select(ctypes.byref(sh), ok, ok, ok, ok, ok, null, ok, need - 256, None) == -6
+    assert L.svf_workspace_init(null, 256, None) == -1
+    assert L.svf_workspace_init(ctypes.c_void_p(0x10010), 256, None) == -6
+
+
+def test_contiguous_cache_needs_no_table():
+    sh = good_shape(page_size=0, max_pages_per_seq=0, kv_strides=(1024 * 256, 256, 128))
+    assert S.svf_workspace_bytes(sh) > 0
+    # argument checks pass up to the (undersized) workspace: no table required
+    ok = ctypes.c_void_p(0x10000)
+    args = [ok] * 13
+    args[3] = None
+    assert S.lib().svf_verify_attn(ctypes.byref(sh), *args, 0, None) == -6

@@ -1,0 +1,253 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Selected block ids are bit-exact apart from counted near-ties (relative score gap 1e-3);
+outputs within max-abs 2e-2 (bf16) / 1e-4 (fp32); representatives within 1e-5."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_21911_amd as S
+import workloads as W
+from oracle import svf_oracle as O
+from svf_harness import (GpuRun, check_attn, check_reps, check_selection, full_parity, oracle_attn, shape_for,
+                         to_gpu)
+
+pytestmark = pytest.mark.gpu
+
+
+def report(name, r):
+    print(f"[parity] {name}: max_abs_err={r['max_abs_err']:.3e} near_ties={r['near_ties']}", flush=True)
+
+
+# ------------------------------------------------------------------ the five configurations
+
+def test_cfg1_tiny_fp32():
+    r = full_parity(W.CONFIGS[1])
+    report("cfg1", r)
+    x, run = r["x"], r["run"]
+    idx = run.sel_idx.cpu().numpy()
+    for h in range(2):
+        assert set(x["planted"][0][h].tolist()) <= set(idx[0, h].tolist())
+    assert r["near_ties"] == 0
+
+
+def test_cfg2_llama8b_bf16():
+    r = full_parity(W.CONFIGS[2])
+    report("cfg2", r)
+    idx = r["run"].sel_idx.cpu().numpy()
+    for h in range(8):
+        assert set(r["x"]["planted"][0][h].tolist()) <= set(idx[0, h].tolist())
+
+
+@pytest.mark.parametrize("cfg_id,T", [(3, 4096), (4, 16384), (5, 8192)])
+def test_shrunk_paged_configs(cfg_id, T):
+    cfg = W.shrink(W.CONFIGS[cfg_id], T)
+    r = full_parity(cfg)
+    report(f"cfg{cfg_id}@T={T}", r)
+
+
+@pytest.mark.parametrize("cfg_id", [3, 4, 5])
+def test_full_size_configs(cfg_id):
+    """One layer at the benchmark's full shape, in the launch configuration the bench times."""
+    cfg = W.CONFIGS[cfg_id]
+    r = full_parity(cfg)
+    report(f"cfg{cfg_id} full", r)
+    if cfg_id == 4:   # more planted blocks than budget: everything kept must be planted
+        idx = r["run"].sel_idx.cpu().numpy()
+        for h in range(cfg.Hkv):
+            assert set(idx[0, h].tolist()) <= set(r["x"]["planted"][0][h].tolist())
+
+
+def test_cfg3_reuse_layer_matches_anchor_blocks():
+    """Eq. 9: the non-anchor layer attends with the anchor's block set."""
+    cfg = W.shrink(W.CONFIGS[3], 4096)
+    x0 = W.make_layer(cfg, 0)
+    x1 = W.make_layer(cfg, 1)
+    run0 = GpuRun(cfg, to_gpu(x0))
+    run0.block_reps().verify_step(True).sync()
+    idx0, cnt0 = run0.sel_idx.clone(), run0.sel_cnt.clone()
+    run1 = GpuRun(cfg, to_gpu(x1))
+    run1.sel_idx.copy_(idx0)
+    run1.sel_cnt.copy_(cnt0)
+    run1.verify_step(False).sync()
+    assert torch.equal(run1.sel_idx, idx0)
+    ref, lse = oracle_attn(cfg, x1, idx0.cpu(), cnt0.cpu())
+    check_attn(cfg, run1.out, run1.lse, ref, lse)
+    # and it is bit-identical to svf_verify_attn with the same indices
+    out_step = run1.out.clone()
+    run1.out.fill_(float("nan"))
+    run1.verify_attn().sync()
+    assert torch.equal(out_step.view(torch.int16), run1.out.view(torch.int16))
+
+
+# ------------------------------------------------------------------ edge cases
+
+def small(dtype="bf16", **kw):
+    base = dict(name="edge", cfg_id=9, dtype=dtype, B=2, Hq=8, Hkv=2, d=128, T=1024, block_size=64, gamma=4,
+                k_blocks=4, page_size=16, planted=2, shift=1.5)
+    base.update(kw)
+    return W.VerifyConfig(**base)
+
+
+EDGE = {
+    "ragged_lengths": small(min_len=100),
+    "dense_budget": small(k_blocks=16),
+    "budget_above_blocks": small(k_blocks=40, min_len=300),
+    "gamma1_decode": small(gamma=1),
+    "gamma64_chain": small(gamma=64, B=1),
+    "tree16": small(gamma=16, tree_depth=4),
+    "sink_local": small(n_sink=1, n_local=2, k_blocks=5, min_len=500),
+    "block16_page64": small(block_size=16, page_size=64, k_blocks=12),
+    "block48_contig": small(block_size=48, page_size=0, T=1000, min_len=700, k_blocks=5),
+    "block128_page16": small(block_size=128, page_size=16, k_blocks=3),
+    "d64_bf16": small(d=64),
+    "f32_d128": small(dtype="f32"),
+    "f32_d64_paged": small(dtype="f32", d=64, min_len=64),
+    "gqa8": small(Hq=16, Hkv=2, gamma=6),
+    "mha": small(Hq=4, Hkv=4, gamma=3),
+    "short_seq": small(T=40, page_size=8, block_size=16, k_blocks=2),
+}
+
+
+@pytest.mark.parametrize("name", sorted(EDGE))
+def test_edge_case(name):
+    r = full_parity(EDGE[name])
+    report(name, r)
+
+
+def test_hnd_strides_and_scale():
+    """Head-major pages ([page][Hkv][slot][d]) through the stride fields, and an explicit softmax scale."""
+    cfg = small(min_len=400)
+    x = W.make_layer(cfg)
+    xg = to_gpu(x)
+    for key in ("k_pool", "v_pool"):
+        hnd = xg[key].permute(0, 2, 1, 3).contiguous()          # storage [page][Hkv][slot][d]
+        xg[key + "_store"] = hnd
+        xg[key] = hnd.permute(0, 2, 1, 3)                        # logical view, strides carry the layout
+    shape = shape_for(cfg, xg, sm_scale=0.05)
+    assert shape.kv_stride_head == cfg.page_size * cfg.d and shape.kv_stride_tok == cfg.d
+    run = GpuRun(cfg, xg, shape)
+    run.block_reps().score_select().verify_attn().sync()
+    ref = check_reps(cfg, x, run.reps)
+    check_selection(cfg, x, O.block_scores(x["q"], ref), run.sel_idx, run.sel_cnt)
+    out_ref, lse_ref = oracle_attn(cfg, x, run.sel_idx.cpu(), run.sel_cnt.cpu(), sm_scale=0.05)
+    check_attn(cfg, run.out, run.lse, out_ref, lse_ref)
+
+
+def test_per_batch_masks_and_null_mask():
+    cfg = small(gamma=5)
+    x = W.make_layer(cfg)
+    xg = to_gpu(x)
+    masks = torch.tensor([[1, 3, 5, 9, 19], [1, 3, 7, 15, 31]], dtype=torch.int64)
+    run = GpuRun(cfg, xg, shape_for(cfg, xg, mask_per_batch=1))
+    run.block_reps().score_select().verify_attn(mask=masks.cuda()).sync()
+    ref, lse = oracle_attn(cfg, x, run.sel_idx.cpu(), run.sel_cnt.cpu(), mask=masks)
+    check_attn(cfg, run.out, run.lse, ref, lse)
+    run2 = GpuRun(cfg, xg)
+    run2.block_reps().score_select().verify_attn(mask=None).sync()     # NULL mask = linear causal
+    ref2, lse2 = oracle_attn(cfg, x, run2.sel_idx.cpu(), run2.sel_cnt.cpu(), mask=None)
+    check_attn(cfg, run2.out, run2.lse, ref2, lse2)
+
+
+def test_incremental_block_reps():
+    """Representatives of a block range only: other rows stay untouched."""
+    cfg = small()
+    x = W.make_layer(cfg)
+    run = GpuRun(cfg, to_gpu(x), poison=False)
+    run.reps.fill_(123.0)
+    run.block_reps(first_block=5, n_blocks=3).sync()
+    ref = O.block_reps(x["k_pool"], x["block_table"], x["seq_lens"], cfg.block_size, cfg.nb_max)
+    got = run.reps.cpu().double().numpy()
+    assert np.abs(got[:, :, 5:8] - ref[:, :, 5:8]).max() < 1e-5
+    assert (got[:, :, :5] == 123.0).all() and (got[:, :, 8:] == 123.0).all()
+
+
+def test_exact_ties_lowest_index_wins():
+    """All representatives equal => every score ties => blocks 0..k-1 (after forced ones)."""
+    cfg = small(n_sink=0, n_local=1, k_blocks=4)
+    x = W.make_layer(cfg)
+    run = GpuRun(cfg, to_gpu(x), poison=False)
+    run.reps.fill_(0.25)
+    run.score_select().sync()
+    idx = run.sel_idx.cpu().numpy()
+    assert (idx == np.array([0, 1, 2, 15])).all()
+    run.reps.fill_(0.0)                      # +0 / -0 scores must tie as well
+    run.score_select().sync()
+    assert (run.sel_idx.cpu().numpy() == np.array([0, 1, 2, 15])).all()
+
+
+# ------------------------------------------------------------------ properties that hold at any size
+
+def test_constant_values_give_constant_output():
+    cfg = W.shrink(W.CONFIGS[3], 4096)
+    x = W.make_layer(cfg)
+    x["v_pool"] = torch.full_like(x["v_pool"], 0.375)
+    x["v_draft"] = torch.full_like(x["v_draft"], 0.375)
+    run = GpuRun(cfg, to_gpu(x))
+    run.block_reps().score_select().verify_attn().sync()
+    out = run.out.float().cpu()
+    assert (out - 0.375).abs().max() <= 0.375 * 2 ** -8        # one bf16 ulp
+
+
+def test_unselected_block_cannot_influence_output():
+    cfg = W.shrink(W.CONFIGS[3], 4096)
+    x = W.make_layer(cfg)
+    run = GpuRun(cfg, to_gpu(x))
+    run.block_reps().score_select().verify_attn().sync()
+    out0, idx0 = run.out.clone(), run.sel_idx.clone()
+    # overwrite V of one unselected block per (b, h) with large noise
+    idx = idx0.cpu().numpy()
+    table = x["block_table"]
+    g = torch.Generator().manual_seed(5)
+    v2 = x["v_pool"].clone()
+    for b in range(cfg.B):
+        for h in range(cfg.Hkv):
+            j = next(j for j in range(cfg.nb_max) if j not in set(idx[b, h].tolist()))
+            for t in range(j * cfg.block_size, (j + 1) * cfg.block_size):
+                pg = int(table[b, t // cfg.page_size])
+                v2[pg, t % cfg.page_size, h] = (torch.randn(cfg.d, generator=g) * 100).to(v2.dtype)
+    run.x["v_pool"] = v2.cuda()
+    run.out.fill_(float("nan"))
+    run.verify_attn().sync()
+    assert torch.equal(run.sel_idx, idx0)
+    assert torch.equal(run.out.view(torch.int16), out0.view(torch.int16))
+
+
+def test_page_permutation_is_invisible():
+    """Same logical cache in two physical page orders: identical representatives, ids and outputs."""
+    cfg = W.shrink(W.CONFIGS[3], 4096)
+    x = W.make_layer(cfg)
+    run = GpuRun(cfg, to_gpu(x))
+    run.block_reps().score_select().verify_attn().sync()
+    n_pages = x["k_pool"].shape[0]
+    perm = torch.randperm(n_pages, generator=torch.Generator().manual_seed(3))
+    y = dict(x)
+    inv = torch.empty_like(perm)
+    inv[perm] = torch.arange(n_pages)
+    y["k_pool"] = x["k_pool"][perm]
+    y["v_pool"] = x["v_pool"][perm]
+    y["block_table"] = inv[x["block_table"].long()].to(torch.int32)
+    run2 = GpuRun(cfg, to_gpu(y))
+    run2.block_reps().score_select().verify_attn().sync()
+    assert torch.equal(run.reps.view(torch.int32), run2.reps.view(torch.int32))
+    assert torch.equal(run.sel_idx, run2.sel_idx)
+    assert torch.equal(run.out.view(torch.int16), run2.out.view(torch.int16))
+
+
+def test_repeated_calls_are_bit_stable():
+    cfg = W.CONFIGS[2]
+    x = W.make_layer(cfg)
+    run = GpuRun(cfg, to_gpu(x))
+    run.block_reps().score_select().verify_attn().sync()
+    out0, idx0 = run.out.clone(), run.sel_idx.clone()
+    for _ in range(5):
+        run.out.fill_(float("nan"))
+        run.verify_step(True).sync()
+        assert torch.equal(run.sel_idx, idx0)
+        assert torch.equal(run.out.view(torch.int16), out0.view(torch.int16))
+
+
+def test_budget_helper_matches_oracle():
+    for L, L0, rho, bs in [(32768, 4096, 0.1, 64), (4096, 4096, 0.1, 64), (131072, 1024, 0.1, 128), (777, 100, 0.5, 7)]:
+        assert S.svf_budget_blocks(L, L0, rho, bs) == O.budget_blocks(L, L0, rho, bs)
