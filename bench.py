@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse verification-attention step on one MI355X.
+
+A "step" is one verification step of the whole model: for every layer, svf_verify_step with
+retrieval (scores + top-N) on anchor layers and reuse of the anchor's block set elsewhere
+(Sec. 3.3), i.e. cfg 3: 32 x verification attention + 16 x score/select at 32k context,
+8 drafts, 2048-token budget, paged KV.  Block representatives are built once before the timed
+region (they are maintained at prefill / cache growth, not per step) and timed separately.
+
+Prints ONE JSON line (see the field list at the bottom).  Inputs are synthetic and resident in
+HBM before the timed region; every layer has its own KV pool so no layer's KV is re-read from
+cache between steps.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--cfg", type=int, default=3, help="workload configuration (3 = the headline metric)")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the config's)")
+    ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=4, help="layers the CPU oracle is timed on")
+    ap.add_argument("--profile-only", default="", help="run only this many steps of the timed loop (for rocprofv3)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 "
+              "(the path shards over batch / KV heads with no exchange, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2512_21911_amd as S
+    import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    S.lib()                      # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    cfg = W.CONFIGS[args.cfg]
+    n_layers = args.layers or cfg.n_layers
+    t_setup = time.time()
+
+    # ---- per-layer device inputs --------------------------------------------------------
+    layers = []
+    for l in range(n_layers):
+        x = W.make_layer(cfg, l, device="cuda")
+        layers.append(x)
+    x0 = layers[0]
+    shape = S.make_shape(B=cfg.B, gamma=cfg.gamma, Hq=cfg.Hq, Hkv=cfg.Hkv, d=cfg.d, dtype=cfg.dtype,
+                         block_size=cfg.block_size, max_seq_len=cfg.T, k_blocks=cfg.k_blocks, k_pool=x0["k_pool"],
+                         page_size=cfg.page_size,
+                         max_pages_per_seq=(x0["block_table"].shape[1] if x0["block_table"] is not None else 0),
+                         n_sink=cfg.n_sink, n_local=cfg.n_local)
+    ws = S.new_workspace(shape)
+    dev = "cuda"
+    reps = [torch.zeros(cfg.B, cfg.Hkv, cfg.nb_max, cfg.d, device=dev, dtype=torch.float32) for _ in range(n_layers)]
+    outs = [torch.empty(cfg.B, cfg.gamma, cfg.Hq, cfg.d, device=dev, dtype=cfg.torch_dtype) for _ in range(n_layers)]
+    sel_idx = torch.full((cfg.B, cfg.Hkv, cfg.k_blocks), -1, device=dev, dtype=torch.int32)
+    sel_cnt = torch.zeros((cfg.B, cfg.Hkv), device=dev, dtype=torch.int32)
+    # per-anchor copies of the block sets for the attention-only loop
+    sel_idx_l = [torch.empty_like(sel_idx) for _ in range(n_layers)]
+    sel_cnt_l = [torch.empty_like(sel_cnt) for _ in range(n_layers)]
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    # ---- block representatives: built once, timed on their own ---------------------------
+    def reps_pass():
+        for l, x in enumerate(layers):
+            S.svf_block_reps(shape, x["k_pool"], x["block_table"], x["seq_lens"], reps[l])
+    reps_pass()
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record()
+    reps_pass()
+    e1.record()
+    torch.cuda.synchronize()
+    reps_ms = e0.elapsed_time(e1) / n_layers
+    bytes_ = W.algorithmic_bytes(cfg, x0["seq_lens"].cpu())
+
+    # ---- the step -----------------------------------------------------------------------
+    def step():
+        for l, x in enumerate(layers):
+            S.svf_verify_step(shape, cfg.is_anchor(l), x["q"], reps[l], x["k_pool"], x["v_pool"], x["block_table"],
+                              x["seq_lens"], x["k_draft"], x["v_draft"], x["draft_mask"], sel_idx, sel_cnt,
+                              outs[l], ws)
+
+    def attn_only():
+        for l, x in enumerate(layers):
+            S.svf_verify_attn(shape, x["q"], x["k_pool"], x["v_pool"], x["block_table"], x["seq_lens"],
+                              x["k_draft"], x["v_draft"], x["draft_mask"], sel_idx_l[l], sel_cnt_l[l], outs[l], ws)
+
+    def select_only():
+        for l, x in enumerate(layers):
+            if cfg.is_anchor(l):
+                S.svf_score_select(shape, x["q"], reps[l], x["seq_lens"], sel_idx_l[l], sel_cnt_l[l], ws)
+
+    # block sets per layer (anchor's own, followers copy) for the attention-only loop
+    for l, x in enumerate(layers):
+        if cfg.is_anchor(l):
+            S.svf_score_select(shape, x["q"], reps[l], x["seq_lens"], sel_idx_l[l], sel_cnt_l[l], ws)
+        else:
+            sel_idx_l[l].copy_(sel_idx_l[l - 1])
+            sel_cnt_l[l].copy_(sel_cnt_l[l - 1])
+    torch.cuda.synchronize()
+    setup_s = time.time() - t_setup
+
+    def make_runner(fn):
+        """Plain launches, or one captured HIP graph of the whole call sequence."""
+        if args.no_graph:
+            return fn
+        fn()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            fn()
+        return graph.replay
+
+    def timed(run, iters, warm):
+        for _ in range(warm):
+            run()
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(iters):
+            run()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / iters          # ms per call of run()
+
+    run_step = make_runner(step)
+    if args.profile_only:
+        n = int(args.profile_only)
+        for _ in range(n):
+            run_step()
+        torch.cuda.synchronize()
+        print(json.dumps({"profile_only_steps": n, "workload": cfg.name}))
+        return
+
+    ms_step = timed(run_step, args.steps, args.warmup)
+    run_attn = make_runner(attn_only)
+    ms_attn = timed(run_attn, args.steps, args.warmup)
+    run_sel = make_runner(select_only)
+    ms_sel = timed(run_sel, args.steps, args.warmup)
+    ms_step_eager = timed(step, max(3, args.steps // 5), 2)
+
+    n_anchor = sum(1 for l in range(n_layers) if cfg.is_anchor(l))
+    attn_us = ms_attn * 1e3 / n_layers                        # average duration of one attention launch
+    sel_us = ms_sel * 1e3 / max(1, n_anchor)
+    attn_gbps = bytes_["verify_attn"] / (attn_us * 1e-6) / 1e9
+    step_bytes = n_layers * bytes_["verify_attn"] + n_anchor * bytes_["score_select"]
+
+    # ---- sampled check against the oracle + CPU baseline (rank 0, N = 1) ------------------
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import svf_oracle as O
+        import numpy as np
+        n_cpu = max(1, min(args.cpu_layers, n_layers))
+        wall = 0.0
+        cpu_t = 0.0
+        idx = cnt = None
+        worst = 0.0
+        gi, gc = torch.empty_like(sel_idx), torch.empty_like(sel_cnt)
+        run_step()
+        torch.cuda.synchronize()
+        for l in range(n_cpu):
+            x = W.make_layer(cfg, l, device="cpu")
+            # the same seeds give different normals on CPU and GPU generators, so the GPU is re-run on
+            # this CPU-generated layer for the sampled parity check
+            xr = O.block_reps(x["k_pool"], x["block_table"], x["seq_lens"], cfg.block_size, cfg.nb_max)
+            w0, c0 = time.perf_counter(), time.process_time()
+            if cfg.is_anchor(l):
+                s = O.block_scores(x["q"], xr)
+                idx, cnt = O.select_blocks(s, x["seq_lens"], cfg.block_size, cfg.k_blocks, cfg.n_sink, cfg.n_local)
+            out_ref, _ = O.verify_attn(x["q"], x["k_pool"], x["v_pool"], x["block_table"], x["seq_lens"],
+                                       x["k_draft"], x["v_draft"], x["draft_mask"], idx, cnt, cfg.block_size)
+            wall += time.perf_counter() - w0
+            cpu_t += time.process_time() - c0
+            xg = {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in x.items()}
+            r = torch.empty_like(reps[0])
+            o = torch.empty_like(outs[0])
+            S.svf_block_reps(shape, xg["k_pool"], xg["block_table"], xg["seq_lens"], r)
+            # anchor layers retrieve into gi / gc; the following layers reuse them (Eq. 9)
+            S.svf_verify_step(shape, cfg.is_anchor(l), xg["q"], r, xg["k_pool"], xg["v_pool"], xg["block_table"],
+                              xg["seq_lens"], xg["k_draft"], xg["v_draft"], xg["draft_mask"], gi, gc, o, ws)
+            torch.cuda.synchronize()
+            if cfg.is_anchor(l) and not np.array_equal(gi.cpu().numpy(), idx):
+                raise SystemExit("bench: GPU block selection differs from the oracle on the sampled layer")
+            worst = max(worst, float(np.abs(o.double().cpu().numpy() - out_ref).max()))
+            del xg, x
+        tol = 2e-2 if cfg.dtype == "bf16" else 1e-4
+        if worst > tol:
+            raise SystemExit(f"bench: sampled parity check failed: max-abs {worst:.3e} > {tol}")
+        cpu_us_step = wall / n_cpu * n_layers * 1e6
+        cpu_baseline = {"value": round(cpu_us_step, 1), "unit": "us/step",
+                        "cores": max(1, int(round(cpu_t / max(wall, 1e-9)))), "kind": "oracle",
+                        "sample": f"oracle select+attention timed on layers 0..{n_cpu - 1} of {n_layers} "
+                                  f"({wall:.2f} s wall), scaled to {n_layers} layers; max-abs vs GPU {worst:.2e}"}
+
+    value_us = ms_step * 1e3
+    line = {
+        "metric": "verify-attn us/step (32k ctx, gamma=8, 2k budget)" if args.cfg == 3 else f"verify-attn us/step ({cfg.name})",
+        "value": round(value_us, 2),
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 5),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "d": cfg.d, "T": cfg.T,
+                   "block_size": cfg.block_size, "gamma": cfg.gamma, "budget_tokens": cfg.k_blocks * cfg.block_size,
+                   "page_size": cfg.page_size, "layers": n_layers, "anchor_layers": n_anchor,
+                   "launch": "stream" if args.no_graph else "hipgraph"},
+        "roofline": {"bound": "hbm", "kernel": "svf_verify_attn", "achieved": round(attn_gbps, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": None, "algorithmic_bytes_per_launch": bytes_["verify_attn"],
+                     "avg_launch_us": round(attn_us, 3)},
+        "cpu_baseline": cpu_baseline,
+        "extra": {"step_GBps": round(step_bytes / (value_us * 1e-6) / 1e9, 1),
+                  "step_us_stream_launches": round(ms_step_eager * 1e3, 2),
+                  "score_select_us": round(sel_us, 3),
+                  "score_select_GBps": round(bytes_["score_select"] / (sel_us * 1e-6) / 1e9, 1),
+                  "block_reps_us_per_layer": round(reps_ms * 1e3, 2),
+                  "block_reps_GBps": round(bytes_["block_reps"] / (reps_ms * 1e-3) / 1e9, 1),
+                  "setup_s": round(setup_s, 1)},
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -71,6 +71,7 @@ struct AttnParams {
   float* part_l;               // [B][Hkv][S][Mpad]      partial denominators
   uint32_t* tickets;           // [B][Hkv]               arrival counters, zero between calls
   int32_t B, gamma, Hq, Hkv, G, d, M, Mpad, block_size, k_blocks, n_splits, mask_per_batch, max_seq_len;
+  int32_t block_shift;         // log2(block_size) if a power of two, else -1
   float scale_log2;            // sm_scale * log2(e)
 };
 
