@@ -7,7 +7,8 @@
 //            butterfly reduction inside the lane group.
 //   select:  one workgroup per (sequence, KV head).  Scores become order-preserving 32-bit
 //            keys (forced sink/local blocks get the maximum key); a 4-pass radix select over
-//            LDS histograms finds the key of the weakest kept block, and a final ascending
+//            LDS histograms (bins scanned with a wavefront prefix sum) finds the key of the
+//            weakest kept block, and a final ascending
 //            sweep keeps every block above it plus the lowest-indexed blocks equal to it,
 //            using wavefront ballots for the ordered compaction.  Output is ascending.
 #include <hip/hip_bf16.h>
@@ -114,15 +115,26 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectParams p) {
       if ((k & hi_mask) == prefix) atomicAdd(&hist[(k >> shift) & 0xff], 1u);
     }
     __syncthreads();
-    if (tid == 0) {
-      uint32_t need = sh_need, cum = 0;
-      int bin = 255;
-      for (; bin > 0; --bin) {
-        if (cum + hist[bin] >= need) break;
-        cum += hist[bin];
+    // Thread t looks at bin 255 - t, so an inclusive prefix sum over the threads counts the keys
+    // in this bin and all higher ones; exactly one thread sees the running count cross `need`.
+    {
+      const uint32_t need = sh_need;
+      const uint32_t hcount = hist[255 - tid];
+      uint32_t incl = hcount;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += up;
       }
-      sh_need = need - cum;                 // how many are still wanted from inside this bin
-      sh_prefix = prefix | ((uint32_t)bin << shift);
+      if (lane == 63) wave_eq[wave] = incl;
+      __syncthreads();
+      for (int w = 0; w < wave; ++w) incl += wave_eq[w];
+      const uint32_t above = incl - hcount;        // keys in strictly higher bins
+      __syncthreads();                             // everyone has read sh_need / wave_eq
+      if (incl >= need && above < need) {
+        sh_need = need - above;                    // how many are still wanted from inside this bin
+        sh_prefix = prefix | ((uint32_t)(255 - tid) << shift);
+      }
     }
     __syncthreads();
   }

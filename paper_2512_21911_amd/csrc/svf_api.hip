@@ -96,13 +96,14 @@ AttnPlan plan_attn(const svf_shape_t& s) {
   const size_t pairs = (size_t)s.B * s.Hkv;
   size_t off = 0;
   pl.off_tickets = off;
-  off += align_up(pairs * sizeof(uint32_t));
+  off += align_up(pairs * (pl.Mpad / 32) * sizeof(uint32_t));   // one ticket per (pair, row group)
   pl.off_o = off;
   off += align_up(pairs * pl.n_splits * pl.Mpad * s.d * sizeof(float));
+  // maxima and denominators: two arrays for the vector-ALU kernel, one interleaved (m, l) array
+  // for the matrix-core kernel; same bytes either way
   pl.off_m = off;
-  off += align_up(pairs * pl.n_splits * pl.Mpad * sizeof(float));
-  pl.off_l = off;
-  off += align_up(pairs * pl.n_splits * pl.Mpad * sizeof(float));
+  pl.off_l = off + pairs * pl.n_splits * pl.Mpad * sizeof(float);
+  off += align_up(2 * pairs * pl.n_splits * pl.Mpad * sizeof(float));
   pl.bytes = off;
   return pl;
 }
@@ -267,6 +268,7 @@ int svf_verify_attn(const svf_shape_t* shape, const void* q, const void* K, cons
   p.part_o = reinterpret_cast<float*>(w + pl.off_o);
   p.part_m = reinterpret_cast<float*>(w + pl.off_m);
   p.part_l = reinterpret_cast<float*>(w + pl.off_l);
+  p.part_ml = p.part_m;
   p.B = shape->B;
   p.gamma = shape->gamma;
   p.Hq = shape->Hq;

@@ -8,29 +8,36 @@
 // (plus the draft tokens) are cut into 32-token tiles; tile t belongs to wavefront t mod NW,
 // NW = 4 * n_splits wavefronts per pair (4 per workgroup).  The launch is sized so that a
 // wavefront owns at most kMaxTiles tiles, i.e. every byte the kernel will ever read is
-// requested within the first microsecond: the kernel is a single HBM burst followed by a
-// merge, which is what a 34 MB problem on an 8 TB/s part needs.
+// requested as early as the memory system accepts it: the kernel is one HBM burst followed by
+// a merge, which is what a 34 MB problem on an 8 TB/s part needs.
 //
 // Data path.  A wavefront resolves the addresses of all its tiles first (selected block id ->
 // page table -> row offset), then streams K and V rows straight into LDS with 16-byte
 // direct-to-LDS loads (no registers in between; two 16 KB stages per wavefront, private to it,
-// so no workgroup barrier is needed in the main loop).  The 16-byte chunks of a row are placed
-// at an XOR-swizzled position (chosen on the global-address side, since the LDS side of such
-// a load is fixed by the lane id) which makes the fragment reads below bank-conflict free.
+// so the main loop needs no workgroup barrier).  The 16-byte chunks of a row are placed at an
+// XOR-swizzled position (chosen on the global-address side, since the LDS side of such a load
+// is fixed by the lane id) which keeps the fragment reads below off each other's banks.
+// The LDS reads of the main loop are issued by hand (inline ds_read + explicit waits): the
+// compiler would otherwise wait for every outstanding direct-to-LDS load before any LDS read
+// and serialise the two stages.
 //
 // Math.  Both products run on the matrix cores in transposed form so that a query row lives
 // in a fixed lane (lane mod 32) from the first MFMA to the final store:
-//   S^T[token][row] = K[token][:] . Q[row][:]       A = K tile (LDS, ds_read_b128), B = Q (registers)
+//   S^T[token][row] = K[token][:] . Q[row][:]           A = K tile (LDS, 16-byte reads), B = Q (registers)
 //   O^T[dim][row]  += V^T[dim][token] P^T[token][row]   A = V tile (LDS, 8-byte reads + byte
-//                                                    permutes = transpose), B = P (registers)
+//                                                       permutes = transpose), B = P (registers)
 // The row maximum / denominator therefore need one cross-lane step (lanes l and l+32) per tile
-// and the rescale of O is a per-lane scalar.  Softmax runs in the log2 domain in fp32; P is
-// rounded to bf16 for the second product, accumulators are fp32.
+// and the rescale of O is a per-lane scalar, applied only when the maximum moved by more than
+// kRescaleGap (the stale maximum is kept otherwise; the final division makes this exact).
+// Softmax runs in the log2 domain in fp32; P is rounded to bf16 (hardware RNE) for the second
+// product; accumulators are fp32.
 //
-// Merge.  The four wavefronts of a workgroup combine through LDS (log-sum-exp rule); with more
-// than one split per pair the workgroup writes an unnormalised fp32 partial and the last
-// workgroup to arrive for that pair (atomic ticket) merges all splits and writes out / lse,
-// so the whole call is a single launch.
+// Merge.  The four wavefronts of a workgroup combine through LDS (log-sum-exp rule).  With one
+// split per pair the workgroup writes out / lse itself.  Otherwise it writes an unnormalised
+// fp32 partial, and the last workgroup to arrive for that pair (atomic ticket, release /
+// acquire fences at device scope) merges all splits: the whole call is a single launch.
+// Workgroup ids are mapped so that all splits of a pair share id mod 8, which on this part
+// places them on one XCD, i.e. the partials normally never leave that XCD's L2.
 #include <hip/hip_bf16.h>
 
 #include "svf_device.h"
@@ -45,10 +52,18 @@ constexpr int kTile = 32;            // tokens per tile
 constexpr int kD = 128;              // head dimension
 constexpr int kRowBytes = kD * 2;    // one bf16 K/V row
 constexpr int kTileBytes = kTile * kRowBytes;          // 8 KB: K (or V) part of a stage
+constexpr int kStageBytes = 2 * kTileBytes;            // K then V
+constexpr int kWaveLds = 2 * kStageBytes;              // two stages per wavefront: 32 KB
 constexpr int kMaxTiles = 4;         // tiles a wavefront may own
+constexpr int kXcds = 8;
+constexpr float kRescaleGap = 8.0f;  // log2 units the running maximum may lag behind
+
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float floatx2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 
 #define SVF_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define SVF_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -61,83 +76,244 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("" ::: "memory");
 }
 
+// Hand-issued LDS reads.  The value is not valid until lds_wait8() has been given the register.
+template <int OFF>
+__device__ __forceinline__ u32x4 lds_read16(uint32_t addr) {
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+template <int OFF>
+__device__ __forceinline__ u32x2 lds_read8(uint32_t addr) {
+  u32x2 v;
+  asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+// Waits for all LDS reads; the registers pass through the statement so that no use of them can
+// be scheduled above the wait.
+template <typename T>
+__device__ __forceinline__ void lds_wait8(T (&r)[8]) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7])
+               :
+               : "memory");
+}
+
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  // round to nearest even
-  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-  a += 0x7fffu + ((a >> 16) & 1u);
-  b += 0x7fffu + ((b >> 16) & 1u);
-  return (a >> 16) | (b & 0xffff0000u);
+  const floatx2 f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));   // round to nearest even
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// LDS: two stages of one K tile and one V tile per wavefront.  The four arrays are separate
-// objects on purpose: the compiler then knows which outstanding direct-to-LDS loads a given
-// LDS read can depend on, and waits for those only.  After the main loop array w is reused as
-// wavefront w's fp32 output buffer for the in-workgroup merge.
-constexpr int kArrayBytes = kWaves * kTileBytes;      // 32 KB
-static_assert(kArrayBytes >= 64 * kD * 4, "one array holds a wavefront's 64 x 128 fp32 output");
+// Stores of data exchanged between workgroups.  A relaxed atomic store at device scope compiles
+// to a write-through store, so making it visible across the chip's L2 slices needs no bulk
+// write-back, only a wait for the store's acknowledgement.
+__device__ __forceinline__ void store_coherent4(float* p, float4 v) {
+  // the 16-byte form of the same device-scope write-through store
+  const u32x4 bits = {__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(bits) : "memory");
+}
+__device__ __forceinline__ void store_coherent2(float* p, float a, float b) {
+  const uint64_t bits = (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32);
+  __hip_atomic_store(reinterpret_cast<uint64_t*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
-// grid: (n_splits, Hkv, B * row_groups); block: 256
+// One 32-token tile against RT row tiles.  kaddr / vaddr: this lane's LDS byte addresses of its
+// K fragments (8 k-steps) and V rows (8 k-slots) in stage 0; STAGE_OFF selects the stage.
+template <int RT, int STAGE_OFF, bool FIRST>
+__device__ __forceinline__ void process_tile(const uint32_t (&kaddr)[8], const uint32_t (&vaddr)[8],
+                                             const bf16x8 (&qf)[RT][8], const uint32_t (&allowed)[RT],
+                                             bool all_visible, float scale_log2, int g,
+                                             float (&m_run)[RT], float (&l_run)[RT], floatx16 (&oacc)[RT][4]) {
+  // K fragments, then the first half of the V rows (they land while the S MFMAs run)
+  u32x4 kf[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) kf[ks] = lds_read16<STAGE_OFF>(kaddr[ks]);
+  lds_wait8(kf);
+  u32x2 x0[8], x1[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) x0[e] = lds_read8<STAGE_OFF + kTileBytes>(vaddr[e]);
+
+  // S^T = K Q^T : token = lane mod 32 (A rows), query row = lane mod 32 (B columns)
+  floatx16 sacc[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sacc[rt][v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+      sacc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[ks]), qf[rt][ks],
+                                                         sacc[rt], 0, 0, 0);
+  }
+
+  // online softmax; value v of a lane is token 8*(v/4) + 4*g + v%4 of the tile
+  bf16x8 pf[RT][2];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    float sc[16];
+    if (all_visible) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sc[v] = sacc[rt][v] * scale_log2;
+    } else {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int tok = 8 * (v >> 2) + 4 * g + (v & 3);
+        sc[v] = ((allowed[rt] >> tok) & 1u) ? sacc[rt][v] * scale_log2 : -INFINITY;
+      }
+    }
+    float mx = sc[0];
+#pragma unroll
+    for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sc[v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    // keep the old reference while the maximum has not run away from it
+    float m_ref = m_run[rt];
+    if (FIRST) {
+      m_ref = mx;
+    } else {
+      const bool move = mx > m_ref + kRescaleGap;
+      if (__any(move)) {
+        const float m_new = move ? mx : m_ref;
+        const float alpha = m_new == m_ref ? 1.0f : fast_exp2(m_ref - m_new);   // -inf - finite -> 0
+        l_run[rt] *= alpha;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) oacc[rt][nt][v] *= alpha;
+        m_ref = m_new;
+      }
+    }
+    m_run[rt] = m_ref;
+    const float m_use = m_ref == -INFINITY ? 0.f : m_ref;
+    float ls = 0.f;
+    float pe[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      pe[v] = fast_exp2(sc[v] - m_use);
+      ls += pe[v];
+    }
+    l_run[rt] += ls;
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) {
+      u32x4 w;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) w[j] = pack_bf16(pe[8 * ks2 + 2 * j], pe[8 * ks2 + 2 * j + 1]);
+      pf[rt][ks2] = __builtin_bit_cast(bf16x8, w);
+    }
+  }
+
+  // O^T += V^T P^T : A row i = lane mod 32 carries dims 4*i + nt; k-slot e of lane group g is
+  // token 16*ks2 + 8*(e/4) + 4*g + e%4.  x[e] holds dims 4*i .. 4*i+3 of that token.
+  lds_wait8(x0);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) x1[e] = lds_read8<STAGE_OFF + kTileBytes + 16 * kRowBytes>(vaddr[e]);
+#pragma unroll
+  for (int ks2 = 0; ks2 < 2; ++ks2) {
+    if (ks2 == 1) lds_wait8(x1);
+    const u32x2(&x)[8] = ks2 == 0 ? x0 : x1;
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+      u32x4 w;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t a = nt < 2 ? x[2 * j][0] : x[2 * j][1];
+        const uint32_t c2 = nt < 2 ? x[2 * j + 1][0] : x[2 * j + 1][1];
+        w[j] = __builtin_amdgcn_perm(c2, a, (nt & 1) ? 0x07060302u : 0x05040100u);
+      }
+      const bf16x8 vf = __builtin_bit_cast(bf16x8, w);
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+        oacc[rt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[rt][ks2], oacc[rt][nt], 0, 0, 0);
+    }
+  }
+}
+
+// grid: 1-D, kXcds * ceil(groups / kXcds) * n_splits workgroups, groups = B * Hkv * row_groups
 template <int RT>
-__global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p, int row_groups) {
-  __shared__ __attribute__((aligned(1024))) unsigned char sK0[kArrayBytes];
-  __shared__ __attribute__((aligned(1024))) unsigned char sV0[kArrayBytes];
-  __shared__ __attribute__((aligned(1024))) unsigned char sK1[kArrayBytes];
-  __shared__ __attribute__((aligned(1024))) unsigned char sV1[kArrayBytes];
+__global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p, int row_groups, int groups) {
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[kWaves * kWaveLds];
   __shared__ float sm_m[kWaves][64];
   __shared__ float sm_l[kWaves][64];
+  __shared__ int sm_last;
 
-  const int split = blockIdx.x, h = blockIdx.y;
-  const int b = blockIdx.z / row_groups, rg = blockIdx.z - b * row_groups;
+  // workgroup id -> (group, split): all splits of a group share id mod kXcds
+  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+  const int group = xcd + kXcds * (slot / p.n_splits);
+  const int split = slot % p.n_splits;
+  if (group >= groups) return;
+  const int pair = group / row_groups, rg = group - pair * row_groups;
+  const int b = pair / p.Hkv, h = pair - b * p.Hkv;
+
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
   const int l32 = lane & 31, g = lane >> 5;
-  const int pair = b * p.Hkv + h;
   constexpr int ROWS = 32 * RT;
   const int row0 = rg * ROWS;
-
-  const int L = clamped_len(p.seq_lens, b, p.max_seq_len);
-  const int cnt = min(max(p.sel_cnt[pair], 0), p.k_blocks);
-  const int32_t* __restrict__ sel = p.sel_idx + (int64_t)pair * p.k_blocks;
-  const int n_prefix = cnt * p.block_size;
-  const int tiles_d = (p.gamma + kTile - 1) / kTile;           // draft tiles come first
-  const int tiles = tiles_d + (n_prefix + kTile - 1) / kTile;
   const int NW = kWaves * p.n_splits;
   const int gw = split * kWaves + wave;
+  const int tiles_d = (p.gamma + kTile - 1) / kTile;           // draft tiles come first
 
   const __hip_bfloat16* Kc = static_cast<const __hip_bfloat16*>(p.K);
   const __hip_bfloat16* Vc = static_cast<const __hip_bfloat16*>(p.V);
   const __hip_bfloat16* Kd = static_cast<const __hip_bfloat16*>(p.k_draft);
   const __hip_bfloat16* Vd = static_cast<const __hip_bfloat16*>(p.v_draft);
+  const int32_t* __restrict__ sel = p.sel_idx + (int64_t)pair * p.k_blocks;
+
+  // ---- queries of this lane's rows as B operands, and the rows' draft masks -------------------
+  // Issued before anything else: vector loads complete in order, so a wait for these must not
+  // have the K/V stream in front of it.
+  bf16x8 qf[RT][8];
+  uint64_t rmask[RT];
+  int rdraft[RT];                // draft index of the row, -1 for padding rows
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int row = row0 + rt * 32 + l32;
+    const bool ok = row < p.M;
+    const int i = ok ? row / p.G : 0;
+    const int j = h * p.G + (ok ? row - i * p.G : 0);
+    const __hip_bfloat16* qrow =
+        static_cast<const __hip_bfloat16*>(p.q) + (((int64_t)b * p.gamma + i) * p.Hq + j) * kD + g * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[rt][ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
+    // unconditional load (row 0's entry for padding rows); combined with the causal default
+    // only after the stream has been started, so that nothing waits on it here
+    const uint64_t* mp = p.draft_mask ? p.draft_mask + (p.mask_per_batch ? (int64_t)b * p.gamma + i : i) : nullptr;
+    rmask[rt] = mp ? *mp : 0;
+    rdraft[rt] = ok ? i : -1;
+  }
 
   // ---- resolve the addresses of all tiles this wavefront owns --------------------------------
   // Written without branches around the loads so that the (up to four) block-id loads go out
-  // together, then the page-table loads: two memory round trips instead of eight.
-  // Rows are 16-byte aligned, so bit 0 of an element offset is free to say "relative to the
-  // draft arrays" (set) or "relative to the cache pools" (clear).
-  const int64_t safe_off = (((int64_t)b * p.gamma * p.Hkv + h) * kD) | 1;   // draft 0: always readable
+  // together and at once (they do not wait for sel_cnt / seq_lens), then the page-table loads:
+  // two memory round trips in front of the K/V stream.
+  int t_in[kMaxTiles], t_blk[kMaxTiles];
+#pragma unroll
+  for (int u = 0; u < kMaxTiles; ++u) {
+    const int t = gw + u * NW;
+    int slot_p = (t - tiles_d) * kTile + l32;
+    slot_p = slot_p < 0 ? 0 : slot_p;
+    int bi = p.block_shift >= 0 ? slot_p >> p.block_shift : slot_p / p.block_size;
+    t_in[u] = slot_p - bi * p.block_size;
+    bi = bi < p.k_blocks ? bi : p.k_blocks - 1;
+    t_blk[u] = sel[bi];
+  }
+  const int L = clamped_len(p.seq_lens, b, p.max_seq_len);
+  const int cnt = min(max(p.sel_cnt[pair], 0), p.k_blocks);
+  const int n_prefix = cnt * p.block_size;
+  const int tiles = tiles_d + (n_prefix + kTile - 1) / kTile;
+
   int n_my = 0;
   bool t_draft[kMaxTiles], t_ok[kMaxTiles];
-  int t_blk[kMaxTiles], t_in[kMaxTiles];
+  int t_phys[kMaxTiles], t_slot[kMaxTiles];
 #pragma unroll
   for (int u = 0; u < kMaxTiles; ++u) {
     const int t = gw + u * NW;
     if (t < tiles) n_my = u + 1;
     t_draft[u] = t < tiles_d;
-    const int slot = (t - tiles_d) * kTile + l32;
-    t_ok[u] = t < tiles && !t_draft[u] && slot < n_prefix;
-    const int sl = t_ok[u] ? slot : 0;
-    const int bi = p.block_shift >= 0 ? sl >> p.block_shift : sl / p.block_size;
-    t_in[u] = sl - bi * p.block_size;
-    t_blk[u] = sel[bi];                                  // bi < k_blocks always
-  }
-  int t_phys[kMaxTiles], t_slot[kMaxTiles];
-#pragma unroll
-  for (int u = 0; u < kMaxTiles; ++u) {
+    const int slot_p = (t - tiles_d) * kTile + l32;
     int tok = t_blk[u] * p.block_size + t_in[u];
-    t_ok[u] = t_ok[u] && t_blk[u] >= 0 && tok < L;
+    t_ok[u] = t < tiles && !t_draft[u] && slot_p < n_prefix && t_blk[u] >= 0 && tok < L;
     tok = t_ok[u] ? tok : 0;
     if (p.kv.page_size == 0) {
       t_phys[u] = b;
@@ -148,6 +324,9 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       t_phys[u] = p.table[(int64_t)b * p.kv.max_pages + pg];   // pg = 0 for invalid slots
     }
   }
+  // Rows are 16-byte aligned, so bit 0 of an element offset is free to say "relative to the
+  // draft arrays" (set) or "relative to the cache pools" (clear).
+  const int64_t safe_off = (((int64_t)b * p.gamma * p.Hkv + h) * kD) | 1;   // draft 0: always readable
   int64_t t_off[kMaxTiles];
   uint32_t t_valid[kMaxTiles];
 #pragma unroll
@@ -167,29 +346,10 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     t_valid[u] = (uint32_t)__ballot(ok);
   }
 
-  // ---- queries of this lane's rows as B operands, and the rows' draft masks -------------------
-  bf16x8 qf[RT][8];
-  uint64_t rmask[RT];
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    const int row = row0 + rt * 32 + l32;
-    const bool ok = row < p.M;
-    const int i = ok ? row / p.G : 0;
-    const int j = h * p.G + (ok ? row - i * p.G : 0);
-    const __hip_bfloat16* qrow =
-        static_cast<const __hip_bfloat16*>(p.q) + (((int64_t)b * p.gamma + i) * p.Hq + j) * kD + g * 8;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qf[rt][ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
-    uint64_t m = 0;
-    if (ok) {
-      if (p.draft_mask) m = p.draft_mask[p.mask_per_batch ? (int64_t)b * p.gamma + i : i];
-      else m = i >= 63 ? ~0ull : ((2ull << i) - 1ull);
-    }
-    rmask[rt] = m;
-  }
-
   // chunk swizzle: 16-byte chunk c of the row in tile slot s sits at position c ^ (s & 15)
-  auto issue_tile = [&](int64_t my_off, unsigned char* kdst, unsigned char* vdst) {
+  unsigned char* const my_lds = smem + wave * kWaveLds;
+  auto issue_tile = [&](int64_t my_off, unsigned char* kdst) {
+    unsigned char* vdst = kdst + kTileBytes;
     const int pos = lane & 15;
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
@@ -204,10 +364,30 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(vsrc), SVF_LDS_PTR(vdst + n * 1024), 16, 0, 0);
     }
   };
-  unsigned char* const myK0 = sK0 + wave * kTileBytes;
-  unsigned char* const myV0 = sV0 + wave * kTileBytes;
-  unsigned char* const myK1 = sK1 + wave * kTileBytes;
-  unsigned char* const myV1 = sV1 + wave * kTileBytes;
+  // Everything loaded so far (queries, block ids, page table entries) is needed before the
+  // stream starts anyway; draining the counter here keeps later register reuse from being
+  // mistaken for a hazard against the stream.
+  wait_vmcnt<0>();
+  if (n_my > 0) issue_tile(t_off[0], my_lds);
+  if (n_my > 1) issue_tile(t_off[1], my_lds + kStageBytes);
+
+  // this lane's LDS read addresses inside stage 0 (stage 1 = + kStageBytes, an immediate)
+  const uint32_t lds0 = (uint32_t)(uintptr_t)SVF_LDS_PTR(my_lds);
+  uint32_t kaddr[8], vaddr[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) kaddr[ks] = lds0 + l32 * kRowBytes + (((2 * ks + g) ^ (l32 & 15)) << 4);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int tok = 8 * (e >> 2) + 4 * g + (e & 3);
+    vaddr[e] = lds0 + tok * kRowBytes + (((l32 >> 1) ^ (tok & 15)) << 4) + ((l32 & 1) << 3);
+  }
+
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int i = rdraft[rt];
+    if (i < 0) rmask[rt] = 0;
+    else if (!p.draft_mask) rmask[rt] = i >= 63 ? ~0ull : ((2ull << i) - 1ull);   // linear causal drafts
+  }
 
   // ---- main loop ---------------------------------------------------------------------------
   float m_run[RT], l_run[RT];
@@ -222,113 +402,37 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       for (int v = 0; v < 16; ++v) oacc[rt][nt][v] = 0.f;
   }
 
-  if (n_my > 0) issue_tile(t_off[0], myK0, myV0);
-  if (n_my > 1) issue_tile(t_off[1], myK1, myV1);
-
 #pragma unroll
   for (int u = 0; u < kMaxTiles; ++u) {
     if (u < n_my) {
-      // the 16 loads of tile u are followed by at most the 16 loads of tile u + 1
+      // The 16 loads of tile u are followed by at most the 16 loads of tile u + 1 (the query
+      // loads above only make this wait more conservative).
       if (u + 1 < n_my) wait_vmcnt<16>(); else wait_vmcnt<0>();
-      const unsigned char* kt = (u & 1) ? myK1 : myK0;
-      const unsigned char* vt = (u & 1) ? myV1 : myV0;
-
-      // S^T = K Q^T : token = l32 (A rows), row = l32 (B cols)
-      floatx16 sacc[RT];
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) sacc[rt][v] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const int c = 2 * ks + g;
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kt + l32 * kRowBytes + ((c ^ (l32 & 15)) << 4));
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-          sacc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rt][ks], sacc[rt], 0, 0, 0);
-      }
-
-      // online softmax; value v of a lane is token 8*(v/4) + 4*g + v%4 of the tile
+      uint32_t allowed[RT];
+      const bool all_visible = !t_draft[u] && t_valid[u] == 0xffffffffu;
       const int draft_base = (gw + u * NW) * kTile;       // first draft index of a draft tile
-      bf16x8 pf[RT][2];
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
-        uint32_t allowed = t_valid[u];
-        if (t_draft[u]) allowed &= (uint32_t)(rmask[rt] >> (draft_base & 63));
-        float sc[16];
-        float mx = -INFINITY;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int tok = 8 * (v >> 2) + 4 * g + (v & 3);
-          const bool vis = (allowed >> tok) & 1u;
-          sc[v] = vis ? sacc[rt][v] * p.scale_log2 : -INFINITY;
-          mx = fmaxf(mx, sc[v]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run[rt], mx);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = fast_exp2(m_run[rt] - m_use);
-        float ls = 0.f;
-        float pe[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          pe[v] = fast_exp2(sc[v] - m_use);
-          ls += pe[v];
-        }
-        l_run[rt] = l_run[rt] * alpha + ls;
-        m_run[rt] = m_new;
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) oacc[rt][nt][v] *= alpha;
-#pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2) {
-          u32x4 w;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) w[j] = pack_bf16(pe[8 * ks2 + 2 * j], pe[8 * ks2 + 2 * j + 1]);
-          pf[rt][ks2] = __builtin_bit_cast(bf16x8, w);
-        }
+        allowed[rt] = t_valid[u];
+        if (t_draft[u]) allowed[rt] &= (uint32_t)(rmask[rt] >> (draft_base & 63));
       }
-
-      // O^T += V^T P^T : A row i = l32 carries dims 4*i + nt, k-slot e of group g is token
-      // 16*ks2 + 8*(e/4) + 4*g + e%4
-#pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2) {
-        uint2 x[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int tok = 16 * ks2 + 8 * (e >> 2) + 4 * g + (e & 3);
-          const int c = l32 >> 1;
-          x[e] = *reinterpret_cast<const uint2*>(vt + tok * kRowBytes + ((c ^ (tok & 15)) << 4) + ((l32 & 1) << 3));
-        }
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-          u32x4 w;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const uint32_t a = nt < 2 ? x[2 * j].x : x[2 * j].y;
-            const uint32_t c2 = nt < 2 ? x[2 * j + 1].x : x[2 * j + 1].y;
-            w[j] = __builtin_amdgcn_perm(c2, a, (nt & 1) ? 0x07060302u : 0x05040100u);
-          }
-          const bf16x8 vf = __builtin_bit_cast(bf16x8, w);
-#pragma unroll
-          for (int rt = 0; rt < RT; ++rt)
-            oacc[rt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[rt][ks2], oacc[rt][nt], 0, 0, 0);
-        }
-      }
-
-      // refill this stage with the tile after next
-      if (u + 2 < kMaxTiles && u + 2 < n_my) {
-        if (u & 1) issue_tile(t_off[u + 2 < kMaxTiles ? u + 2 : 0], myK1, myV1);
-        else issue_tile(t_off[u + 2 < kMaxTiles ? u + 2 : 0], myK0, myV0);
-      }
+      if (u & 1)
+        process_tile<RT, kStageBytes, false>(kaddr, vaddr, qf, allowed, all_visible, p.scale_log2, g, m_run,
+                                             l_run, oacc);
+      else if (u == 0)
+        process_tile<RT, 0, true>(kaddr, vaddr, qf, allowed, all_visible, p.scale_log2, g, m_run, l_run, oacc);
+      else
+        process_tile<RT, 0, false>(kaddr, vaddr, qf, allowed, all_visible, p.scale_log2, g, m_run, l_run, oacc);
+      // refill this stage with the tile after next (all LDS reads of the stage have completed)
+      if (u + 2 < kMaxTiles && u + 2 < n_my)
+        issue_tile(t_off[u + 2 < kMaxTiles ? u + 2 : 0], my_lds + (u & 1) * kStageBytes);
     }
   }
 
   // ---- combine the four wavefronts through LDS ---------------------------------------------
-  // Wavefront w parks its rescaled fp32 output in array w as [ROWS][32 float4]; float4 chunk c4
-  // of row r sits at position c4 ^ (r & 31), which keeps both the row-per-lane writes and the
-  // chunk-per-lane reads off each other's banks.
+  // Wavefront w parks its rescaled fp32 output in its own 32 KB as [ROWS][32 float4]; float4
+  // chunk c4 of row r sits at position c4 ^ (r & 31), which keeps both the row-per-lane writes
+  // and the chunk-per-lane reads off each other's banks.
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) l_run[rt] += __shfl_xor(l_run[rt], 32, 64);
   if (g == 0) {
@@ -339,10 +443,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     }
   }
   __syncthreads();                       // every wavefront is done with its K/V stages
-  float4* const obuf[kWaves] = {reinterpret_cast<float4*>(sK0), reinterpret_cast<float4*>(sV0),
-                                reinterpret_cast<float4*>(sK1), reinterpret_cast<float4*>(sV1)};
   {
-    float4* mine = wave == 0 ? obuf[0] : wave == 1 ? obuf[1] : wave == 2 ? obuf[2] : obuf[3];
+    float4* mine = reinterpret_cast<float4*>(my_lds);
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
       const int r = rt * 32 + l32;
@@ -361,7 +463,9 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   __syncthreads();
 
   // 256 threads: thread -> (row, float4 chunk); ROWS * 32 float4 in total
+  const bool single = p.n_splits == 1;
   const int64_t part_row0 = ((int64_t)pair * p.n_splits + split) * p.Mpad + row0;
+  __hip_bfloat16* out = static_cast<__hip_bfloat16*>(p.out);
   for (int e = tid; e < ROWS * (kD / 4); e += kThreads) {
     const int r = e >> 5, c4 = e & 31;
     float mw = -INFINITY;
@@ -371,24 +475,116 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     float lw = 0.f;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
-      const float4 t = obuf[w][r * 32 + (c4 ^ (r & 31))];
+      const float4 t = reinterpret_cast<const float4*>(smem + w * kWaveLds)[r * 32 + (c4 ^ (r & 31))];
       acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
       const float mwv = sm_m[w][r];
       lw += mwv == -INFINITY ? 0.f : sm_l[w][r] * fast_exp2(mwv - mw);
     }
-    if (row0 + r < p.Mpad) {
-      *reinterpret_cast<float4*>(p.part_o + (part_row0 + r) * kD + 4 * c4) = acc;
-      if (c4 == 0) {
-        p.part_m[part_row0 + r] = mw;
-        p.part_l[part_row0 + r] = lw;
+    const int row = row0 + r;
+    if (single) {
+      if (row < p.M) {
+        const int i = row / p.G, j = h * p.G + row % p.G;
+        const int64_t orow = ((int64_t)b * p.gamma + i) * p.Hq + j;
+        const float inv = 1.0f / lw;
+        uint2 o2;
+        o2.x = pack_bf16(acc.x * inv, acc.y * inv);
+        o2.y = pack_bf16(acc.z * inv, acc.w * inv);
+        *reinterpret_cast<uint2*>(out + orow * kD + 4 * c4) = o2;
+        if (p.lse && c4 == 0) p.lse[orow] = (mw + log2f(lw)) * 0.6931471805599453f;
       }
+    } else if (row < p.Mpad) {
+      float* po = p.part_o + (part_row0 + r) * kD + 4 * c4;
+      store_coherent4(po, acc);
+      if (c4 == 0) store_coherent2(p.part_ml + 2 * (part_row0 + r), mw, lw);
+    }
+  }
+  if (single) return;
+
+  // ---- last workgroup of the group merges the splits ------------------------------------------
+  // The partials were written through to device-coherent memory; once those stores have been
+  // acknowledged (vmcnt = 0) the ticket may be taken.  No bulk cache write-back / invalidate.
+  wait_vmcnt<0>();
+  __syncthreads();
+  if (tid == 0) {
+    const uint32_t prev = __hip_atomic_fetch_add(&p.tickets[group], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = prev == (uint32_t)p.n_splits - 1u;
+    // leave the counter ready for the next call
+    if (last) __hip_atomic_store(&p.tickets[group], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    sm_last = last;
+  }
+  __syncthreads();
+  if (!sm_last) return;
+  // Acquire at device scope: drops whatever this XCD's caches still hold of the partial buffers
+  // (they are reused by every call), after which ordinary 16-byte loads fetch the written-through
+  // data.  Only the one merging workgroup per group pays for it.
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+
+  // Eight threads per row, 16 channels each; the loads of up to kMergeBatch splits are all in
+  // flight before the first is used (a chain of dependent device-scope loads would cost a full
+  // memory round trip per split).
+  constexpr int kMergeBatch = 8;
+  const int64_t g_row0 = (int64_t)pair * p.n_splits * p.Mpad + row0;
+  const int cg = tid & 7;
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int r = rt * 32 + (tid >> 3);
+    const int row = row0 + r;
+    float acc[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) acc[c] = 0.f;
+    float m_acc = -INFINITY, l_acc = 0.f;
+    for (int s0 = 0; s0 < p.n_splits; s0 += kMergeBatch) {
+      float2 ml[kMergeBatch];
+      float4 t[kMergeBatch][4];
+#pragma unroll
+      for (int u = 0; u < kMergeBatch; ++u) {
+        const int s = min(s0 + u, p.n_splits - 1);             // duplicates are given weight 0 below
+        const int64_t pr = g_row0 + (int64_t)s * p.Mpad + r;
+        ml[u] = *reinterpret_cast<const float2*>(p.part_ml + 2 * pr);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) t[u][c] = *reinterpret_cast<const float4*>(p.part_o + pr * kD + cg * 16 + 4 * c);
+      }
+      float mb = m_acc;
+#pragma unroll
+      for (int u = 0; u < kMergeBatch; ++u)
+        if (s0 + u < p.n_splits) mb = fmaxf(mb, ml[u].x);
+      const float fa = m_acc == -INFINITY ? 0.f : fast_exp2(m_acc - mb);
+      l_acc *= fa;
+#pragma unroll
+      for (int c = 0; c < 16; ++c) acc[c] *= fa;
+#pragma unroll
+      for (int u = 0; u < kMergeBatch; ++u) {
+        const float w = (s0 + u < p.n_splits && ml[u].x != -INFINITY) ? fast_exp2(ml[u].x - mb) : 0.f;
+        l_acc += w * ml[u].y;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          acc[4 * c] += w * t[u][c].x;
+          acc[4 * c + 1] += w * t[u][c].y;
+          acc[4 * c + 2] += w * t[u][c].z;
+          acc[4 * c + 3] += w * t[u][c].w;
+        }
+      }
+      m_acc = mb;
+    }
+    if (row < p.M) {
+      const int i = row / p.G, j = h * p.G + row % p.G;
+      const int64_t orow = ((int64_t)b * p.gamma + i) * p.Hq + j;
+      const float inv = 1.0f / l_acc;
+      u32x4 o0, o1;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        o0[c] = pack_bf16(acc[2 * c] * inv, acc[2 * c + 1] * inv);
+        o1[c] = pack_bf16(acc[8 + 2 * c] * inv, acc[8 + 2 * c + 1] * inv);
+      }
+      u32x4* dst = reinterpret_cast<u32x4*>(out + orow * kD + cg * 16);
+      dst[0] = o0;
+      dst[1] = o1;
+      if (p.lse && cg == 0) p.lse[orow] = (m_acc + log2f(l_acc)) * 0.6931471805599453f;
     }
   }
 }
 
 }  // namespace
-
-hipError_t launch_merge_splits(const AttnParams& p, int dtype, hipStream_t st);
 
 bool mfma_supported(const svf_shape_t& s) { return s.dtype == SVF_BF16 && s.d == 128; }
 
@@ -410,15 +606,13 @@ int mfma_splits(const svf_shape_t& s) {
 hipError_t launch_verify_attn_mfma(const AttnParams& p, hipStream_t st) {
   const int rows = p.M <= 32 ? 32 : 64;
   const int row_groups = (p.M + rows - 1) / rows;
-  dim3 grid(p.n_splits, p.Hkv, p.B * row_groups);
-  hipError_t e;
+  const int groups = p.B * p.Hkv * row_groups;
+  const unsigned grid = (unsigned)(kXcds * ((groups + kXcds - 1) / kXcds) * p.n_splits);
   if (rows == 32)
-    hipLaunchKernelGGL(verify_attn_mfma_kernel<1>, grid, dim3(kThreads), 0, st, p, row_groups);
+    hipLaunchKernelGGL(verify_attn_mfma_kernel<1>, dim3(grid), dim3(kThreads), 0, st, p, row_groups, groups);
   else
-    hipLaunchKernelGGL(verify_attn_mfma_kernel<2>, grid, dim3(kThreads), 0, st, p, row_groups);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  return launch_merge_splits(p, SVF_BF16, st);
+    hipLaunchKernelGGL(verify_attn_mfma_kernel<2>, dim3(grid), dim3(kThreads), 0, st, p, row_groups, groups);
+  return hipGetLastError();
 }
 
 }  // namespace svf
