@@ -21,6 +21,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
+constexpr int kKeysPerThread = 8;      // selection keys a thread keeps in registers
 constexpr int kPasses = 4;              // blocks scored per lane group in the scores kernel
 
 template <typename T>
@@ -39,8 +40,20 @@ __global__ __launch_bounds__(kThreads) void block_scores_kernel(SelectParams p) 
 
   const int b = blockIdx.z, h = blockIdx.y;
   const int G = p.Hq / p.Hkv;
-  const int L = clamped_len(p.seq_lens, b, p.max_seq_len);
-  const int nb = (L + p.block_size - 1) / p.block_size;
+  const int sub = threadIdx.x % LPB;
+
+  // The representative rows go out first and unconditionally (rows past the sequence's last block
+  // exist in the buffer; their result is discarded), so that they and the query share one memory
+  // round trip instead of queuing behind it.
+  float4 r[kPasses];
+  int jj[kPasses];
+#pragma unroll
+  for (int u = 0; u < kPasses; ++u) {
+    const int j = (blockIdx.x * kPasses + u) * BPW + threadIdx.x / LPB;
+    jj[u] = j;
+    const int jc = j < p.nb_max ? j : p.nb_max - 1;
+    r[u] = *reinterpret_cast<const float4*>(p.reps + (((int64_t)b * p.Hkv + h) * p.nb_max + jc) * D + sub * 4);
+  }
 
   // first draft token's query, averaged over the query heads of this KV head
   if (threadIdx.x < D) {
@@ -49,26 +62,14 @@ __global__ __launch_bounds__(kThreads) void block_scores_kernel(SelectParams p) 
     for (int g = 0; g < G; ++g) s += to_float<T>(q[(int64_t)g * D]);
     q0[threadIdx.x] = s / (float)G;
   }
+  const int L = clamped_len(p.seq_lens, b, p.max_seq_len);
+  const int nb = (L + p.block_size - 1) / p.block_size;
   __syncthreads();
 
-  const int sub = threadIdx.x % LPB;
   const float4 qv = make_float4(q0[sub * 4], q0[sub * 4 + 1], q0[sub * 4 + 2], q0[sub * 4 + 3]);
-  float dot[kPasses];
-  int jj[kPasses];
 #pragma unroll
   for (int u = 0; u < kPasses; ++u) {
-    const int j = (blockIdx.x * kPasses + u) * BPW + threadIdx.x / LPB;
-    jj[u] = j;
-    dot[u] = 0.f;
-    if (j < nb) {
-      const float4 r = *reinterpret_cast<const float4*>(
-          p.reps + (((int64_t)b * p.Hkv + h) * p.nb_max + j) * D + sub * 4);
-      dot[u] = r.x * qv.x + r.y * qv.y + r.z * qv.z + r.w * qv.w;
-    }
-  }
-#pragma unroll
-  for (int u = 0; u < kPasses; ++u) {
-    float v = dot[u];
+    float v = r[u].x * qv.x + r[u].y * qv.y + r[u].z * qv.z + r[u].w * qv.w;
 #pragma unroll
     for (int o = LPB / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
     if (sub == 0 && jj[u] < p.nb_max)
@@ -103,6 +104,14 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectParams p) {
     return score_key(sc[j]);
   };
 
+  // keys of the first kKeysPerThread * 256 blocks stay in registers for all passes
+  uint32_t kreg[kKeysPerThread];
+#pragma unroll
+  for (int i = 0; i < kKeysPerThread; ++i) {
+    const int j = tid + i * kThreads;
+    kreg[i] = j < nb ? key_of(j) : 0u;
+  }
+
   // radix select: key of the cnt-th largest element
   if (tid == 0) { sh_prefix = 0; sh_need = (uint32_t)cnt; }
   for (int shift = 24; shift >= 0; shift -= 8) {
@@ -110,7 +119,10 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectParams p) {
     __syncthreads();
     const uint32_t prefix = sh_prefix;
     const uint32_t hi_mask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
-    for (int j = tid; j < nb; j += kThreads) {
+#pragma unroll
+    for (int i = 0; i < kKeysPerThread; ++i)
+      if (tid + i * kThreads < nb && (kreg[i] & hi_mask) == prefix) atomicAdd(&hist[(kreg[i] >> shift) & 0xff], 1u);
+    for (int j = tid + kKeysPerThread * kThreads; j < nb; j += kThreads) {
       const uint32_t k = key_of(j);
       if ((k & hi_mask) == prefix) atomicAdd(&hist[(k >> shift) & 0xff], 1u);
     }

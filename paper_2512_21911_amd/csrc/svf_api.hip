@@ -96,7 +96,7 @@ AttnPlan plan_attn(const svf_shape_t& s) {
   const size_t pairs = (size_t)s.B * s.Hkv;
   size_t off = 0;
   pl.off_tickets = off;
-  off += align_up(pairs * (pl.Mpad / 32) * sizeof(uint32_t));   // one ticket per (pair, row group)
+  off += align_up(pairs * (pl.Mpad / 32) * sizeof(uint64_t));   // one ticket per (pair, row group)
   pl.off_o = off;
   off += align_up(pairs * pl.n_splits * pl.Mpad * s.d * sizeof(float));
   // maxima and denominators: two arrays for the vector-ALU kernel, one interleaved (m, l) array
@@ -264,7 +264,7 @@ int svf_verify_attn(const svf_shape_t* shape, const void* q, const void* K, cons
   p.sel_cnt = sel_cnt;
   p.out = out;
   p.lse = lse_or_null;
-  p.tickets = reinterpret_cast<uint32_t*>(w + pl.off_tickets);
+  p.tickets = reinterpret_cast<uint64_t*>(w + pl.off_tickets);
   p.part_o = reinterpret_cast<float*>(w + pl.off_o);
   p.part_m = reinterpret_cast<float*>(w + pl.off_m);
   p.part_l = reinterpret_cast<float*>(w + pl.off_l);

@@ -70,7 +70,7 @@ struct AttnParams {
   float* part_m;               // [B][Hkv][S][Mpad]      running maxima (log2 domain)
   float* part_l;               // [B][Hkv][S][Mpad]      partial denominators
   float* part_ml;              // [B][Hkv][S][Mpad][2]   (maximum, denominator) pairs; aliases part_m / part_l
-  uint32_t* tickets;           // [B][Hkv][row groups]   arrival counters, zero between calls
+  uint64_t* tickets;           // [B][Hkv][row groups]   arrival counters, zero between calls
   int32_t B, gamma, Hq, Hkv, G, d, M, Mpad, block_size, k_blocks, n_splits, mask_per_batch, max_seq_len;
   int32_t block_shift;         // log2(block_size) if a power of two, else -1
   float scale_log2;            // sm_scale * log2(e)

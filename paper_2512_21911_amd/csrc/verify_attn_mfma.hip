@@ -3,8 +3,9 @@
 // mask, to each other).
 //
 // Shape of the work.  For one (sequence, KV head) the gamma x G query rows that share the KV
-// head are packed into M = gamma * G rows (row = draft * G + head-in-group) so that every
-// selected key/value is read from HBM once and used by all of them.  The selected tokens
+// head are packed into M = gamma * G rows (row = draft * G + head-in-group), 32 rows per
+// workgroup, so that every selected key/value is read from HBM once and used by all of them
+// (with more than 32 rows the row groups of a pair run on one XCD and share its L2).  The selected tokens
 // (plus the draft tokens) are cut into 32-token tiles; tile t belongs to wavefront t mod NW,
 // NW = 4 * n_splits wavefronts per pair (4 per workgroup).  The launch is sized so that a
 // wavefront owns at most kMaxTiles tiles, i.e. every byte the kernel will ever read is
@@ -109,9 +110,8 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // Stores of data exchanged between workgroups.  A relaxed atomic store at device scope compiles
 // to a write-through store, so making it visible across the chip's L2 slices needs no bulk
 // write-back, only a wait for the store's acknowledgement.
-__device__ __forceinline__ void store_coherent4(float* p, float4 v) {
+__device__ __forceinline__ void store_coherent16(void* p, u32x4 bits) {
   // the 16-byte form of the same device-scope write-through store
-  const u32x4 bits = {__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
   asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(bits) : "memory");
 }
 __device__ __forceinline__ void store_coherent2(float* p, float a, float b) {
@@ -151,21 +151,18 @@ __device__ __forceinline__ void process_tile(const uint32_t (&kaddr)[8], const u
   bf16x8 pf[RT][2];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
-    float sc[16];
-    if (all_visible) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sc[v] = sacc[rt][v] * scale_log2;
-    } else {
+    // invisible tokens drop out by setting their raw score to -inf (the scale is positive)
+    if (!all_visible) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int tok = 8 * (v >> 2) + 4 * g + (v & 3);
-        sc[v] = ((allowed[rt] >> tok) & 1u) ? sacc[rt][v] * scale_log2 : -INFINITY;
+        if (!((allowed[rt] >> tok) & 1u)) sacc[rt][v] = -INFINITY;
       }
     }
-    float mx = sc[0];
+    float mx = sacc[rt][0];
 #pragma unroll
-    for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sc[v]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sacc[rt][v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
     // keep the old reference while the maximum has not run away from it
     float m_ref = m_run[rt];
     if (FIRST) {
@@ -189,7 +186,7 @@ __device__ __forceinline__ void process_tile(const uint32_t (&kaddr)[8], const u
     float pe[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      pe[v] = fast_exp2(sc[v] - m_use);
+      pe[v] = fast_exp2(__builtin_fmaf(sacc[rt][v], scale_log2, -m_use));
       ls += pe[v];
     }
     l_run[rt] += ls;
@@ -228,6 +225,88 @@ __device__ __forceinline__ void process_tile(const uint32_t (&kaddr)[8], const u
   }
 }
 
+// Partials exchanged between the workgroups of a group: per row (m, l) in fp32 and the
+// normalised output o / l in bf16 (its magnitude is bounded by the values' and bf16 is the
+// precision of the inputs and of the final output; accumulation stays fp32 on both sides).
+// 8-byte load of four such channels (or of an (m, l) pair).  LOCAL: the data is known to sit
+// in, or behind, this XCD's L2, so only the per-CU cache has to be bypassed, which is what a
+// relaxed atomic load at workgroup scope compiles to; otherwise a plain load (after an acquire).
+template <bool LOCAL>
+__device__ __forceinline__ uint64_t load_partial8(const void* p) {
+  if (LOCAL)
+    return __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  return *reinterpret_cast<const uint64_t*>(p);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// Final merge of a group's split partials by its last workgroup (256 threads): eight threads
+// per row, 16 channels each.  All splits, the workgroup's own included, are read back in split
+// order, so the result does not depend on which workgroup happened to arrive last; the loads of
+// kMergeBatch splits are all in flight before the first is used.
+template <bool LOCAL>
+__device__ __forceinline__ void merge_splits(const AttnParams& p, int64_t g_row, int64_t orow, bool row_ok, int cg) {
+  constexpr int kMergeBatch = 8;
+  const uint16_t* part_o = reinterpret_cast<const uint16_t*>(p.part_o);
+  float acc[16];
+#pragma unroll
+  for (int c = 0; c < 16; ++c) acc[c] = 0.f;
+  float m_acc = -INFINITY, l_acc = 0.f;
+  for (int s0 = 0; s0 < p.n_splits; s0 += kMergeBatch) {
+    float pm[kMergeBatch], pl[kMergeBatch];
+    uint32_t t[kMergeBatch][8];
+#pragma unroll
+    for (int u = 0; u < kMergeBatch; ++u) {
+      // entries past the last split (index clamped) get weight 0 below
+      const int64_t pr = g_row + (int64_t)min(s0 + u, p.n_splits - 1) * p.Mpad;
+      const uint64_t ml = load_partial8<LOCAL>(p.part_ml + 2 * pr);
+      pm[u] = __uint_as_float((uint32_t)ml);
+      pl[u] = __uint_as_float((uint32_t)(ml >> 32));
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const uint64_t w = load_partial8<LOCAL>(part_o + pr * kD + cg * 16 + 4 * c);
+        t[u][2 * c] = (uint32_t)w;
+        t[u][2 * c + 1] = (uint32_t)(w >> 32);
+      }
+    }
+    float mb = m_acc;
+#pragma unroll
+    for (int u = 0; u < kMergeBatch; ++u) {
+      if (s0 + u >= p.n_splits) pm[u] = -INFINITY;
+      mb = fmaxf(mb, pm[u]);
+    }
+    const float fa = m_acc == -INFINITY ? 0.f : fast_exp2(m_acc - mb);
+    l_acc *= fa;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) acc[c] *= fa;
+#pragma unroll
+    for (int u = 0; u < kMergeBatch; ++u) {
+      // weight of split s: exp2(m_s - m) * l_s, applied to its normalised output
+      const float w = pm[u] != -INFINITY ? fast_exp2(pm[u] - mb) * pl[u] : 0.f;
+      l_acc += w;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        acc[2 * c] += w * bf16_lo(t[u][c]);
+        acc[2 * c + 1] += w * bf16_hi(t[u][c]);
+      }
+    }
+    m_acc = mb;
+  }
+  if (row_ok) {
+    const float inv = 1.0f / l_acc;
+    u32x4 o0, o1;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      o0[c] = pack_bf16(acc[2 * c] * inv, acc[2 * c + 1] * inv);
+      o1[c] = pack_bf16(acc[8 + 2 * c] * inv, acc[8 + 2 * c + 1] * inv);
+    }
+    u32x4* dst = reinterpret_cast<u32x4*>(static_cast<__hip_bfloat16*>(p.out) + orow * kD + cg * 16);
+    dst[0] = o0;
+    dst[1] = o1;
+    if (p.lse && cg == 0) p.lse[orow] = (m_acc + log2f(l_acc)) * 0.6931471805599453f;
+  }
+}
+
 // grid: 1-D, kXcds * ceil(groups / kXcds) * n_splits workgroups, groups = B * Hkv * row_groups
 template <int RT>
 __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p, int row_groups, int groups) {
@@ -241,7 +320,10 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   const int group = xcd + kXcds * (slot / p.n_splits);
   const int split = slot % p.n_splits;
   if (group >= groups) return;
-  const int pair = group / row_groups, rg = group - pair * row_groups;
+  // row groups of one pair are `pairs` apart, i.e. on the same XCD whenever pairs is a multiple
+  // of eight: the second reader of a pair's K/V then finds them in that XCD's L2
+  const int pairs = groups / row_groups;
+  const int rg = group / pairs, pair = group - rg * pairs;
   const int b = pair / p.Hkv, h = pair - b * p.Hkv;
 
   const int tid = threadIdx.x;
@@ -452,6 +534,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) mw = fmaxf(mw, sm_m[w][r]);
       const float f = m_run[rt] == -INFINITY ? 0.f : fast_exp2(m_run[rt] - mw);
+      if (g == 0) sm_l[wave][r] = l_run[rt] * f;           // denominators leave here already rescaled
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int i = 8 * (v >> 2) + 4 * g + (v & 3);      // dims 4*i .. 4*i+3
@@ -462,125 +545,99 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   }
   __syncthreads();
 
-  // 256 threads: thread -> (row, float4 chunk); ROWS * 32 float4 in total
+  // 256 threads: eight per row, 16 channels (four float4 chunks) each; RT passes of 32 rows
   const bool single = p.n_splits == 1;
-  const int64_t part_row0 = ((int64_t)pair * p.n_splits + split) * p.Mpad + row0;
-  __hip_bfloat16* out = static_cast<__hip_bfloat16*>(p.out);
-  for (int e = tid; e < ROWS * (kD / 4); e += kThreads) {
-    const int r = e >> 5, c4 = e & 31;
-    float mw = -INFINITY;
+  const int cg = tid & 7;
+  float racc[RT][16];
+  int64_t rorow[RT];
+  bool rok[RT];
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) mw = fmaxf(mw, sm_m[w][r]);
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    float lw = 0.f;
+  for (int rt = 0; rt < RT; ++rt) {
+    const int r = rt * 32 + (tid >> 3);
+    float mw = -INFINITY, lw = 0.f;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
-      const float4 t = reinterpret_cast<const float4*>(smem + w * kWaveLds)[r * 32 + (c4 ^ (r & 31))];
-      acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
-      const float mwv = sm_m[w][r];
-      lw += mwv == -INFINITY ? 0.f : sm_l[w][r] * fast_exp2(mwv - mw);
+      mw = fmaxf(mw, sm_m[w][r]);
+      lw += sm_l[w][r];
     }
+#pragma unroll
+    for (int c = 0; c < 16; ++c) racc[rt][c] = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float4 t = reinterpret_cast<const float4*>(smem + w * kWaveLds)[r * 32 + ((cg * 4 + c) ^ (r & 31))];
+        racc[rt][4 * c] += t.x; racc[rt][4 * c + 1] += t.y; racc[rt][4 * c + 2] += t.z; racc[rt][4 * c + 3] += t.w;
+      }
     const int row = row0 + r;
+    rok[rt] = row < p.M;
+    const int i = rok[rt] ? row / p.G : 0, j = h * p.G + (rok[rt] ? row % p.G : 0);
+    rorow[rt] = ((int64_t)b * p.gamma + i) * p.Hq + j;
     if (single) {
-      if (row < p.M) {
-        const int i = row / p.G, j = h * p.G + row % p.G;
-        const int64_t orow = ((int64_t)b * p.gamma + i) * p.Hq + j;
+      if (rok[rt]) {
         const float inv = 1.0f / lw;
-        uint2 o2;
-        o2.x = pack_bf16(acc.x * inv, acc.y * inv);
-        o2.y = pack_bf16(acc.z * inv, acc.w * inv);
-        *reinterpret_cast<uint2*>(out + orow * kD + 4 * c4) = o2;
-        if (p.lse && c4 == 0) p.lse[orow] = (mw + log2f(lw)) * 0.6931471805599453f;
+        u32x4 o0, o1;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          o0[c] = pack_bf16(racc[rt][2 * c] * inv, racc[rt][2 * c + 1] * inv);
+          o1[c] = pack_bf16(racc[rt][8 + 2 * c] * inv, racc[rt][8 + 2 * c + 1] * inv);
+        }
+        u32x4* dst = reinterpret_cast<u32x4*>(static_cast<__hip_bfloat16*>(p.out) + rorow[rt] * kD + cg * 16);
+        dst[0] = o0;
+        dst[1] = o1;
+        if (p.lse && cg == 0) p.lse[rorow[rt]] = (mw + log2f(lw)) * 0.6931471805599453f;
       }
     } else if (row < p.Mpad) {
-      float* po = p.part_o + (part_row0 + r) * kD + 4 * c4;
-      store_coherent4(po, acc);
-      if (c4 == 0) store_coherent2(p.part_ml + 2 * (part_row0 + r), mw, lw);
+      // this split's partial: normalised output in bf16, (m, l) in fp32, written through
+      const int64_t pr = ((int64_t)pair * p.n_splits + split) * p.Mpad + row;
+      const float inv = lw > 0.f ? 1.0f / lw : 0.f;
+      u32x4 o0, o1;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        o0[c] = pack_bf16(racc[rt][2 * c] * inv, racc[rt][2 * c + 1] * inv);
+        o1[c] = pack_bf16(racc[rt][8 + 2 * c] * inv, racc[rt][8 + 2 * c + 1] * inv);
+      }
+      uint16_t* po = reinterpret_cast<uint16_t*>(p.part_o) + pr * kD + cg * 16;
+      store_coherent16(po, o0);
+      store_coherent16(po + 8, o1);
+      if (cg == 0) store_coherent2(p.part_ml + 2 * pr, mw, lw);
     }
   }
   if (single) return;
 
   // ---- last workgroup of the group merges the splits ------------------------------------------
   // The partials were written through to device-coherent memory; once those stores have been
-  // acknowledged (vmcnt = 0) the ticket may be taken.  No bulk cache write-back / invalidate.
+  // acknowledged (vmcnt = 0) the ticket may be taken.  No bulk cache write-back.
+  // The ticket is one 64-bit counter: bits [15:0] count arrivals, and eight 6-bit fields above
+  // count arrivals per XCD, so that the last workgroup learns whether every partial of its
+  // group was written through the L2 it is about to read from.
   wait_vmcnt<0>();
   __syncthreads();
   if (tid == 0) {
-    const uint32_t prev = __hip_atomic_fetch_add(&p.tickets[group], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const int last = prev == (uint32_t)p.n_splits - 1u;
+    uint32_t xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    const int field = 16 + 6 * (int)(xcc & 7u);
+    const uint64_t prev = __hip_atomic_fetch_add(&p.tickets[group], 1ull | (1ull << field), __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+    const bool last = (prev & 0xffffull) == (uint64_t)(p.n_splits - 1);
+    const bool same_xcd = p.n_splits <= 63 && ((prev >> field) & 63ull) == (uint64_t)(p.n_splits - 1);
     // leave the counter ready for the next call
-    if (last) __hip_atomic_store(&p.tickets[group], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    sm_last = last;
+    if (last) __hip_atomic_store(&p.tickets[group], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    sm_last = last ? (same_xcd ? 2 : 1) : 0;
   }
   __syncthreads();
-  if (!sm_last) return;
-  // Acquire at device scope: drops whatever this XCD's caches still hold of the partial buffers
-  // (they are reused by every call), after which ordinary 16-byte loads fetch the written-through
-  // data.  Only the one merging workgroup per group pays for it.
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-
-  // Eight threads per row, 16 channels each; the loads of up to kMergeBatch splits are all in
-  // flight before the first is used (a chain of dependent device-scope loads would cost a full
-  // memory round trip per split).
-  constexpr int kMergeBatch = 8;
-  const int64_t g_row0 = (int64_t)pair * p.n_splits * p.Mpad + row0;
-  const int cg = tid & 7;
+  const int last_kind = sm_last;
+  if (last_kind == 0) return;
+  // Remote writers: acquire at device scope, which drops whatever this XCD's caches still hold
+  // of the partial buffers (they are reused by every call); ordinary loads then fetch the
+  // written-through data.  Local writers only (the normal case): this XCD's L2 is their common
+  // coherence point, loads that bypass the per-CU cache are enough.
+  if (last_kind == 1) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
-    const int r = rt * 32 + (tid >> 3);
-    const int row = row0 + r;
-    float acc[16];
-#pragma unroll
-    for (int c = 0; c < 16; ++c) acc[c] = 0.f;
-    float m_acc = -INFINITY, l_acc = 0.f;
-    for (int s0 = 0; s0 < p.n_splits; s0 += kMergeBatch) {
-      float2 ml[kMergeBatch];
-      float4 t[kMergeBatch][4];
-#pragma unroll
-      for (int u = 0; u < kMergeBatch; ++u) {
-        const int s = min(s0 + u, p.n_splits - 1);             // duplicates are given weight 0 below
-        const int64_t pr = g_row0 + (int64_t)s * p.Mpad + r;
-        ml[u] = *reinterpret_cast<const float2*>(p.part_ml + 2 * pr);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) t[u][c] = *reinterpret_cast<const float4*>(p.part_o + pr * kD + cg * 16 + 4 * c);
-      }
-      float mb = m_acc;
-#pragma unroll
-      for (int u = 0; u < kMergeBatch; ++u)
-        if (s0 + u < p.n_splits) mb = fmaxf(mb, ml[u].x);
-      const float fa = m_acc == -INFINITY ? 0.f : fast_exp2(m_acc - mb);
-      l_acc *= fa;
-#pragma unroll
-      for (int c = 0; c < 16; ++c) acc[c] *= fa;
-#pragma unroll
-      for (int u = 0; u < kMergeBatch; ++u) {
-        const float w = (s0 + u < p.n_splits && ml[u].x != -INFINITY) ? fast_exp2(ml[u].x - mb) : 0.f;
-        l_acc += w * ml[u].y;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          acc[4 * c] += w * t[u][c].x;
-          acc[4 * c + 1] += w * t[u][c].y;
-          acc[4 * c + 2] += w * t[u][c].z;
-          acc[4 * c + 3] += w * t[u][c].w;
-        }
-      }
-      m_acc = mb;
-    }
-    if (row < p.M) {
-      const int i = row / p.G, j = h * p.G + row % p.G;
-      const int64_t orow = ((int64_t)b * p.gamma + i) * p.Hq + j;
-      const float inv = 1.0f / l_acc;
-      u32x4 o0, o1;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        o0[c] = pack_bf16(acc[2 * c] * inv, acc[2 * c + 1] * inv);
-        o1[c] = pack_bf16(acc[8 + 2 * c] * inv, acc[8 + 2 * c + 1] * inv);
-      }
-      u32x4* dst = reinterpret_cast<u32x4*>(out + orow * kD + cg * 16);
-      dst[0] = o0;
-      dst[1] = o1;
-      if (p.lse && cg == 0) p.lse[orow] = (m_acc + log2f(l_acc)) * 0.6931471805599453f;
-    }
+    const int64_t g_row = (int64_t)pair * p.n_splits * p.Mpad + row0 + rt * 32 + (tid >> 3);
+    if (last_kind == 2) merge_splits<true>(p, g_row, rorow[rt], rok[rt], cg);
+    else merge_splits<false>(p, g_row, rorow[rt], rok[rt], cg);
   }
 }
 
@@ -592,7 +649,7 @@ bool mfma_supported(const svf_shape_t& s) { return s.dtype == SVF_BF16 && s.d ==
 // never more than kMaxTiles tiles per wavefront, never less than one tile per wavefront.
 int mfma_splits(const svf_shape_t& s) {
   const int M = s.gamma * (s.Hq / s.Hkv);
-  const int rows = M <= 32 ? 32 : 64;
+  const int rows = 32;
   const int64_t groups = (int64_t)s.B * s.Hkv * ((M + rows - 1) / rows);
   const int64_t tiles = ((int64_t)s.k_blocks * s.block_size + kTile - 1) / kTile + (s.gamma + kTile - 1) / kTile;
   int64_t lo = (tiles + kWaves * kMaxTiles - 1) / (kWaves * kMaxTiles);
@@ -604,14 +661,11 @@ int mfma_splits(const svf_shape_t& s) {
 }
 
 hipError_t launch_verify_attn_mfma(const AttnParams& p, hipStream_t st) {
-  const int rows = p.M <= 32 ? 32 : 64;
+  const int rows = 32;
   const int row_groups = (p.M + rows - 1) / rows;
   const int groups = p.B * p.Hkv * row_groups;
   const unsigned grid = (unsigned)(kXcds * ((groups + kXcds - 1) / kXcds) * p.n_splits);
-  if (rows == 32)
-    hipLaunchKernelGGL(verify_attn_mfma_kernel<1>, dim3(grid), dim3(kThreads), 0, st, p, row_groups, groups);
-  else
-    hipLaunchKernelGGL(verify_attn_mfma_kernel<2>, dim3(grid), dim3(kThreads), 0, st, p, row_groups, groups);
+  hipLaunchKernelGGL(verify_attn_mfma_kernel<1>, dim3(grid), dim3(kThreads), 0, st, p, row_groups, groups);
   return hipGetLastError();
 }
 
