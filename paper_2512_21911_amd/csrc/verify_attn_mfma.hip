@@ -119,21 +119,21 @@ __device__ __forceinline__ void store_coherent2(float* p, float a, float b) {
   __hip_atomic_store(reinterpret_cast<uint64_t*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// One 32-token tile against RT row tiles.  kaddr / vaddr: this lane's LDS byte addresses of its
-// K fragments (8 k-steps) and V rows (8 k-slots) in stage 0; STAGE_OFF selects the stage.
-template <int RT, int STAGE_OFF, bool FIRST>
-__device__ __forceinline__ void process_tile(const uint32_t (&kaddr)[8], const uint32_t (&vaddr)[8],
+// One 32-token tile against RT row tiles.  krel / vrel: this lane's byte offsets of its K
+// fragments (8 k-steps) and V rows (8 k-slots) inside a stage; stage: LDS address of the stage.
+template <int RT, bool FIRST>
+__device__ __forceinline__ void process_tile(uint32_t stage, const uint32_t (&krel)[8], const uint32_t (&vrel)[8],
                                              const bf16x8 (&qf)[RT][8], const uint32_t (&allowed)[RT],
                                              bool all_visible, float scale_log2, int g,
                                              float (&m_run)[RT], float (&l_run)[RT], floatx16 (&oacc)[RT][4]) {
   // K fragments, then the first half of the V rows (they land while the S MFMAs run)
   u32x4 kf[8];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) kf[ks] = lds_read16<STAGE_OFF>(kaddr[ks]);
+  for (int ks = 0; ks < 8; ++ks) kf[ks] = lds_read16<0>(stage + krel[ks]);
   lds_wait8(kf);
   u32x2 x0[8], x1[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) x0[e] = lds_read8<STAGE_OFF + kTileBytes>(vaddr[e]);
+  for (int e = 0; e < 8; ++e) x0[e] = lds_read8<kTileBytes>(stage + vrel[e]);
 
   // S^T = K Q^T : token = lane mod 32 (A rows), query row = lane mod 32 (B columns)
   floatx16 sacc[RT];
@@ -203,7 +203,7 @@ __device__ __forceinline__ void process_tile(const uint32_t (&kaddr)[8], const u
   // token 16*ks2 + 8*(e/4) + 4*g + e%4.  x[e] holds dims 4*i .. 4*i+3 of that token.
   lds_wait8(x0);
 #pragma unroll
-  for (int e = 0; e < 8; ++e) x1[e] = lds_read8<STAGE_OFF + kTileBytes + 16 * kRowBytes>(vaddr[e]);
+  for (int e = 0; e < 8; ++e) x1[e] = lds_read8<kTileBytes + 16 * kRowBytes>(stage + vrel[e]);
 #pragma unroll
   for (int ks2 = 0; ks2 < 2; ++ks2) {
     if (ks2 == 1) lds_wait8(x1);
@@ -310,7 +310,9 @@ __device__ __forceinline__ void merge_splits(const AttnParams& p, int64_t g_row,
 // grid: 1-D, kXcds * ceil(groups / kXcds) * n_splits workgroups, groups = B * Hkv * row_groups
 template <int RT>
 __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p, int row_groups, int groups) {
-  __shared__ __attribute__((aligned(1024))) unsigned char smem[kWaves * kWaveLds];
+  // two stages per wavefront, plus one extra stage for the first draft tile so that the
+  // wavefront owning it (wavefront 0 of split 0) still has all its loads in flight at once
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[kWaves * kWaveLds + kStageBytes];
   __shared__ float sm_m[kWaves][64];
   __shared__ float sm_l[kWaves][64];
   __shared__ int sm_last;
@@ -430,38 +432,65 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
 
   // chunk swizzle: 16-byte chunk c of the row in tile slot s sits at position c ^ (s & 15)
   unsigned char* const my_lds = smem + wave * kWaveLds;
-  auto issue_tile = [&](int64_t my_off, unsigned char* kdst) {
+  // Load n of a tile covers slots 4n .. 4n+3 (16 lanes per slot); a lane fetches the byte address
+  // of "its" slot's K row (bit 0: the row is a draft row) from the lane that resolved it.  The
+  // shuffles of a tile are issued together, ahead of its loads, so that their LDS round trips
+  // overlap instead of sitting between the loads.
+  const int64_t kbase_c = (int64_t)(uintptr_t)Kc, kbase_d = (int64_t)(uintptr_t)Kd;
+  const int64_t dv_c = (int64_t)(uintptr_t)Vc - kbase_c, dv_d = (int64_t)(uintptr_t)Vd - kbase_d;
+  // element offset (bit 0 = draft) -> byte address of the K row, bit 0 kept; masks, not selects
+  auto row_addr = [&](int64_t off) -> int64_t {
+    const int64_t is_d = -(off & 1);
+    return kbase_c + ((kbase_d - kbase_c) & is_d) + ((off & ~(int64_t)1) << 1) + (off & 1);
+  };
+  auto gather_tile = [&](int64_t my_addr, int64_t (&a)[8]) {
+#pragma unroll
+    for (int n = 0; n < 8; ++n) a[n] = __shfl(my_addr, 4 * n + (lane >> 4), 64);
+  };
+  auto issue_tile = [&](const int64_t (&a)[8], unsigned char* kdst) {
     unsigned char* vdst = kdst + kTileBytes;
     const int pos = lane & 15;
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
       const int s = 4 * n + (lane >> 4);                 // slot of this lane in load n
-      const int64_t off = __shfl(my_off, s, 64);
       const int c = pos ^ (s & 15);
-      const bool from_draft = off & 1;
-      const int64_t o = (off & ~(int64_t)1) + c * 8;
-      const __hip_bfloat16* ksrc = (from_draft ? Kd : Kc) + o;
-      const __hip_bfloat16* vsrc = (from_draft ? Vd : Vc) + o;
-      __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(ksrc), SVF_LDS_PTR(kdst + n * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(vsrc), SVF_LDS_PTR(vdst + n * 1024), 16, 0, 0);
+      const int64_t ka = (a[n] & ~(int64_t)1) + c * 16;
+      const int64_t va = ka + dv_c + ((dv_d - dv_c) & -(a[n] & 1));
+      __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(ka), SVF_LDS_PTR(kdst + n * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(va), SVF_LDS_PTR(vdst + n * 1024), 16, 0, 0);
     }
   };
   // Everything loaded so far (queries, block ids, page table entries) is needed before the
   // stream starts anyway; draining the counter here keeps later register reuse from being
   // mistaken for a hazard against the stream.
   wait_vmcnt<0>();
-  if (n_my > 0) issue_tile(t_off[0], my_lds);
-  if (n_my > 1) issue_tile(t_off[1], my_lds + kStageBytes);
+  // Tile u of a wavefront sits in stage u & 1; the owner of draft tile 0 keeps that tile in
+  // the extra stage and its other tiles in stages (u - 1) & 1.
+  const bool own_x = gw == 0;
+  unsigned char* const x_lds = smem + kWaves * kWaveLds;
+  auto stage_ptr = [&](int u) -> unsigned char* {
+    if (own_x) return u == 0 ? x_lds : my_lds + ((u - 1) & 1) * kStageBytes;
+    return my_lds + (u & 1) * kStageBytes;
+  };
+  int n_issued = 0;
+  {
+    int64_t a0[8], a1[8], a2[8];
+    gather_tile(row_addr(t_off[0]), a0);
+    gather_tile(row_addr(t_off[1]), a1);
+    if (own_x) gather_tile(row_addr(t_off[2]), a2);
+    if (n_my > 0) { issue_tile(a0, stage_ptr(0)); n_issued = 1; }
+    if (n_my > 1) { issue_tile(a1, stage_ptr(1)); n_issued = 2; }
+    if (own_x && n_my > 2) { issue_tile(a2, stage_ptr(2)); n_issued = 3; }
+  }
 
-  // this lane's LDS read addresses inside stage 0 (stage 1 = + kStageBytes, an immediate)
-  const uint32_t lds0 = (uint32_t)(uintptr_t)SVF_LDS_PTR(my_lds);
-  uint32_t kaddr[8], vaddr[8];
+  // this lane's read offsets inside a stage
+  uint32_t krel[8], vrel[8];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) kaddr[ks] = lds0 + l32 * kRowBytes + (((2 * ks + g) ^ (l32 & 15)) << 4);
+  for (int ks = 0; ks < 8; ++ks) krel[ks] = l32 * kRowBytes + (((2 * ks + g) ^ (l32 & 15)) << 4);
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const int tok = 8 * (e >> 2) + 4 * g + (e & 3);
-    vaddr[e] = lds0 + tok * kRowBytes + (((l32 >> 1) ^ (tok & 15)) << 4) + ((l32 & 1) << 3);
+    vrel[e] = tok * kRowBytes + (((l32 >> 1) ^ (tok & 15)) << 4) + ((l32 & 1) << 3);
   }
 
 #pragma unroll
@@ -487,9 +516,10 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
 #pragma unroll
   for (int u = 0; u < kMaxTiles; ++u) {
     if (u < n_my) {
-      // The 16 loads of tile u are followed by at most the 16 loads of tile u + 1 (the query
-      // loads above only make this wait more conservative).
-      if (u + 1 < n_my) wait_vmcnt<16>(); else wait_vmcnt<0>();
+      // Tiles are issued in order, 16 loads each, so tile u has arrived once at most
+      // 16 * (tiles issued after it) loads are outstanding.
+      const int after = n_issued - (u + 1);
+      if (after >= 2) wait_vmcnt<32>(); else if (after == 1) wait_vmcnt<16>(); else wait_vmcnt<0>();
       uint32_t allowed[RT];
       const bool all_visible = !t_draft[u] && t_valid[u] == 0xffffffffu;
       const int draft_base = (gw + u * NW) * kTile;       // first draft index of a draft tile
@@ -498,16 +528,19 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
         allowed[rt] = t_valid[u];
         if (t_draft[u]) allowed[rt] &= (uint32_t)(rmask[rt] >> (draft_base & 63));
       }
-      if (u & 1)
-        process_tile<RT, kStageBytes, false>(kaddr, vaddr, qf, allowed, all_visible, p.scale_log2, g, m_run,
-                                             l_run, oacc);
-      else if (u == 0)
-        process_tile<RT, 0, true>(kaddr, vaddr, qf, allowed, all_visible, p.scale_log2, g, m_run, l_run, oacc);
+      const uint32_t stage = (uint32_t)(uintptr_t)SVF_LDS_PTR(stage_ptr(u));
+      if (u == 0)
+        process_tile<RT, true>(stage, krel, vrel, qf, allowed, all_visible, p.scale_log2, g, m_run, l_run, oacc);
       else
-        process_tile<RT, 0, false>(kaddr, vaddr, qf, allowed, all_visible, p.scale_log2, g, m_run, l_run, oacc);
-      // refill this stage with the tile after next (all LDS reads of the stage have completed)
-      if (u + 2 < kMaxTiles && u + 2 < n_my)
-        issue_tile(t_off[u + 2 < kMaxTiles ? u + 2 : 0], my_lds + (u & 1) * kStageBytes);
+        process_tile<RT, false>(stage, krel, vrel, qf, allowed, all_visible, p.scale_log2, g, m_run, l_run, oacc);
+      // refill the stage just consumed with the tile two further on (its LDS reads have completed);
+      // the extra stage is never reused
+      if (u + 2 < kMaxTiles && u + 2 < n_my && !(own_x && u == 0)) {
+        int64_t a[8];
+        gather_tile(row_addr(t_off[u + 2 < kMaxTiles ? u + 2 : 0]), a);
+        issue_tile(a, stage_ptr(u));
+        n_issued = u + 3;
+      }
     }
   }
 
