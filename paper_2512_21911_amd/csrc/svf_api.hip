@@ -285,6 +285,8 @@ int svf_verify_attn(const svf_shape_t* shape, const void* q, const void* K, cons
   if ((shape->block_size & (shape->block_size - 1)) == 0)
     for (int sh = 0; sh < 31; ++sh)
       if ((1 << sh) == shape->block_size) p.block_shift = sh;
+  p.g_magic = (1ull << 32) / (uint64_t)p.G + 1ull;
+  p.hkv_magic = (1ull << 32) / (uint64_t)p.Hkv + 1ull;
   p.max_seq_len = shape->max_seq_len;
   const float scale = shape->sm_scale > 0.f ? shape->sm_scale : 1.0f / sqrtf((float)shape->d);
   p.scale_log2 = scale * 1.4426950408889634f;

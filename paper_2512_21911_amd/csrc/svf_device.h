@@ -73,6 +73,8 @@ struct AttnParams {
   uint64_t* tickets;           // [B][Hkv][row groups]   arrival counters, zero between calls
   int32_t B, gamma, Hq, Hkv, G, d, M, Mpad, block_size, k_blocks, n_splits, mask_per_batch, max_seq_len;
   int32_t block_shift;         // log2(block_size) if a power of two, else -1
+  uint64_t g_magic;            // floor(2^32 / G) + 1: n / G == (n * g_magic) >> 32 for n, G < 65536
+  uint64_t hkv_magic;          // the same for Hkv
   float scale_log2;            // sm_scale * log2(e)
 };
 
