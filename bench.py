@@ -30,6 +30,13 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 MEASURED_TRAFFIC_BYTES = {"cfg3_long_batch_32k": 41.2e6}
 
 
+def step_mode(cfg, layer):
+    """Anchor layers retrieve; the others reuse the anchor's blocks and its gather list (all
+    layers of a step share one page table and one set of sequence lengths)."""
+    import paper_2512_21911_amd as S
+    return S.SVF_STEP_ANCHOR if cfg.is_anchor(layer) else S.SVF_STEP_REUSE_GATHER
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,7 +112,7 @@ def main():
     # ---- the step -----------------------------------------------------------------------
     def step():
         for l, x in enumerate(layers):
-            S.svf_verify_step(shape, cfg.is_anchor(l), x["q"], reps[l], x["k_pool"], x["v_pool"], x["block_table"],
+            S.svf_verify_step(shape, step_mode(cfg, l), x["q"], reps[l], x["k_pool"], x["v_pool"], x["block_table"],
                               x["seq_lens"], x["k_draft"], x["v_draft"], x["draft_mask"], sel_idx, sel_cnt,
                               outs[l], ws)
 
@@ -217,7 +224,7 @@ def main():
             o = torch.empty_like(outs[0])
             S.svf_block_reps(shape, xg["k_pool"], xg["block_table"], xg["seq_lens"], r)
             # anchor layers retrieve into gi / gc; the following layers reuse them (Eq. 9)
-            S.svf_verify_step(shape, cfg.is_anchor(l), xg["q"], r, xg["k_pool"], xg["v_pool"], xg["block_table"],
+            S.svf_verify_step(shape, step_mode(cfg, l), xg["q"], r, xg["k_pool"], xg["v_pool"], xg["block_table"],
                               xg["seq_lens"], xg["k_draft"], xg["v_draft"], xg["draft_mask"], gi, gc, o, ws)
             torch.cuda.synchronize()
             if cfg.is_anchor(l) and not np.array_equal(gi.cpu().numpy(), idx):

@@ -144,11 +144,26 @@ int svf_verify_attn(const svf_shape_t* shape, const void* q, const void* K, cons
 
 /*
  * One layer of one verification step with inter-layer retrieval reuse (Sec. 3.3, Eq. 9).
- * do_select != 0 (anchor layer): svf_score_select into sel_idx / sel_cnt, then svf_verify_attn.
- * do_select == 0: svf_verify_attn with the sel_idx / sel_cnt the caller kept from the nearest
- * preceding anchor layer (reps may then be NULL).  KV head h reuses KV head h's set.
+ * mode SVF_STEP_ANCHOR (anchor layer): svf_score_select into sel_idx / sel_cnt, then
+ *   svf_verify_attn.  The call also leaves in `ws` a gather list: where in the cache pools the
+ *   selected rows of this block_table / seq_lens / layout sit.
+ * mode SVF_STEP_REUSE: svf_verify_attn with the sel_idx / sel_cnt the caller kept from the
+ *   nearest preceding anchor layer (reps may then be NULL).  KV head h reuses KV head h's set.
+ *   Nothing but the arguments is relied on.
+ * mode SVF_STEP_REUSE_GATHER: the same result, faster: the kernel reads the anchor call's gather
+ *   list instead of walking sel_idx and block_table again.  The caller promises that `ws`,
+ *   sel_idx, sel_cnt, block_table, seq_lens and every field of `shape` are those of the last
+ *   SVF_STEP_ANCHOR call on this `ws`, contents unchanged (K, V, q, the drafts and the outputs
+ *   may differ: the layers of one verification step share their page table).  A broken promise
+ *   gives attention over the anchor call's rows, never an access outside the pools it was built
+ *   for.  Shapes that have no gather list (anything but bf16 with d = 128 and block and page
+ *   sizes that are multiples of four, or more than 1024 kept blocks) take the SVF_STEP_REUSE path.
+ * Any other mode: SVF_ERR_SHAPE.
  */
-int svf_verify_step(const svf_shape_t* shape, int do_select, const void* q, const float* reps,
+#define SVF_STEP_REUSE 0
+#define SVF_STEP_ANCHOR 1
+#define SVF_STEP_REUSE_GATHER 2
+int svf_verify_step(const svf_shape_t* shape, int mode, const void* q, const float* reps,
                     const void* K, const void* V, const int32_t* block_table,
                     const int32_t* seq_lens, const void* k_draft, const void* v_draft,
                     const uint64_t* draft_mask_or_null, int32_t* sel_idx, int32_t* sel_cnt,

@@ -154,9 +154,12 @@ def svf_verify_attn(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, dra
                                  _stream()), "svf_verify_attn")
 
 
-def svf_verify_step(shape, do_select, q, reps, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask,
+SVF_STEP_REUSE, SVF_STEP_ANCHOR, SVF_STEP_REUSE_GATHER = 0, 1, 2
+
+
+def svf_verify_step(shape, mode, q, reps, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask,
                     sel_idx, sel_cnt, out, ws, lse=None):
-    _check(lib().svf_verify_step(ctypes.byref(shape), int(bool(do_select)), _ptr(q), _ptr(reps), _ptr(K), _ptr(V),
+    _check(lib().svf_verify_step(ctypes.byref(shape), int(mode), _ptr(q), _ptr(reps), _ptr(K), _ptr(V),
                                  _ptr(block_table), _ptr(seq_lens), _ptr(k_draft), _ptr(v_draft),
                                  _ptr(draft_mask), _ptr(sel_idx), _ptr(sel_cnt), _ptr(out), _ptr(lse),
                                  _ptr(ws), ws.numel(), _stream()), "svf_verify_step")

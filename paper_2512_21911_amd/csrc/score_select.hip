@@ -4,7 +4,7 @@
 // Two kernels.
 //   scores:  wide, HBM-bound pass over the fp32 representatives.  A group of d/4 lanes owns
 //            one block: float4 loads, fp32 dot with the group-mean first-draft query,
-//            butterfly reduction inside the lane group.
+//            reduction inside the lane group.
 //   select:  one workgroup per (sequence, KV head).  Scores become order-preserving 32-bit
 //            keys (forced sink/local blocks get the maximum key); a 4-pass radix select over
 //            LDS histograms (bins scanned with a wavefront prefix sum) finds the key of the
@@ -24,63 +24,51 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kKeysPerThread = 8;      // selection keys a thread keeps in registers
 constexpr int kPasses = 4;              // blocks scored per lane group in the scores kernel
 
-template <typename T>
-__device__ __forceinline__ float to_float(T x);
-template <>
-__device__ __forceinline__ float to_float<float>(float x) { return x; }
-template <>
-__device__ __forceinline__ float to_float<__hip_bfloat16>(__hip_bfloat16 x) { return __bfloat162float(x); }
-
 // grid: (ceil(nb_max / (kPasses * blocks per pass)), Hkv, B)
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void block_scores_kernel(SelectParams p) {
-  constexpr int LPB = D / 4;                 // lanes per block
+  constexpr int LPB = kScoreLanes;           // lanes per block
+  constexpr int NCH = D / (4 * LPB);         // 16-byte chunks per lane: sub, sub + 8, ...
   constexpr int BPW = kThreads / LPB;        // blocks per workgroup pass
-  __shared__ float q0[D];
+  __shared__ __attribute__((aligned(16))) float q0[D];
 
   const int b = blockIdx.z, h = blockIdx.y;
   const int G = p.Hq / p.Hkv;
   const int sub = threadIdx.x % LPB;
 
-  // The representative rows go out first and unconditionally (rows past the sequence's last block
-  // exist in the buffer; their result is discarded), so that they and the query share one memory
-  // round trip instead of queuing behind it.
-  float4 r[kPasses];
+  // All loads go out before anything waits, so that the query and the representatives share one
+  // memory round trip.  First draft token's query: channel threadIdx.x mod D of the group's heads
+  // (loaded by every thread, used by the first D); representative rows unconditionally (rows past
+  // the sequence's last block exist in the buffer; their result is discarded).
+  const T* qch = static_cast<const T*>(p.q) + ((int64_t)b * p.gamma * p.Hq + (int64_t)h * G) * D + threadIdx.x % D;
+  const QueryHeads<T> qh = load_query_heads<T>(qch, G, D);
+  float4 r[kPasses][NCH];
   int jj[kPasses];
 #pragma unroll
   for (int u = 0; u < kPasses; ++u) {
     const int j = (blockIdx.x * kPasses + u) * BPW + threadIdx.x / LPB;
     jj[u] = j;
     const int jc = j < p.nb_max ? j : p.nb_max - 1;
-    r[u] = *reinterpret_cast<const float4*>(p.reps + (((int64_t)b * p.Hkv + h) * p.nb_max + jc) * D + sub * 4);
+    const float* row = p.reps + (((int64_t)b * p.Hkv + h) * p.nb_max + jc) * D + sub * 4;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) r[u][i] = *reinterpret_cast<const float4*>(row + i * 4 * LPB);
   }
 
-  // first draft token's query, averaged over the query heads of this KV head
-  if (threadIdx.x < D) {
-    const T* q = static_cast<const T*>(p.q) + ((int64_t)b * p.gamma * p.Hq + (int64_t)h * G) * D + threadIdx.x;
-    float s = 0.f;
-    for (int g = 0; g < G; ++g) s += to_float<T>(q[(int64_t)g * D]);
-    q0[threadIdx.x] = s / (float)G;
-  }
+  // averaged over the query heads of this KV head
+  if (threadIdx.x < D) q0[threadIdx.x] = mean_query_channel<T>(qh, qch, G, D);
   const int L = clamped_len(p.seq_lens, b, p.max_seq_len);
   const int nb = (L + p.block_size - 1) / p.block_size;
   __syncthreads();
 
-  const float4 qv = make_float4(q0[sub * 4], q0[sub * 4 + 1], q0[sub * 4 + 2], q0[sub * 4 + 3]);
+  float4 qv[NCH];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) qv[i] = *reinterpret_cast<const float4*>(q0 + sub * 4 + i * 4 * LPB);
 #pragma unroll
   for (int u = 0; u < kPasses; ++u) {
-    float v = r[u].x * qv.x + r[u].y * qv.y + r[u].z * qv.z + r[u].w * qv.w;
-#pragma unroll
-    for (int o = LPB / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    const float v = block_score<NCH>(r[u], qv);
     if (sub == 0 && jj[u] < p.nb_max)
       p.scores[((int64_t)b * p.Hkv + h) * p.nb_max + jj[u]] = jj[u] < nb ? v + 0.0f : 0.0f;
   }
-}
-
-// Larger score <=> larger key; -0 and +0 map to the same key.
-__device__ __forceinline__ uint32_t score_key(float s) {
-  uint32_t u = __float_as_uint(s + 0.0f);
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
 // grid: (Hkv, B)
@@ -89,6 +77,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectParams p) {
   __shared__ uint32_t sh_prefix, sh_need;
   __shared__ uint32_t wave_eq[kWaves], wave_sel[kWaves];
   __shared__ uint32_t base_eq, base_sel;
+  __shared__ int32_t sh_sel[kMaxGatherBlocks];     // kept block ids, for the gather list
 
   const int b = blockIdx.y, h = blockIdx.x;
   const int tid = threadIdx.x;
@@ -171,7 +160,10 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectParams p) {
     __syncthreads();
     uint32_t pos = base_sel + (uint32_t)__popcll(m_sel & ((1ull << lane) - 1ull));
     for (int w = 0; w < wave; ++w) pos += wave_sel[w];
-    if (keep) out[pos] = j;
+    if (keep) {
+      out[pos] = j;
+      if (pos < (uint32_t)kMaxGatherBlocks) sh_sel[pos] = j;
+    }
     __syncthreads();
     if (tid == 0) {
       uint32_t e = 0, s = 0;
@@ -183,13 +175,34 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectParams p) {
   }
   for (int i = cnt + tid; i < p.k_blocks; i += kThreads) out[i] = -1;
   if (tid == 0) p.sel_cnt[(int64_t)b * p.Hkv + h] = cnt;
+
+  // Gather list: where the K row of every fourth selected-token slot sits in the pool, and how
+  // many of its four slots hold a real token.  (The last loop iteration ended with a barrier, so
+  // sh_sel is complete; block and page sizes are multiples of four, so the four slots share a
+  // block and a page.)
+  if (p.gather) {
+    uint64_t* gl = p.gather + ((int64_t)b * p.Hkv + h) * p.gather_groups;
+    for (int e = tid; e < p.gather_groups; e += kThreads) {
+      const int slot0 = 4 * e;
+      const int bi = slot0 / p.block_size;
+      uint64_t entry = 0;
+      if (bi < cnt) {
+        const int tok0 = sh_sel[bi] * p.block_size + (slot0 - bi * p.block_size);
+        const int nv = min(max(L - tok0, 0), 4);
+        if (nv > 0) {
+          const int64_t off = (token_offset(p.kv, p.table, b, tok0) + (int64_t)h * p.kv.stride_head) * 2;
+          entry = ((uint64_t)off & kGatherOffsetMask) | ((uint64_t)nv << kGatherCountShift);
+        }
+      }
+      gl[e] = entry;
+    }
+  }
 }
 
 }  // namespace
 
 hipError_t launch_score_select(const SelectParams& p, int dtype, hipStream_t st) {
-  const int lpb = p.d / 4;
-  const int bpw = kPasses * (kThreads / lpb);
+  const int bpw = kPasses * (kThreads / kScoreLanes);
   dim3 g1((p.nb_max + bpw - 1) / bpw, p.Hkv, p.B);
   if (dtype == SVF_F32) {
     if (p.d == 64) hipLaunchKernelGGL((block_scores_kernel<float, 64>), g1, dim3(kThreads), 0, st, p);

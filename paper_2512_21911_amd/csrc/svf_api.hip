@@ -76,7 +76,7 @@ int hip_code(hipError_t e) { return e == hipSuccess ? SVF_OK : SVF_ERR_HIP; }
 
 }  // namespace
 
-// Workspace layout: [tickets | partial o | partial m | partial l | scores]
+// Workspace layout: [tickets | partial o | partial m | partial l | gather list | scores]
 AttnPlan plan_attn(const svf_shape_t& s) {
   AttnPlan pl;
   const int G = s.Hq / s.Hkv;
@@ -104,6 +104,11 @@ AttnPlan plan_attn(const svf_shape_t& s) {
   pl.off_m = off;
   pl.off_l = off + pairs * pl.n_splits * pl.Mpad * sizeof(float);
   off += align_up(2 * pairs * pl.n_splits * pl.Mpad * sizeof(float));
+  pl.gather = pl.mfma && s.k_blocks <= kMaxGatherBlocks;
+  pl.fused_select = pl.gather && nb_max_of(s) <= kMaxGatherBlocks;
+  pl.gather_groups = pl.gather ? (int32_t)(((int64_t)s.k_blocks * s.block_size + 31) / 32 * 8) : 0;
+  pl.off_gather = off;
+  off += align_up(pairs * (size_t)pl.gather_groups * sizeof(uint64_t));
   pl.bytes = off;
   return pl;
 }
@@ -202,9 +207,12 @@ int svf_block_reps(const svf_shape_t* shape, const void* K, const int32_t* block
   return hip_code(launch_block_reps(p, shape->dtype, shape->B, static_cast<hipStream_t>(stream)));
 }
 
-int svf_score_select(const svf_shape_t* shape, const void* q, const float* reps,
-                     const int32_t* seq_lens, int32_t* sel_idx, int32_t* sel_cnt,
-                     float* scores_or_null, void* ws, size_t ws_bytes, void* stream) {
+// block_table given (or the cache unpaged) and with_gather: the selection also leaves its gather
+// list in the workspace
+static int score_select_impl(const svf_shape_t* shape, const void* q, const float* reps,
+                             const int32_t* seq_lens, int32_t* sel_idx, int32_t* sel_cnt,
+                             float* scores_or_null, void* ws, size_t ws_bytes, void* stream,
+                             bool with_gather, const int32_t* block_table) {
   int rc = check_shape(shape);
   if (rc) return rc;
   if (!q || !reps || !seq_lens || !sel_idx || !sel_cnt) return SVF_ERR_NULL;
@@ -230,14 +238,28 @@ int svf_score_select(const svf_shape_t* shape, const void* q, const float* reps,
   p.n_sink = shape->n_sink;
   p.n_local = shape->n_local;
   p.max_seq_len = shape->max_seq_len;
+  const AttnPlan pl = plan_attn(*shape);
+  p.gather = nullptr;
+  p.table = block_table;
+  p.kv = layout_of(*shape);
+  p.gather_groups = pl.gather_groups;
+  if (with_gather && pl.gather) p.gather = reinterpret_cast<uint64_t*>(static_cast<char*>(ws) + pl.off_gather);
   return hip_code(launch_score_select(p, shape->dtype, static_cast<hipStream_t>(stream)));
 }
 
-int svf_verify_attn(const svf_shape_t* shape, const void* q, const void* K, const void* V,
-                    const int32_t* block_table, const int32_t* seq_lens, const void* k_draft,
-                    const void* v_draft, const uint64_t* draft_mask_or_null, const int32_t* sel_idx,
-                    const int32_t* sel_cnt, void* out, float* lse_or_null, void* ws, size_t ws_bytes,
-                    void* stream) {
+int svf_score_select(const svf_shape_t* shape, const void* q, const float* reps,
+                     const int32_t* seq_lens, int32_t* sel_idx, int32_t* sel_cnt,
+                     float* scores_or_null, void* ws, size_t ws_bytes, void* stream) {
+  return score_select_impl(shape, q, reps, seq_lens, sel_idx, sel_cnt, scores_or_null, ws, ws_bytes, stream,
+                           false, nullptr);
+}
+
+// use_gather: the workspace holds the gather list of exactly this sel_idx / block_table / seq_lens
+static int verify_attn_impl(const svf_shape_t* shape, const void* q, const void* K, const void* V,
+                            const int32_t* block_table, const int32_t* seq_lens, const void* k_draft,
+                            const void* v_draft, const uint64_t* draft_mask_or_null, const int32_t* sel_idx,
+                            const int32_t* sel_cnt, void* out, float* lse_or_null, void* ws, size_t ws_bytes,
+                            void* stream, bool use_gather, const float* reps_to_select_from = nullptr) {
   int rc = check_shape(shape);
   if (rc) return rc;
   if (!q || !K || !V || !seq_lens || !k_draft || !v_draft || !sel_idx || !sel_cnt || !out ||
@@ -269,6 +291,23 @@ int svf_verify_attn(const svf_shape_t* shape, const void* q, const void* K, cons
   p.part_m = reinterpret_cast<float*>(w + pl.off_m);
   p.part_l = reinterpret_cast<float*>(w + pl.off_l);
   p.part_ml = p.part_m;
+  p.gather = (use_gather && pl.gather) ? reinterpret_cast<const uint64_t*>(w + pl.off_gather) : nullptr;
+  p.gather_groups = pl.gather_groups;
+  // retrieval inside the kernel: sel_idx / sel_cnt are then outputs (the caller passed them writable)
+  p.reps = nullptr;
+  p.sel_idx_out = nullptr;
+  p.sel_cnt_out = nullptr;
+  p.gather_out = nullptr;
+  p.nb_max = nb_max_of(*shape);
+  p.n_sink = shape->n_sink;
+  p.n_local = shape->n_local;
+  if (reps_to_select_from && pl.fused_select) {
+    p.reps = reps_to_select_from;
+    p.sel_idx_out = const_cast<int32_t*>(sel_idx);
+    p.sel_cnt_out = const_cast<int32_t*>(sel_cnt);
+    p.gather_out = reinterpret_cast<uint64_t*>(w + pl.off_gather);
+    p.gather = nullptr;
+  }
   p.B = shape->B;
   p.gamma = shape->gamma;
   p.Hq = shape->Hq;
@@ -295,12 +334,23 @@ int svf_verify_attn(const svf_shape_t* shape, const void* q, const void* K, cons
   return hip_code(launch_verify_attn_valu(p, shape->dtype, st));
 }
 
-int svf_verify_step(const svf_shape_t* shape, int do_select, const void* q, const float* reps,
+int svf_verify_attn(const svf_shape_t* shape, const void* q, const void* K, const void* V,
+                    const int32_t* block_table, const int32_t* seq_lens, const void* k_draft,
+                    const void* v_draft, const uint64_t* draft_mask_or_null, const int32_t* sel_idx,
+                    const int32_t* sel_cnt, void* out, float* lse_or_null, void* ws, size_t ws_bytes,
+                    void* stream) {
+  return verify_attn_impl(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask_or_null, sel_idx,
+                          sel_cnt, out, lse_or_null, ws, ws_bytes, stream, false);
+}
+
+int svf_verify_step(const svf_shape_t* shape, int mode, const void* q, const float* reps,
                     const void* K, const void* V, const int32_t* block_table, const int32_t* seq_lens,
                     const void* k_draft, const void* v_draft, const uint64_t* draft_mask_or_null,
                     int32_t* sel_idx, int32_t* sel_cnt, void* out, float* lse_or_null, void* ws,
                     size_t ws_bytes, void* stream) {
   // validate everything both halves need before enqueuing the first one
+  if (mode != SVF_STEP_REUSE && mode != SVF_STEP_ANCHOR && mode != SVF_STEP_REUSE_GATHER) return SVF_ERR_SHAPE;
+  const bool do_select = mode == SVF_STEP_ANCHOR;
   int rc = check_shape(shape);
   if (rc) return rc;
   if (!q || !K || !V || !seq_lens || !k_draft || !v_draft || !sel_idx || !sel_cnt || !out ||
@@ -311,12 +361,16 @@ int svf_verify_step(const svf_shape_t* shape, int do_select, const void* q, cons
     return SVF_ERR_SHAPE;
   rc = check_ws(shape, ws, ws_bytes);
   if (rc) return rc;
+  if (do_select && plan_attn(*shape).fused_select)
+    return verify_attn_impl(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask_or_null, sel_idx,
+                            sel_cnt, out, lse_or_null, ws, ws_bytes, stream, false, reps);
   if (do_select) {
-    rc = svf_score_select(shape, q, reps, seq_lens, sel_idx, sel_cnt, nullptr, ws, ws_bytes, stream);
+    rc = score_select_impl(shape, q, reps, seq_lens, sel_idx, sel_cnt, nullptr, ws, ws_bytes, stream, true,
+                           block_table);
     if (rc) return rc;
   }
-  return svf_verify_attn(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask_or_null,
-                         sel_idx, sel_cnt, out, lse_or_null, ws, ws_bytes, stream);
+  return verify_attn_impl(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask_or_null, sel_idx,
+                          sel_cnt, out, lse_or_null, ws, ws_bytes, stream, mode != SVF_STEP_REUSE);
 }
 
 }  // extern "C"

@@ -1,6 +1,7 @@
 // Internal declarations shared by the libsvf translation units (not part of the C ABI).
 #pragma once
 
+#include <hip/hip_bf16.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -42,6 +43,16 @@ struct RepsParams {
   int32_t Hkv, d, block_size, nb_max, first_block, n_blocks, max_seq_len;
 };
 
+// Gather list (an optional by-product of block selection that the matrix-core attention kernel
+// can consume instead of walking sel_idx and the page table itself): for every (sequence, KV
+// head), entry e describes the four consecutive selected-token slots 4e .. 4e+3 (slot = position
+// in the concatenation of the kept blocks): bits [55:0] = byte offset of the first slot's K row
+// from the start of the K pool (head offset included; V uses the same offset in its pool),
+// bits [58:56] = number of those slots that hold a real token (0..4, a prefix of the four).
+constexpr int kGatherCountShift = 56;
+constexpr uint64_t kGatherOffsetMask = (1ull << kGatherCountShift) - 1ull;
+constexpr int kMaxGatherBlocks = 1024;   // block budgets above this do without a gather list
+
 struct SelectParams {
   const void* q;            // [B][gamma][Hq][d]
   const float* reps;        // [B][Hkv][nb_max][d]
@@ -50,6 +61,11 @@ struct SelectParams {
   int32_t* sel_idx;         // [B][Hkv][k]
   int32_t* sel_cnt;         // [B][Hkv]
   int32_t B, gamma, Hq, Hkv, d, block_size, nb_max, k_blocks, n_sink, n_local, max_seq_len;
+  // optional gather list output (NULL: none); needs the cache addressing of the layer
+  uint64_t* gather;         // [B][Hkv][gather_groups]
+  const int32_t* table;
+  KvLayout kv;
+  int32_t gather_groups;
 };
 
 struct AttnParams {
@@ -71,6 +87,14 @@ struct AttnParams {
   float* part_l;               // [B][Hkv][S][Mpad]      partial denominators
   float* part_ml;              // [B][Hkv][S][Mpad][2]   (maximum, denominator) pairs; aliases part_m / part_l
   uint64_t* tickets;           // [B][Hkv][row groups]   arrival counters, zero between calls
+  const uint64_t* gather;      // [B][Hkv][gather_groups] gather list matching sel_idx, or NULL
+  int32_t gather_groups;
+  // in-kernel retrieval (matrix-core kernel on anchor layers): reps != NULL switches it on
+  const float* reps;           // [B][Hkv][nb_max][d]
+  int32_t* sel_idx_out;        // [B][Hkv][k_blocks]
+  int32_t* sel_cnt_out;        // [B][Hkv]
+  uint64_t* gather_out;        // [B][Hkv][gather_groups]
+  int32_t nb_max, n_sink, n_local;
   int32_t B, gamma, Hq, Hkv, G, d, M, Mpad, block_size, k_blocks, n_splits, mask_per_batch, max_seq_len;
   int32_t block_shift;         // log2(block_size) if a power of two, else -1
   uint64_t g_magic;            // floor(2^32 / G) + 1: n / G == (n * g_magic) >> 32 for n, G < 65536
@@ -85,6 +109,71 @@ __device__ __forceinline__ int clamped_len(const int32_t* __restrict__ seq_lens,
   return L < 0 ? 0 : (L > max_seq_len ? max_seq_len : L);
 }
 
+// ---- block scores (Sec. 3.1, Eq. 5): pieces shared by the stand-alone scores kernel and the
+// attention kernel that retrieves for itself, so that both produce the same bits ---------------
+
+// Larger score <=> larger key; -0 and +0 map to the same key.
+__device__ __forceinline__ uint32_t score_key(float s) {
+  uint32_t u = __float_as_uint(s + 0.0f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Eight consecutive lanes own one block: lane s of the group holds the 16-byte channel chunks
+// s, s + 8, s + 16, ... of the representative (so that each load instruction of the group covers
+// 128 contiguous bytes).  Sum over the group, every lane receiving the total; fixed pairing
+// lane ^ 1, lane ^ 2, mirror inside 8, all three cross-lane operand modifiers of the add itself.
+constexpr int kScoreLanes = 8;
+__device__ __forceinline__ float lane8_sum(float v) {
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, true));    // quad_perm [1,0,3,2]
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, true));    // quad_perm [2,3,0,1]
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, true));   // row_half_mirror
+  return v;
+}
+
+// q0 . representative for this lane's chunks, then over the lane group: a fixed chain of fused
+// multiply-adds followed by lane8_sum.  NCH = d / 32 chunks per lane.
+template <int NCH>
+__device__ __forceinline__ float block_score(const float4 (&r)[NCH], const float4 (&q)[NCH]) {
+  float acc = r[0].x * q[0].x;
+  acc = __builtin_fmaf(r[0].y, q[0].y, acc);
+  acc = __builtin_fmaf(r[0].z, q[0].z, acc);
+  acc = __builtin_fmaf(r[0].w, q[0].w, acc);
+#pragma unroll
+  for (int i = 1; i < NCH; ++i) {
+    acc = __builtin_fmaf(r[i].x, q[i].x, acc);
+    acc = __builtin_fmaf(r[i].y, q[i].y, acc);
+    acc = __builtin_fmaf(r[i].z, q[i].z, acc);
+    acc = __builtin_fmaf(r[i].w, q[i].w, acc);
+  }
+  return lane8_sum(acc);
+}
+
+__device__ __forceinline__ float query_value(float x) { return x; }
+__device__ __forceinline__ float query_value(__hip_bfloat16 x) { return __bfloat162float(x); }
+
+// Channel c of the first draft token's query averaged over the G query heads of a KV head:
+// heads added in order, then one division.  q points at channel c of the group's first head,
+// heads are D elements apart.  In two steps so that a caller can put other loads between the
+// (unconditional) loads of the first eight heads and the arithmetic that waits for them.
+template <typename T>
+struct QueryHeads { T v[8]; };
+template <typename T>
+__device__ __forceinline__ QueryHeads<T> load_query_heads(const T* q, int G, int D) {
+  QueryHeads<T> h;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) h.v[u] = q[(int64_t)min(u, G - 1) * D];
+  return h;
+}
+template <typename T>
+__device__ __forceinline__ float mean_query_channel(const QueryHeads<T>& h, const T* q, int G, int D) {
+  float s = 0.f;
+#pragma unroll
+  for (int u = 0; u < 8; ++u)
+    if (u < G) s += query_value(h.v[u]);
+  for (int g = 8; g < G; ++g) s += query_value(q[(int64_t)g * D]);
+  return s / (float)G;
+}
+
 // Launchers (each validates nothing: the C ABI layer has already done so).
 hipError_t launch_block_reps(const RepsParams& p, int dtype, int B, hipStream_t st);
 hipError_t launch_score_select(const SelectParams& p, int dtype, hipStream_t st);
@@ -94,7 +183,10 @@ hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st);
 struct AttnPlan {
   int32_t M, Mpad, n_splits;
   bool mfma;                 // bf16, d = 128: matrix-core kernel; otherwise the vector-ALU kernel
-  size_t off_o, off_m, off_l, off_tickets, bytes;
+  bool fused_select;         // anchor layers retrieve inside the attention kernel
+  bool gather;               // the shape can use a gather list
+  int32_t gather_groups;     // entries per (sequence, KV head): a whole number of 32-token tiles
+  size_t off_o, off_m, off_l, off_tickets, off_gather, bytes;
 };
 AttnPlan plan_attn(const svf_shape_t& s);
 

@@ -311,6 +311,94 @@ __device__ __forceinline__ void merge_splits(const AttnParams& p, int64_t g_row,
   }
 }
 
+// Where the kernel learns which rows to fetch.
+constexpr int kResolve = 0;   // sel_idx / sel_cnt in memory, page table walked per tile
+constexpr int kGather = 1;    // gather list left behind by an earlier selection
+constexpr int kSelect = 2;    // the workgroup retrieves for itself (scores + top-N), then as kResolve
+
+constexpr int kMaxSelectBlocks = 1024;   // blocks per sequence the in-kernel retrieval handles
+
+// Inclusive prefix sum over the 64 lanes with cross-lane operand modifiers only: shifts by
+// 1, 2, 4, 8 inside each row of 16 lanes (lanes without a source add zero), then the last lane
+// of row 0 / row 2 into rows 1 / 3, then the last lane of row 1 into rows 2 and 3.
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x) {
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, true);   // row_shr:1
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, true);   // row_shr:2
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, true);   // row_shr:4
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, true);   // row_shr:8
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);  // row_bcast:15 -> rows 1, 3
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);  // row_bcast:31 -> rows 2, 3
+  return x;
+}
+
+// Top-cnt of keys[0 .. nb) by the whole workgroup (Sec. 3.1 top-N rule; equal keys: lowest index
+// first).  nb <= kMaxSelectBlocks = 2 * kThreads, so a thread holds keys tid and tid + kThreads.
+// Four 8-bit radix passes find the key of the weakest kept block: LDS histogram (one per pass,
+// zeroed by the caller), one barrier, then every wavefront scans the 256 bins for itself (four
+// bins per lane, wavefront prefix sum), so no second barrier is needed to share the outcome.
+// The final placement needs one more barrier: position of a kept block = blocks above the
+// threshold before it + min(equal blocks before it, equal blocks wanted).  sel[0 .. cnt) ends up
+// ascending.  Requires 1 <= cnt <= nb; all threads of the workgroup must call.
+struct SelectScratch {
+  uint32_t hist[4][256];
+  uint32_t seg[2 * kWaves][2];     // per (round, wavefront): blocks above / equal to the threshold
+};
+__device__ __forceinline__ void workgroup_select(const uint32_t* keys, SelectScratch* sc, int nb, int cnt,
+                                                 int32_t* sel, int tid, int lane, int wave) {
+  const bool has0 = tid < nb, has1 = tid + kThreads < nb;
+  const uint32_t k0 = has0 ? keys[tid] : 0u, k1 = has1 ? keys[tid + kThreads] : 0u;
+  uint32_t prefix = 0, need = (uint32_t)cnt;
+#pragma unroll
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+    if (has0 && (k0 & hi_mask) == prefix) atomicAdd(&sc->hist[pass][(k0 >> shift) & 0xff], 1u);
+    if (has1 && (k1 & hi_mask) == prefix) atomicAdd(&sc->hist[pass][(k1 >> shift) & 0xff], 1u);
+    __syncthreads();
+    // lane l owns bins 255 - 4l (in .w) down to 252 - 4l (in .x): higher bins in lower lanes
+    const uint4 hq = *reinterpret_cast<const uint4*>(&sc->hist[pass][252 - 4 * lane]);
+    const uint32_t own = hq.x + hq.y + hq.z + hq.w;
+    const uint32_t incl = wave_inclusive_sum(own);
+    uint32_t run = incl - own;                      // keys in bins above this lane's
+    const bool cross = incl >= need && run < need;  // exactly one lane
+    uint32_t bin = 255u - 4u * (uint32_t)lane;
+    if (run + hq.w < need) {
+      run += hq.w; --bin;
+      if (run + hq.z < need) {
+        run += hq.z; --bin;
+        if (run + hq.y < need) { run += hq.y; --bin; }
+      }
+    }
+    const int src = __builtin_ctzll(__ballot(cross));
+    prefix |= (uint32_t)__builtin_amdgcn_readlane((int)bin, src) << shift;
+    need -= (uint32_t)__builtin_amdgcn_readlane((int)run, src);   // still wanted from inside that bin
+  }
+  const uint32_t tau = prefix;
+  const uint64_t below = (1ull << lane) - 1ull;
+  const uint64_t gt0 = __ballot(has0 && k0 > tau), eq0 = __ballot(has0 && k0 == tau);
+  const uint64_t gt1 = __ballot(has1 && k1 > tau), eq1 = __ballot(has1 && k1 == tau);
+  if (lane == 0) {
+    sc->seg[wave][0] = (uint32_t)__popcll(gt0);
+    sc->seg[wave][1] = (uint32_t)__popcll(eq0);
+    sc->seg[kWaves + wave][0] = (uint32_t)__popcll(gt1);
+    sc->seg[kWaves + wave][1] = (uint32_t)__popcll(eq1);
+  }
+  __syncthreads();
+  uint32_t gt_before = 0, eq_before = 0;             // over the segments in front of (round 0, this wavefront)
+  for (int w = 0; w < wave; ++w) { gt_before += sc->seg[w][0]; eq_before += sc->seg[w][1]; }
+  {
+    const uint32_t e = eq_before + (uint32_t)__popcll(eq0 & below);
+    const bool is_gt = (gt0 >> lane) & 1ull, is_eq = (eq0 >> lane) & 1ull;
+    if (is_gt || (is_eq && e < need)) sel[gt_before + (uint32_t)__popcll(gt0 & below) + min(e, need)] = tid;
+  }
+  if (nb > kThreads) {
+    for (int w = wave; w < kWaves + wave; ++w) { gt_before += sc->seg[w][0]; eq_before += sc->seg[w][1]; }
+    const uint32_t e = eq_before + (uint32_t)__popcll(eq1 & below);
+    const bool is_gt = (gt1 >> lane) & 1ull, is_eq = (eq1 >> lane) & 1ull;
+    if (is_gt || (is_eq && e < need)) sel[gt_before + (uint32_t)__popcll(gt1 & below) + min(e, need)] = tid + kThreads;
+  }
+}
+
 // What the main loop has to know about a tile whose loads have been issued.
 struct TileInfo {
   uint32_t valid;      // bit s set: slot s holds a real token
@@ -321,6 +409,15 @@ struct TileInfo {
 // Workgroups are handed to the XCDs round-robin in x-fastest order and gridDim.x is a multiple
 // of kXcds, so blockIdx.x mod kXcds names the XCD: all splits and all row groups of a pair
 // share it (the second reader of a pair's K/V finds them in that XCD's L2).
+// MODE kGather: the addresses of the selected rows come from the gather list that an earlier
+// selection left behind (one load, issued together with the query loads) instead of the chain
+// sel_idx -> page table -> address.
+// MODE kSelect (anchor layers, Sec. 3.3): every workgroup first retrieves for its (sequence, KV
+// head) itself: block scores from the representatives (Eq. 5), then the top-N rule, both in
+// LDS; the workgroups of a pair repeat this work (they share an XCD, so the representatives
+// come out of its L2 after the first), which costs less than two more launches.  The result is
+// written to sel_idx / sel_cnt and, tile by tile, to the gather list for the layers that reuse it.
+template <int MODE>
 __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p, int pairs) {
   // one stage per wavefront, plus one for draft tile 0 (its owner then streams its cache tile
   // at the same time); after the main loop stage w becomes wavefront w's fp32 output buffer
@@ -328,6 +425,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   __shared__ float sm_m[kWaves][32];
   __shared__ float sm_l[kWaves][32];
   __shared__ int sm_last;
+  __shared__ int32_t s_sel[MODE == kSelect ? kMaxSelectBlocks : 1];   // kept blocks, ascending
 
   const int split = blockIdx.x / kXcds;
   const int pair = blockIdx.y * kXcds + blockIdx.x % kXcds;
@@ -349,7 +447,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   const char* Vc = static_cast<const char*>(p.V);
   const char* Kd = static_cast<const char*>(p.k_draft);
   const char* Vd = static_cast<const char*>(p.v_draft);
-  const int32_t* __restrict__ sel = p.sel_idx + (int64_t)pair * p.k_blocks;
+  const int32_t* __restrict__ sel_g = p.sel_idx + (int64_t)pair * p.k_blocks;
 
   // ---- this lane's query row as B operands (issued first: vector loads complete in order, so
   // a wait for these must not have the K/V stream in front of it), and the row's draft mask ----
@@ -360,6 +458,12 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     qi = (int)(((uint64_t)(uint32_t)row * p.g_magic) >> 32);            // row / G
     qj = row - qi * p.G;
   }
+  // (retrieval only) channel tid of the group's mean first-draft query: first in the queue, so
+  // that nothing slower has to come back before it
+  const __hip_bfloat16* const q0ch =
+      static_cast<const __hip_bfloat16*>(p.q) + ((int64_t)b * p.gamma * p.Hq + (int64_t)h * p.G) * kD + (tid & (kD - 1));
+  QueryHeads<__hip_bfloat16> q0h;
+  if (MODE == kSelect) q0h = load_query_heads<__hip_bfloat16>(q0ch, p.G, kD);
   bf16x8 qf[8];
   {
     const __hip_bfloat16* qrow = static_cast<const __hip_bfloat16*>(p.q) +
@@ -370,8 +474,76 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   uint64_t rmask = 0;
   if (p.draft_mask) rmask = p.draft_mask[p.mask_per_batch ? (int64_t)b * p.gamma + qi : qi];
 
-  const int L = clamped_len(p.seq_lens, b, p.max_seq_len);
-  const int cnt = min(max(p.sel_cnt[pair], 0), p.k_blocks);
+  // gather entries of this wavefront's tiles: lane 8u + n holds group n of its u-th tile
+  uint64_t gent = 0;
+  if (MODE == kGather) {
+    const int tc = gw + (lane >> 3) * NW - tiles_d;          // cache tile index
+    const int e = tc * 8 + (lane & 7);
+    if (lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups) gent = p.gather[(int64_t)pair * p.gather_groups + e];
+  }
+  int L = 0;
+  if (MODE != kGather) L = clamped_len(p.seq_lens, b, p.max_seq_len);
+  int cnt;
+  if (MODE == kSelect) {
+    // ---- retrieval: q0 = mean first-draft query of the group, key[j] = order-preserving key of
+    // q0 . rep[j] (forced sink / local blocks get the largest key), top-cnt by wavefront 0.
+    // The scratch arrays live in stage 0, which nobody streams into before the last barrier.
+    float* s_q0 = reinterpret_cast<float*>(smem);
+    uint32_t* s_keys = reinterpret_cast<uint32_t*>(smem + kD * 4);
+    SelectScratch* s_sc = reinterpret_cast<SelectScratch*>(smem + kD * 4 + kMaxSelectBlocks * 4);
+    const int nb = (L + p.block_size - 1) / p.block_size;
+    cnt = min(p.k_blocks, nb);
+    constexpr int kNch = kD / (4 * kScoreLanes);       // 16-byte chunks of a representative per lane
+    constexpr int kBatch = 8;                          // passes (of 64 blocks) in flight
+    const int sub = tid % kScoreLanes, jrow = tid / kScoreLanes;
+    const float* rp = p.reps + (int64_t)pair * p.nb_max * kD + sub * 4;
+    // the workgroups of a pair walk the same rows: each starts at another pass, so that they do
+    // not all queue at the same memory channel
+    const int rot = (split + rg * p.n_splits) % kBatch;
+    float4 r[kBatch][kNch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {                 // first batch goes out with the query loads
+      const float* row = rp + (int64_t)min(((u + rot) % kBatch) * 64 + jrow, p.nb_max - 1) * kD;
+#pragma unroll
+      for (int i = 0; i < kNch; ++i) r[u][i] = *reinterpret_cast<const float4*>(row + i * 4 * kScoreLanes);
+    }
+    if (tid < kD) s_q0[tid] = mean_query_channel<__hip_bfloat16>(q0h, q0ch, p.G, kD);
+    for (int i = tid; i < 4 * 256; i += kThreads) (&s_sc->hist[0][0])[i] = 0;
+    __syncthreads();
+    float4 qv[kNch];
+#pragma unroll
+    for (int i = 0; i < kNch; ++i) qv[i] = *reinterpret_cast<const float4*>(s_q0 + sub * 4 + i * 4 * kScoreLanes);
+    for (int j0 = 0; j0 < nb; j0 += 64 * kBatch) {
+      float v[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) v[u] = block_score<kNch>(r[u], qv);
+      if (j0 + 64 * kBatch < nb) {
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+          const float* row = rp + (int64_t)min(j0 + 64 * kBatch + ((u + rot) % kBatch) * 64 + jrow, p.nb_max - 1) * kD;
+#pragma unroll
+          for (int i = 0; i < kNch; ++i) r[u][i] = *reinterpret_cast<const float4*>(row + i * 4 * kScoreLanes);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int j = j0 + ((u + rot) % kBatch) * 64 + jrow;
+        if (sub == 0 && j < nb)
+          s_keys[j] = (j < p.n_sink || j >= nb - p.n_local) ? 0xffffffffu : score_key(v[u] + 0.0f);
+      }
+    }
+    __syncthreads();
+    if (cnt > 0) workgroup_select(s_keys, s_sc, nb, cnt, s_sel, tid, lane, wave);
+    __syncthreads();
+    // one workgroup of the pair publishes the selection (the one with the least other work)
+    if (split == p.n_splits - 1 && rg == 0) {
+      int32_t* out_idx = p.sel_idx_out + (int64_t)pair * p.k_blocks;
+      for (int i = tid; i < p.k_blocks; i += kThreads) out_idx[i] = i < cnt ? s_sel[i] : -1;
+      if (tid == 0) p.sel_cnt_out[pair] = cnt;
+    }
+  } else {
+    cnt = min(max(p.sel_cnt[pair], 0), p.k_blocks);
+  }
   const int n_prefix = cnt * p.block_size;
   const int tiles = tiles_d + (n_prefix + kTile - 1) / kTile;
   int n_my = 0;
@@ -392,15 +564,16 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   const int32_t* const table_b = p.table + (int64_t)b * p.kv.max_pages;
   const int64_t orow_pair = (int64_t)b * p.gamma * p.Hq + h * p.G;      // output row of (draft 0, head 0)
 
-  // Resolves the addresses of tile t and issues its 16 loads into the stage at `dst`.
-  // Lane (n = lane & 7) resolves the group of slots 4n .. 4n+3; the groups' bases then move to
-  // scalar registers.  Rows that do not exist (past the drafts, past the kept blocks, past the
+  // Resolves the addresses of tile t (the wavefront's u-th) and issues its 16 loads into the
+  // stage at `dst`.  Lane 8u + n resolves the group of slots 4n .. 4n+3 (without a gather list
+  // every lane with lane & 7 == n does); the groups' bases then move to scalar registers.  Rows that do not exist (past the drafts, past the kept blocks, past the
   // sequence's end) are redirected to the nearest valid row of their group, or, if the whole
   // group is void, to the first draft row (finite, always mapped); they are masked out of the
   // softmax through `valid`.
-  auto issue_tile = [&](int t, unsigned char* dst) -> TileInfo {
+  auto issue_tile = [&](int t, int u, unsigned char* dst) -> TileInfo {
     TileInfo ti;
     const int n8 = lane & 7;
+    const int src0 = __builtin_amdgcn_readfirstlane(8 * u);
     int nv;                         // valid rows in this lane's group (0..4)
     int64_t base;                   // byte address of the group's first K row
     bool from_draft;
@@ -412,12 +585,18 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       from_draft = true;
       row_bytes = drow_bytes;
       ti.draft_base = t * kTile;
+    } else if (MODE == kGather) {
+      nv = (int)(gent >> kGatherCountShift);
+      base = nv > 0 ? (int64_t)(uintptr_t)Kc + (int64_t)(gent & kGatherOffsetMask) : (int64_t)(uintptr_t)kd_pair;
+      from_draft = nv == 0;
+      row_bytes = tok_bytes;
+      ti.draft_base = -1;
     } else {
       const int slot0 = (t - tiles_d) * kTile + 4 * n8;
       const bool in_range = slot0 < n_prefix;
       const int sl = in_range ? slot0 : 0;
       const int bi = p.block_shift >= 0 ? sl >> p.block_shift : sl / p.block_size;
-      const int blk = sel[bi];
+      const int blk = MODE == kSelect ? s_sel[bi] : sel_g[bi];
       const int tok0 = blk * p.block_size + (sl - bi * p.block_size);
       nv = (in_range && blk >= 0) ? min(max(min(n_prefix - slot0, L - tok0), 0), 4) : 0;
       const int tk = nv > 0 ? tok0 : 0;
@@ -430,22 +609,27 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
         sl_in_page = tk - pg * p.kv.page_size;
         phys = nv > 0 ? table_b[pg] : 0;
       }
-      const int64_t off = ((int64_t)phys * p.kv.stride_page + (int64_t)sl_in_page * p.kv.stride_tok) * 2;
-      base = nv > 0 ? (int64_t)(uintptr_t)kc_pair + off : (int64_t)(uintptr_t)kd_pair;
+      // byte offset of the group's first K row from the start of the pool
+      const int64_t off = (kc_pair - Kc) + ((int64_t)phys * p.kv.stride_page + (int64_t)sl_in_page * p.kv.stride_tok) * 2;
+      base = nv > 0 ? (int64_t)(uintptr_t)Kc + off : (int64_t)(uintptr_t)kd_pair;
       from_draft = nv == 0;
       row_bytes = tok_bytes;
       ti.draft_base = -1;
+      // the tile's part of the gather list, for the layers that reuse this selection
+      if (MODE == kSelect && rg == 0 && lane < 8)
+        p.gather_out[(int64_t)pair * p.gather_groups + (t - tiles_d) * 8 + n8] =
+            nv > 0 ? (((uint64_t)off & kGatherOffsetMask) | ((uint64_t)nv << kGatherCountShift)) : 0ull;
     }
     // slot validity: slot s is valid iff (s mod 4) < nv of group s / 4
-    const int nv_s = __shfl(nv, l32 >> 2, 64);
+    const int nv_s = __shfl(nv, src0 + (l32 >> 2), 64);
     ti.valid = (uint32_t)__ballot((l32 & 3) < nv_s);
     unsigned char* vdst = dst + kTileBytes;
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
-      const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)base, n);
-      const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)((uint64_t)base >> 32), n);
-      const int nvn = __builtin_amdgcn_readlane(nv, n);
-      const bool fd = __builtin_amdgcn_readlane((int)from_draft, n) != 0;
+      const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)base, src0 + n);
+      const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)((uint64_t)base >> 32), src0 + n);
+      const int nvn = __builtin_amdgcn_readlane(nv, src0 + n);
+      const bool fd = __builtin_amdgcn_readlane((int)from_draft, src0 + n) != 0;
       const char* kb = reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
       const char* vb = kb + (fd ? dv_d : dv_c);
       // rows past the group's last valid row re-read that row
@@ -477,16 +661,16 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   TileInfo cur = {0u, -1}, nxt = {0u, -1};
   int issued = 0;
   if (n_my > 0) {
-    cur = issue_tile(gw, own_x ? x_stage : my_stage);
+    cur = issue_tile(gw, 0, own_x ? x_stage : my_stage);
     issued = 1;
     if (own_x && n_my > 1) {
-      nxt = issue_tile(gw + NW, my_stage);
+      nxt = issue_tile(gw + NW, 1, my_stage);
       issued = 2;
     }
   }
   for (int u = 0; u < n_my; ++u) {
     if (u >= issued) {                   // the single stage is free again: fetch the next tile
-      cur = issue_tile(gw + u * NW, my_stage);
+      cur = issue_tile(gw + u * NW, u, my_stage);
       issued = u + 1;
     }
     // tiles are issued in order, 16 loads each
@@ -631,7 +815,9 @@ hipError_t launch_verify_attn_mfma(const AttnParams& p, hipStream_t st) {
   const int row_groups = (p.M + 31) / 32;
   const int pairs = p.B * p.Hkv;
   const dim3 grid((unsigned)(kXcds * p.n_splits), (unsigned)((pairs + kXcds - 1) / kXcds), (unsigned)row_groups);
-  hipLaunchKernelGGL(verify_attn_mfma_kernel, grid, dim3(kThreads), 0, st, p, pairs);
+  if (p.reps) hipLaunchKernelGGL(verify_attn_mfma_kernel<kSelect>, grid, dim3(kThreads), 0, st, p, pairs);
+  else if (p.gather) hipLaunchKernelGGL(verify_attn_mfma_kernel<kGather>, grid, dim3(kThreads), 0, st, p, pairs);
+  else hipLaunchKernelGGL(verify_attn_mfma_kernel<kResolve>, grid, dim3(kThreads), 0, st, p, pairs);
   return hipGetLastError();
 }
 

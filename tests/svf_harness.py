@@ -149,5 +149,17 @@ def full_parity(cfg, layer=0, x=None):
     # attention is compared on the block set the GPU used (identical to the oracle's unless near-ties occurred)
     out_ref, lse_ref = oracle_attn(cfg, x, run.sel_idx.cpu(), run.sel_cnt.cpu())
     err = check_attn(cfg, run.out, run.lse, out_ref, lse_ref)
+    # the fused step (selection + gather list + attention) and both reuse modes give the same bits
+    out0, lse0, idx0, cnt0 = run.out.clone(), run.lse.clone(), run.sel_idx.clone(), run.sel_cnt.clone()
+    for mode in (S.SVF_STEP_ANCHOR, S.SVF_STEP_REUSE_GATHER, S.SVF_STEP_REUSE):
+        run.out.fill_(float("nan"))
+        run.lse.fill_(float("nan"))
+        if mode == S.SVF_STEP_ANCHOR:
+            run.sel_idx.fill_(-7)
+            run.sel_cnt.fill_(-7)
+        run.verify_step(mode).sync()
+        assert torch.equal(run.sel_idx, idx0) and torch.equal(run.sel_cnt, cnt0), f"step mode {mode}: selection"
+        assert torch.equal(run.out.view(torch.uint8), out0.view(torch.uint8)), f"step mode {mode}: output bits"
+        assert torch.equal(run.lse.view(torch.int32), lse0.view(torch.int32)), f"step mode {mode}: lse bits"
     return {"near_ties": near, "max_abs_err": err, "run": run, "x": x,
             "idx_ref": idx_ref, "cnt_ref": cnt_ref, "scores_ref": scores_ref}

@@ -70,10 +70,16 @@ def test_cfg3_reuse_layer_matches_anchor_blocks():
     run1 = GpuRun(cfg, to_gpu(x1))
     run1.sel_idx.copy_(idx0)
     run1.sel_cnt.copy_(cnt0)
-    run1.verify_step(False).sync()
+    run1.verify_step(S.SVF_STEP_REUSE).sync()            # own workspace: nothing of the anchor call in it
     assert torch.equal(run1.sel_idx, idx0)
     ref, lse = oracle_attn(cfg, x1, idx0.cpu(), cnt0.cpu())
     check_attn(cfg, run1.out, run1.lse, ref, lse)
+    # with the anchor call's workspace the gather list is reused on this layer's pools: same bits
+    out_plain = run1.out.clone()
+    run1.out.fill_(float("nan"))
+    run1.ws = run0.ws
+    run1.verify_step(S.SVF_STEP_REUSE_GATHER).sync()
+    assert torch.equal(run1.out.view(torch.int16), out_plain.view(torch.int16))
     # and it is bit-identical to svf_verify_attn with the same indices
     out_step = run1.out.clone()
     run1.out.fill_(float("nan"))
