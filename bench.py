@@ -88,9 +88,12 @@ def main():
     outs = [torch.empty(cfg.B, cfg.gamma, cfg.Hq, cfg.d, device=dev, dtype=cfg.torch_dtype) for _ in range(n_layers)]
     sel_idx = torch.full((cfg.B, cfg.Hkv, cfg.k_blocks), -1, device=dev, dtype=torch.int32)
     sel_cnt = torch.zeros((cfg.B, cfg.Hkv), device=dev, dtype=torch.int32)
-    # per-anchor copies of the block sets for the attention-only loop
+    # per-layer block sets, and one workspace per anchor (it holds that anchor's gather list), for
+    # the loops that time one kind of launch at a time
     sel_idx_l = [torch.empty_like(sel_idx) for _ in range(n_layers)]
     sel_cnt_l = [torch.empty_like(sel_cnt) for _ in range(n_layers)]
+    anchor_of = [max(a for a in range(l + 1) if cfg.is_anchor(a)) for l in range(n_layers)]
+    ws_l = {a: S.new_workspace(shape) for a in set(anchor_of)}
 
     def ev():
         return torch.cuda.Event(enable_timing=True)
@@ -116,23 +119,30 @@ def main():
                               x["seq_lens"], x["k_draft"], x["v_draft"], x["draft_mask"], sel_idx, sel_cnt,
                               outs[l], ws)
 
+    def one_layer(l, mode):
+        x, a = layers[l], anchor_of[l]
+        S.svf_verify_step(shape, mode, x["q"], reps[l], x["k_pool"], x["v_pool"], x["block_table"],
+                          x["seq_lens"], x["k_draft"], x["v_draft"], x["draft_mask"], sel_idx_l[a], sel_cnt_l[a],
+                          outs[l], ws_l[a])
+
     def attn_only():
-        for l, x in enumerate(layers):
-            S.svf_verify_attn(shape, x["q"], x["k_pool"], x["v_pool"], x["block_table"], x["seq_lens"],
-                              x["k_draft"], x["v_draft"], x["draft_mask"], sel_idx_l[l], sel_cnt_l[l], outs[l], ws)
+        """The attention launch of a reuse layer (the most frequent launch of a step), on every layer."""
+        for l in range(n_layers):
+            one_layer(l, S.SVF_STEP_REUSE_GATHER)
+
+    def anchor_only():
+        """The launch(es) of an anchor layer: retrieval + attention."""
+        for l in range(n_layers):
+            if cfg.is_anchor(l):
+                one_layer(l, S.SVF_STEP_ANCHOR)
 
     def select_only():
+        """Stand-alone block scores + selection (the two-kernel path svf_score_select exposes)."""
         for l, x in enumerate(layers):
             if cfg.is_anchor(l):
-                S.svf_score_select(shape, x["q"], reps[l], x["seq_lens"], sel_idx_l[l], sel_cnt_l[l], ws)
+                S.svf_score_select(shape, x["q"], reps[l], x["seq_lens"], sel_idx, sel_cnt, ws)
 
-    # block sets per layer (anchor's own, followers copy) for the attention-only loop
-    for l, x in enumerate(layers):
-        if cfg.is_anchor(l):
-            S.svf_score_select(shape, x["q"], reps[l], x["seq_lens"], sel_idx_l[l], sel_cnt_l[l], ws)
-        else:
-            sel_idx_l[l].copy_(sel_idx_l[l - 1])
-            sel_cnt_l[l].copy_(sel_cnt_l[l - 1])
+    anchor_only()                      # block sets and gather lists for the attention-only loop
     torch.cuda.synchronize()
     setup_s = time.time() - t_setup
 
@@ -183,6 +193,8 @@ def main():
     ms_step = timed(run_step, args.steps, args.warmup)
     run_attn = make_runner(attn_only)
     ms_attn = timed(run_attn, args.steps, args.warmup)
+    run_anchor = make_runner(anchor_only)
+    ms_anchor = timed(run_anchor, args.steps, args.warmup)
     run_sel = make_runner(select_only)
     ms_sel = timed(run_sel, args.steps, args.warmup)
     ms_step_eager = timed(step, max(3, args.steps // 5), 2)
@@ -190,6 +202,7 @@ def main():
     n_anchor = sum(1 for l in range(n_layers) if cfg.is_anchor(l))
     attn_us = ms_attn * 1e3 / n_layers                        # average duration of one attention launch
     sel_us = ms_sel * 1e3 / max(1, n_anchor)
+    anchor_us = ms_anchor * 1e3 / max(1, n_anchor)
     attn_gbps = bytes_["verify_attn"] / (attn_us * 1e-6) / 1e9
     step_bytes = n_layers * bytes_["verify_attn"] + n_anchor * bytes_["score_select"]
 
@@ -258,7 +271,8 @@ def main():
                    "block_size": cfg.block_size, "gamma": cfg.gamma, "budget_tokens": cfg.k_blocks * cfg.block_size,
                    "page_size": cfg.page_size, "layers": n_layers, "anchor_layers": n_anchor,
                    "launch": "stream" if args.no_graph else "hipgraph"},
-        "roofline": {"bound": "hbm", "kernel": "svf_verify_attn", "achieved": round(attn_gbps, 1),
+        "roofline": {"bound": "hbm", "kernel": "verify_attn_mfma_kernel (reuse layer)" if cfg.dtype == "bf16" and cfg.d == 128
+                     else "verify_attn_valu_kernel", "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if n_layers == cfg.n_layers else None,
                      "algorithmic_bytes_per_launch": bytes_["verify_attn"],
@@ -266,8 +280,10 @@ def main():
         "cpu_baseline": cpu_baseline,
         "extra": {"step_GBps": round(step_bytes / (value_us * 1e-6) / 1e9, 1),
                   "step_us_stream_launches": round(ms_step_eager * 1e3, 2),
-                  "score_select_us": round(sel_us, 3),
-                  "score_select_GBps": round(bytes_["score_select"] / (sel_us * 1e-6) / 1e9, 1),
+                  "anchor_layer_us": round(anchor_us, 3),
+                  "anchor_layer_GBps": round((bytes_["verify_attn"] + bytes_["score_select"]) / (anchor_us * 1e-6) / 1e9, 1),
+                  "standalone_score_select_us": round(sel_us, 3),
+                  "standalone_score_select_GBps": round(bytes_["score_select"] / (sel_us * 1e-6) / 1e9, 1),
                   "block_reps_us_per_layer": round(reps_ms * 1e3, 2),
                   "block_reps_GBps": round(bytes_["block_reps"] / (reps_ms * 1e-3) / 1e9, 1),
                   "setup_s": round(setup_s, 1)},

@@ -314,7 +314,9 @@ __device__ __forceinline__ void merge_splits(const AttnParams& p, int64_t g_row,
 // Where the kernel learns which rows to fetch.
 constexpr int kResolve = 0;   // sel_idx / sel_cnt in memory, page table walked per tile
 constexpr int kGather = 1;    // gather list left behind by an earlier selection
-constexpr int kSelect = 2;    // the workgroup retrieves for itself (scores + top-N), then as kResolve
+constexpr int kSelect = 2;    // the workgroup retrieves for itself (scores + top-N), builds its own
+                              // gather entries, then as kGather
+constexpr int kTableLoads = 8;   // page-table entries a thread stages in LDS (rows up to 8 * kThreads pages)
 
 constexpr int kMaxSelectBlocks = 1024;   // blocks per sequence the in-kernel retrieval handles
 
@@ -464,6 +466,16 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       static_cast<const __hip_bfloat16*>(p.q) + ((int64_t)b * p.gamma * p.Hq + (int64_t)h * p.G) * kD + (tid & (kD - 1));
   QueryHeads<__hip_bfloat16> q0h;
   if (MODE == kSelect) q0h = load_query_heads<__hip_bfloat16>(q0ch, p.G, kD);
+  // (retrieval only) the sequence's page-table row goes to LDS while the scores are computed, so
+  // that turning kept blocks into addresses afterwards costs no further trip to memory
+  const int32_t* const table_row = p.table + (int64_t)b * p.kv.max_pages;
+  const bool table_in_lds = MODE == kSelect && p.kv.page_size != 0 && p.kv.max_pages <= kTableLoads * kThreads;
+  int32_t tbl[kTableLoads];
+  if (MODE == kSelect && table_in_lds) {
+#pragma unroll
+    for (int u = 0; u < kTableLoads; ++u)
+      if (u * kThreads < p.kv.max_pages) tbl[u] = table_row[min(tid + u * kThreads, p.kv.max_pages - 1)];
+  }
   bf16x8 qf[8];
   {
     const __hip_bfloat16* qrow = static_cast<const __hip_bfloat16*>(p.q) +
@@ -487,7 +499,9 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   if (MODE == kSelect) {
     // ---- retrieval: q0 = mean first-draft query of the group, key[j] = order-preserving key of
     // q0 . rep[j] (forced sink / local blocks get the largest key), top-cnt by wavefront 0.
-    // The scratch arrays live in stage 0, which nobody streams into before the last barrier.
+    // The scratch arrays live in stage 0 and the page-table row in the stages after it; nobody
+    // streams into them before the last barrier of this part.
+    int32_t* s_table = reinterpret_cast<int32_t*>(smem + kStageBytes);
     float* s_q0 = reinterpret_cast<float*>(smem);
     uint32_t* s_keys = reinterpret_cast<uint32_t*>(smem + kD * 4);
     SelectScratch* s_sc = reinterpret_cast<SelectScratch*>(smem + kD * 4 + kMaxSelectBlocks * 4);
@@ -509,6 +523,11 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     }
     if (tid < kD) s_q0[tid] = mean_query_channel<__hip_bfloat16>(q0h, q0ch, p.G, kD);
     for (int i = tid; i < 4 * 256; i += kThreads) (&s_sc->hist[0][0])[i] = 0;
+    if (table_in_lds) {
+#pragma unroll
+      for (int u = 0; u < kTableLoads; ++u)
+        if (tid + u * kThreads < p.kv.max_pages) s_table[tid + u * kThreads] = tbl[u];
+    }
     __syncthreads();
     float4 qv[kNch];
 #pragma unroll
@@ -541,6 +560,34 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       for (int i = tid; i < p.k_blocks; i += kThreads) out_idx[i] = i < cnt ? s_sel[i] : -1;
       if (tid == 0) p.sel_cnt_out[pair] = cnt;
     }
+    // gather entries of this wavefront's tiles (lane 8u + n: group n of its u-th tile), kept for
+    // the loads below and written out for the layers that reuse the selection
+    {
+      const int tc = gw + (lane >> 3) * NW - (p.gamma + kTile - 1) / kTile;     // cache tile index
+      const int e = tc * 8 + (lane & 7);
+      if (lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups) {
+        const int slot0 = 4 * e;
+        if (slot0 < cnt * p.block_size) {
+          const int bi = p.block_shift >= 0 ? slot0 >> p.block_shift : slot0 / p.block_size;
+          const int tok0 = s_sel[bi] * p.block_size + (slot0 - bi * p.block_size);
+          const int nv = min(max(L - tok0, 0), 4);
+          if (nv > 0) {
+            int64_t row;                               // element offset of the token's row of head 0
+            if (p.kv.page_size == 0) {
+              row = (int64_t)b * p.kv.stride_page + (int64_t)tok0 * p.kv.stride_tok;
+            } else {
+              const int pg = p.kv.page_shift >= 0 ? tok0 >> p.kv.page_shift : tok0 / p.kv.page_size;
+              const int phys = table_in_lds ? s_table[pg] : table_row[pg];
+              row = (int64_t)phys * p.kv.stride_page + (int64_t)(tok0 - pg * p.kv.page_size) * p.kv.stride_tok;
+            }
+            const uint64_t off = (uint64_t)((row + (int64_t)h * p.kv.stride_head) * 2);
+            gent = (off & kGatherOffsetMask) | ((uint64_t)nv << kGatherCountShift);
+          }
+        }
+        if (rg == 0) p.gather_out[(int64_t)pair * p.gather_groups + e] = gent;
+      }
+    }
+    __syncthreads();                 // the last reads of the staged page table are done
   } else {
     cnt = min(max(p.sel_cnt[pair], 0), p.k_blocks);
   }
@@ -561,7 +608,6 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   // cache rows of this pair: page 0 (or, without paging, the sequence's own slab), token 0
   const char* const kc_pair = Kc + ((int64_t)(p.kv.page_size == 0 ? b : 0) * p.kv.stride_page +
                                     (int64_t)h * p.kv.stride_head) * 2;
-  const int32_t* const table_b = p.table + (int64_t)b * p.kv.max_pages;
   const int64_t orow_pair = (int64_t)b * p.gamma * p.Hq + h * p.G;      // output row of (draft 0, head 0)
 
   // Resolves the addresses of tile t (the wavefront's u-th) and issues its 16 loads into the
@@ -585,7 +631,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       from_draft = true;
       row_bytes = drow_bytes;
       ti.draft_base = t * kTile;
-    } else if (MODE == kGather) {
+    } else if (MODE != kResolve) {
       nv = (int)(gent >> kGatherCountShift);
       base = nv > 0 ? (int64_t)(uintptr_t)Kc + (int64_t)(gent & kGatherOffsetMask) : (int64_t)(uintptr_t)kd_pair;
       from_draft = nv == 0;
@@ -596,7 +642,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       const bool in_range = slot0 < n_prefix;
       const int sl = in_range ? slot0 : 0;
       const int bi = p.block_shift >= 0 ? sl >> p.block_shift : sl / p.block_size;
-      const int blk = MODE == kSelect ? s_sel[bi] : sel_g[bi];
+      const int blk = sel_g[bi];
       const int tok0 = blk * p.block_size + (sl - bi * p.block_size);
       nv = (in_range && blk >= 0) ? min(max(min(n_prefix - slot0, L - tok0), 0), 4) : 0;
       const int tk = nv > 0 ? tok0 : 0;
@@ -607,7 +653,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       } else {
         const int pg = p.kv.page_shift >= 0 ? tk >> p.kv.page_shift : tk / p.kv.page_size;
         sl_in_page = tk - pg * p.kv.page_size;
-        phys = nv > 0 ? table_b[pg] : 0;
+        phys = nv > 0 ? table_row[pg] : 0;
       }
       // byte offset of the group's first K row from the start of the pool
       const int64_t off = (kc_pair - Kc) + ((int64_t)phys * p.kv.stride_page + (int64_t)sl_in_page * p.kv.stride_tok) * 2;
@@ -615,10 +661,6 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       from_draft = nv == 0;
       row_bytes = tok_bytes;
       ti.draft_base = -1;
-      // the tile's part of the gather list, for the layers that reuse this selection
-      if (MODE == kSelect && rg == 0 && lane < 8)
-        p.gather_out[(int64_t)pair * p.gather_groups + (t - tiles_d) * 8 + n8] =
-            nv > 0 ? (((uint64_t)off & kGatherOffsetMask) | ((uint64_t)nv << kGatherCountShift)) : 0ull;
     }
     // slot validity: slot s is valid iff (s mod 4) < nv of group s / 4
     const int nv_s = __shfl(nv, src0 + (l32 >> 2), 64);
