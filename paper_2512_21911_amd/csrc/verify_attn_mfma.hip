@@ -726,23 +726,22 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   }
 
   // ---- combine the eight wavefronts through LDS ------------------------------------------------
-  // Wavefront w parks its rescaled fp32 output in stage w as [32 rows][32 float4]; float4 chunk
-  // c4 of row r sits at position c4 ^ r, which keeps both the row-per-lane writes and the
-  // chunk-per-lane reads off each other's banks.
+  // Wavefront w parks its fp32 output, as it stands (relative to its own running maximum), in
+  // its own stage as [32 rows][32 float4], as soon as it is done; float4 chunk c4 of row r sits
+  // at position c4 ^ r, which keeps both the row-per-lane writes and the chunk-per-lane reads
+  // off each other's banks.  After the one barrier the readers bring the eight slices to the
+  // common maximum while they add them.
   l_run += __shfl_xor(l_run, 32, 64);
-  if (g == 0) sm_m[wave][l32] = m_run;
-  __syncthreads();                       // every wavefront is done with its K/V stage
+  if (g == 0) {
+    sm_m[wave][l32] = m_run;
+    sm_l[wave][l32] = l_run;
+  }
   {
-    float mw = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) mw = fmaxf(mw, sm_m[w][l32]);
-    const float f = m_run == -INFINITY ? 0.f : fast_exp2(m_run - mw);
-    if (g == 0) sm_l[wave][l32] = l_run * f;               // denominators leave here already rescaled
     float4* mine = reinterpret_cast<float4*>(my_stage);
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int i = 8 * (v >> 2) + 4 * g + (v & 3);        // dims 4*i .. 4*i+3
-      mine[l32 * 32 + (i ^ l32)] = make_float4(oacc[0][v] * f, oacc[1][v] * f, oacc[2][v] * f, oacc[3][v] * f);
+      mine[l32 * 32 + (i ^ l32)] = make_float4(oacc[0][v], oacc[1][v], oacc[2][v], oacc[3][v]);
     }
   }
   __syncthreads();
@@ -751,10 +750,16 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   const bool single = p.n_splits == 1;
   const int r = tid >> 4, cg = tid & 15;
   float mw = -INFINITY, lw = 0.f;
+  float fw[kWaves];
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) {
-    mw = fmaxf(mw, sm_m[w][r]);
-    lw += sm_l[w][r];
+    fw[w] = sm_m[w][r];
+    mw = fmaxf(mw, fw[w]);
+  }
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    fw[w] = fw[w] == -INFINITY ? 0.f : fast_exp2(fw[w] - mw);      // a slice that saw no token counts nothing
+    lw = __builtin_fmaf(sm_l[w][r], fw[w], lw);
   }
   float racc[8];
 #pragma unroll
@@ -764,7 +769,10 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
       const float4 t = reinterpret_cast<const float4*>(smem + w * kStageBytes)[r * 32 + ((cg * 2 + c) ^ r)];
-      racc[4 * c] += t.x; racc[4 * c + 1] += t.y; racc[4 * c + 2] += t.z; racc[4 * c + 3] += t.w;
+      racc[4 * c] = __builtin_fmaf(t.x, fw[w], racc[4 * c]);
+      racc[4 * c + 1] = __builtin_fmaf(t.y, fw[w], racc[4 * c + 1]);
+      racc[4 * c + 2] = __builtin_fmaf(t.z, fw[w], racc[4 * c + 2]);
+      racc[4 * c + 3] = __builtin_fmaf(t.w, fw[w], racc[4 * c + 3]);
     }
   const int orow_row = row0 + r;
   const bool rok = orow_row < p.M;

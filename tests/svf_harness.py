@@ -88,6 +88,8 @@ def check_reps(cfg, x, reps_gpu, reps_ref=None):
     lens = x["seq_lens"].cpu().tolist()
     for b, L in enumerate(lens):
         nb = -(-L // cfg.block_size)
+        if nb == 0:
+            continue
         err = np.abs(got[b, :, :nb] - ref[b, :, :nb]) / np.maximum(1.0, np.abs(ref[b, :, :nb]))
         assert np.isfinite(got[b, :, :nb]).all(), "non-finite representative"
         assert err.max() <= REPS_TOL, f"reps mismatch b={b}: {err.max():.3e}"
@@ -110,8 +112,10 @@ def check_selection(cfg, x, scores_ref, idx_gpu, cnt_gpu, n_sink=0, n_local=0, k
             c = int(cnt_ref[b, h])
             g = idx_g[b, h, :c]
             assert (np.diff(g) > 0).all(), "selected ids must ascend"
-            assert g.min() >= 0 and g.max() < nb
             assert (idx_g[b, h, c:] == -1).all(), "padding must be -1"
+            if c == 0:
+                continue
+            assert g.min() >= 0 and g.max() < nb
             if (g == idx_ref[b, h, :c]).all():
                 continue
             ties = set(O.near_tie_blocks(scores_ref[b, h], nb, idx_ref[b, h, :c], TIE_GAP))

@@ -113,6 +113,17 @@ EDGE = {
     "gqa8": small(Hq=16, Hkv=2, gamma=6),
     "mha": small(Hq=4, Hkv=4, gamma=3),
     "short_seq": small(T=40, page_size=8, block_size=16, k_blocks=2),
+    # the anchor kernel's own retrieval: sixteen query heads per KV head (more than one batch of
+    # head loads), a second selection key per thread (more than 512 blocks), a page table too long
+    # to be staged in LDS, two row groups
+    "gqa16": small(Hq=32, Hkv=2, gamma=2),
+    "blocks_768": small(B=1, Hq=4, Hkv=1, T=49152, k_blocks=24, planted=5, min_len=40000),
+    "long_page_table": small(B=1, Hq=4, Hkv=1, T=20480, page_size=4, k_blocks=8, planted=3),
+    "two_row_groups": small(Hq=16, Hkv=2, gamma=7, n_sink=1, n_local=1),
+    # shapes that leave the fused path: more than 1024 blocks (two retrieval kernels + gather list),
+    # more than 1024 kept blocks (no gather list)
+    "blocks_2048": small(B=1, Hq=4, Hkv=1, T=32768, block_size=16, k_blocks=40, planted=6),
+    "budget_1500_blocks": small(B=1, Hq=4, Hkv=1, T=8192, block_size=4, page_size=4, k_blocks=1500, planted=20),
 }
 
 
@@ -120,6 +131,16 @@ EDGE = {
 def test_edge_case(name):
     r = full_parity(EDGE[name])
     report(name, r)
+
+
+def test_empty_sequence_in_a_batch():
+    """A sequence with no prefix attends to its drafts only; its neighbours are unaffected."""
+    cfg = small(B=3, min_len=100)
+    x = W.make_layer(cfg)
+    x["seq_lens"][1] = 0
+    r = full_parity(cfg, x=x)
+    assert r["run"].sel_cnt.cpu().tolist()[1] == [0, 0]
+    report("empty sequence", r)
 
 
 def test_hnd_strides_and_scale():
