@@ -363,17 +363,23 @@ __device__ __forceinline__ void workgroup_select(const uint32_t* keys, SelectScr
     const uint32_t incl = wave_inclusive_sum(own);
     uint32_t run = incl - own;                      // keys in bins above this lane's
     const bool cross = incl >= need && run < need;  // exactly one lane
-    uint32_t bin = 255u - 4u * (uint32_t)lane;
+    uint32_t bin = 255u - 4u * (uint32_t)lane, in_bin = hq.w;
     if (run + hq.w < need) {
-      run += hq.w; --bin;
+      run += hq.w; --bin; in_bin = hq.z;
       if (run + hq.z < need) {
-        run += hq.z; --bin;
-        if (run + hq.y < need) { run += hq.y; --bin; }
+        run += hq.z; --bin; in_bin = hq.y;
+        if (run + hq.y < need) { run += hq.y; --bin; in_bin = hq.x; }
       }
     }
     const int src = __builtin_ctzll(__ballot(cross));
     prefix |= (uint32_t)__builtin_amdgcn_readlane((int)bin, src) << shift;
     need -= (uint32_t)__builtin_amdgcn_readlane((int)run, src);   // still wanted from inside that bin
+    // every key of that bin is wanted: no need to look at the lower digits (the threshold is the
+    // bin's smallest possible key, and every key equal to it is kept)
+    if (need == (uint32_t)__builtin_amdgcn_readlane((int)in_bin, src)) {
+      need = 0xffffffffu;
+      break;
+    }
   }
   const uint32_t tau = prefix;
   const uint64_t below = (1ull << lane) - 1ull;
