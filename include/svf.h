@@ -98,7 +98,7 @@ int32_t svf_budget_blocks(int64_t L, int64_t L0, double rho, int32_t block_size,
  * 0 if the shape is invalid).  The workspace must be 256-byte aligned and must have been
  * cleared to zero once (svf_workspace_init) before its first use; the library leaves it
  * in a reusable state after every call.  Calls that share one workspace must be ordered
- * on one stream.
+ * on one stream.  A workspace serves one shape: clear it again before using it with another.
  */
 size_t svf_workspace_bytes(const svf_shape_t* shape);
 
@@ -160,6 +160,15 @@ int svf_verify_attn(const svf_shape_t* shape, const void* q, const void* K, cons
  *   sizes that are multiples of four, or more than 1024 kept blocks) take the SVF_STEP_REUSE path.
  * Any other mode: SVF_ERR_SHAPE.
  */
+/*
+ * Tuning / test knob of the retrieving attention kernel (SVF_STEP_ANCHOR, shapes with a gather
+ * list): the workgroups of one (sequence, KV head, row group) each score a share of the blocks
+ * and wait for the others' keys; `polls` bounds that wait (default 64), after which a workgroup
+ * scores all blocks itself.  0 switches the exchange off.  The result is the same bits either
+ * way.  Process-wide, takes effect at the next call; 0 <= polls <= 4096, else SVF_ERR_SHAPE.
+ */
+int svf_set_exchange_polls(int polls);
+
 #define SVF_STEP_REUSE 0
 #define SVF_STEP_ANCHOR 1
 #define SVF_STEP_REUSE_GATHER 2

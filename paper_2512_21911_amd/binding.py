@@ -41,7 +41,7 @@ class SvfError(RuntimeError):
 _lib = None
 
 EXPORTS = ["svf_version", "svf_strerror", "svf_budget_blocks", "svf_workspace_bytes", "svf_workspace_init",
-           "svf_block_reps", "svf_score_select", "svf_verify_attn", "svf_verify_step"]
+           "svf_block_reps", "svf_score_select", "svf_verify_attn", "svf_verify_step", "svf_set_exchange_polls"]
 
 
 def lib() -> ctypes.CDLL:
@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
         shp = ctypes.POINTER(SvfShape)
         L.svf_version.restype = ctypes.c_int
+        L.svf_set_exchange_polls.restype = ctypes.c_int
+        L.svf_set_exchange_polls.argtypes = [ctypes.c_int]
         L.svf_version.argtypes = []
         L.svf_strerror.restype = ctypes.c_char_p
         L.svf_strerror.argtypes = [ctypes.c_int]
@@ -155,6 +157,10 @@ def svf_verify_attn(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, dra
 
 
 SVF_STEP_REUSE, SVF_STEP_ANCHOR, SVF_STEP_REUSE_GATHER = 0, 1, 2
+
+
+def svf_set_exchange_polls(polls):
+    _check(lib().svf_set_exchange_polls(int(polls)), "svf_set_exchange_polls")
 
 
 def svf_verify_step(shape, mode, q, reps, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask,

@@ -3,6 +3,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "svf_device.h"
 
 namespace svf {
@@ -109,6 +111,12 @@ AttnPlan plan_attn(const svf_shape_t& s) {
   pl.gather_groups = pl.gather ? (int32_t)(((int64_t)s.k_blocks * s.block_size + 31) / 32 * 8) : 0;
   pl.off_gather = off;
   off += align_up(pairs * (size_t)pl.gather_groups * sizeof(uint64_t));
+  // key exchange of the in-kernel retrieval: per (pair, row group)
+  const size_t groups = pairs * (pl.Mpad / 32);
+  pl.off_xkeys = off;
+  off += align_up(pl.fused_select ? groups * (size_t)nb_max_of(s) * sizeof(uint64_t) : 0);
+  pl.off_epochs = off;
+  off += align_up(pl.fused_select ? groups * sizeof(uint32_t) : 0);
   pl.bytes = off;
   return pl;
 }
@@ -134,11 +142,21 @@ hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st) {
 
 }  // namespace svf
 
+// Polls a workgroup of the retrieving attention kernel spends waiting for the block keys of the
+// other workgroups of its group before it scores everything itself (svf_set_exchange_polls).
+static std::atomic<int> g_exchange_polls{64};
+
 using namespace svf;
 
 extern "C" {
 
 int svf_version(void) { return 100; }
+
+int svf_set_exchange_polls(int polls) {
+  if (polls < 0 || polls > 4096) return SVF_ERR_SHAPE;
+  g_exchange_polls.store(polls, std::memory_order_relaxed);
+  return SVF_OK;
+}
 
 const char* svf_strerror(int code) {
   switch (code) {
@@ -301,6 +319,9 @@ static int verify_attn_impl(const svf_shape_t* shape, const void* q, const void*
   p.nb_max = nb_max_of(*shape);
   p.n_sink = shape->n_sink;
   p.n_local = shape->n_local;
+  p.xkeys = reinterpret_cast<uint64_t*>(w + pl.off_xkeys);
+  p.epochs = reinterpret_cast<uint32_t*>(w + pl.off_epochs);
+  p.poll_budget = g_exchange_polls.load(std::memory_order_relaxed);
   if (reps_to_select_from && pl.fused_select) {
     p.reps = reps_to_select_from;
     p.sel_idx_out = const_cast<int32_t*>(sel_idx);

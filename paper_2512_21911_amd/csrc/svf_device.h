@@ -95,6 +95,11 @@ struct AttnParams {
   int32_t* sel_cnt_out;        // [B][Hkv]
   uint64_t* gather_out;        // [B][Hkv][gather_groups]
   int32_t nb_max, n_sink, n_local;
+  // exchange of block keys between the workgroups of a (pair, row group): one 64-bit word per
+  // block (key in the low half, the call's tag in the high half), one tag counter per group
+  uint64_t* xkeys;             // [groups][nb_max]
+  uint32_t* epochs;            // [groups]
+  int32_t poll_budget;         // polls before a workgroup scores everything itself; 0: no exchange
   int32_t B, gamma, Hq, Hkv, G, d, M, Mpad, block_size, k_blocks, n_splits, mask_per_batch, max_seq_len;
   int32_t block_shift;         // log2(block_size) if a power of two, else -1
   uint64_t g_magic;            // floor(2^32 / G) + 1: n / G == (n * g_magic) >> 32 for n, G < 65536
@@ -186,7 +191,7 @@ struct AttnPlan {
   bool fused_select;         // anchor layers retrieve inside the attention kernel
   bool gather;               // the shape can use a gather list
   int32_t gather_groups;     // entries per (sequence, KV head): a whole number of 32-token tiles
-  size_t off_o, off_m, off_l, off_tickets, off_gather, bytes;
+  size_t off_o, off_m, off_l, off_tickets, off_gather, off_xkeys, off_epochs, bytes;
 };
 AttnPlan plan_attn(const svf_shape_t& s);
 

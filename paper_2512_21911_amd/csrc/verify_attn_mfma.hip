@@ -434,7 +434,23 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   __shared__ float sm_l[kWaves][32];
   __shared__ int sm_last;
   __shared__ int32_t s_sel[MODE == kSelect ? kMaxSelectBlocks : 1];   // kept blocks, ascending
+  __shared__ int s_exchange_failed;
 
+  // The kernel arguments are read piecemeal further down, and every scalar-memory wait is a wait
+  // for all scalar loads: touch each 64-byte line of the argument block once now, so that the
+  // later reads come out of the scalar cache.
+  {
+    const __attribute__((address_space(4))) uint32_t* ka =
+        (const __attribute__((address_space(4))) uint32_t*)__builtin_amdgcn_kernarg_segment_ptr();
+    static_assert(sizeof(AttnParams) > 5 * 64, "argument block shorter than the lines touched");
+    const uint32_t w0 = ka[0], w1 = ka[16], w2 = ka[32], w3 = ka[48], w4 = ka[64], w5 = ka[80];
+    asm volatile("" : : "s"(w0), "s"(w1), "s"(w2), "s"(w3), "s"(w4), "s"(w5));
+  }
+  // Values that are the same for the whole workgroup but come from device memory (lengths,
+  // counts) are loaded through the vector path with this opaque zero in the address: a scalar
+  // load would stall the next read of a kernel argument until it is back.
+  int vzero;
+  asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
   const int split = blockIdx.x / kXcds;
   const int pair = blockIdx.y * kXcds + blockIdx.x % kXcds;
   const int rg = blockIdx.z;
@@ -476,6 +492,11 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   // that turning kept blocks into addresses afterwards costs no further trip to memory
   const int32_t* const table_row = p.table + (int64_t)b * p.kv.max_pages;
   const bool table_in_lds = MODE == kSelect && p.kv.page_size != 0 && p.kv.max_pages <= kTableLoads * kThreads;
+  // (retrieval only) with more than one split the workgroups of a group share the scoring; the
+  // tag marks the keys of this call (the group's counter moves on by one per call)
+  const bool share_scores = MODE == kSelect && p.n_splits >= 2 && p.poll_budget > 0;
+  uint32_t tag = 0;
+  if (MODE == kSelect) tag = p.epochs[group + vzero];              // + 1 once it has arrived
   int32_t tbl[kTableLoads];
   if (MODE == kSelect && table_in_lds) {
 #pragma unroll
@@ -500,7 +521,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     if (lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups) gent = p.gather[(int64_t)pair * p.gather_groups + e];
   }
   int L = 0;
-  if (MODE != kGather) L = clamped_len(p.seq_lens, b, p.max_seq_len);
+  if (MODE != kGather) L = clamped_len(p.seq_lens, b + vzero, p.max_seq_len);
   int cnt;
   if (MODE == kSelect) {
     // ---- retrieval: q0 = mean first-draft query of the group, key[j] = order-preserving key of
@@ -511,50 +532,96 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     float* s_q0 = reinterpret_cast<float*>(smem);
     uint32_t* s_keys = reinterpret_cast<uint32_t*>(smem + kD * 4);
     SelectScratch* s_sc = reinterpret_cast<SelectScratch*>(smem + kD * 4 + kMaxSelectBlocks * 4);
-    const int nb = (L + p.block_size - 1) / p.block_size;
-    cnt = min(p.k_blocks, nb);
+    int nb = 0;                                        // known once the length has arrived
     constexpr int kNch = kD / (4 * kScoreLanes);       // 16-byte chunks of a representative per lane
     constexpr int kBatch = 8;                          // passes (of 64 blocks) in flight
     const int sub = tid % kScoreLanes, jrow = tid / kScoreLanes;
     const float* rp = p.reps + (int64_t)pair * p.nb_max * kD + sub * 4;
-    // the workgroups of a pair walk the same rows: each starts at another pass, so that they do
-    // not all queue at the same memory channel
+    uint64_t* const xk = p.xkeys + (int64_t)group * p.nb_max;
+    // workgroups that walk the same rows each start at another pass, so that they do not all
+    // queue at the same memory channel
     const int rot = (split + rg * p.n_splits) % kBatch;
     float4 r[kBatch][kNch];
+    float4 qv[kNch];
+    // One batch of passes first, first + stride, ... (pass = 64 consecutive blocks): optionally
+    // load the rows, then score them; keys go to LDS and, if published, tagged to the group's
+    // exchange array through a write-through store.
+    auto batch = [&](int first, int stride, bool rotate, bool load, bool score, bool publish) {
 #pragma unroll
-    for (int u = 0; u < kBatch; ++u) {                 // first batch goes out with the query loads
-      const float* row = rp + (int64_t)min(((u + rot) % kBatch) * 64 + jrow, p.nb_max - 1) * kD;
+      for (int u = 0; u < kBatch; ++u) {
+        const int ps = first + stride * (rotate ? (u + rot) % kBatch : u);
+        if (load && ps * 64 < p.nb_max) {
+          const float* row = rp + (int64_t)min(ps * 64 + jrow, p.nb_max - 1) * kD;
 #pragma unroll
-      for (int i = 0; i < kNch; ++i) r[u][i] = *reinterpret_cast<const float4*>(row + i * 4 * kScoreLanes);
-    }
+          for (int i = 0; i < kNch; ++i) r[u][i] = *reinterpret_cast<const float4*>(row + i * 4 * kScoreLanes);
+        }
+      }
+      if (!score) return;
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int ps = first + stride * (rotate ? (u + rot) % kBatch : u);
+        if (ps * 64 < nb) {                            // uniform
+          const float v = block_score<kNch>(r[u], qv);
+          const int j = ps * 64 + jrow;
+          if (sub == 0 && j < nb) {
+            const uint32_t key = (j < p.n_sink || j >= nb - p.n_local) ? 0xffffffffu : score_key(v + 0.0f);
+            s_keys[j] = key;
+            if (publish)
+              __hip_atomic_store(xk + j, (uint64_t)key | ((uint64_t)tag << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+        }
+      }
+    };
+    // the first batch goes out with the query loads
+    if (share_scores) batch(split, p.n_splits, false, true, false, false);
+    else batch(0, 1, true, true, false, false);
     if (tid < kD) s_q0[tid] = mean_query_channel<__hip_bfloat16>(q0h, q0ch, p.G, kD);
     for (int i = tid; i < 4 * 256; i += kThreads) (&s_sc->hist[0][0])[i] = 0;
+    if (tid == 0) s_exchange_failed = 0;
     if (table_in_lds) {
 #pragma unroll
       for (int u = 0; u < kTableLoads; ++u)
         if (tid + u * kThreads < p.kv.max_pages) s_table[tid + u * kThreads] = tbl[u];
     }
     __syncthreads();
-    float4 qv[kNch];
+    L = __builtin_amdgcn_readfirstlane(L);
+    nb = (L + p.block_size - 1) / p.block_size;
+    cnt = min(p.k_blocks, nb);
+    tag = (uint32_t)__builtin_amdgcn_readfirstlane((int)tag) + 1u;
 #pragma unroll
     for (int i = 0; i < kNch; ++i) qv[i] = *reinterpret_cast<const float4*>(s_q0 + sub * 4 + i * 4 * kScoreLanes);
-    for (int j0 = 0; j0 < nb; j0 += 64 * kBatch) {
-      float v[kBatch];
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) v[u] = block_score<kNch>(r[u], qv);
-      if (j0 + 64 * kBatch < nb) {
-#pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-          const float* row = rp + (int64_t)min(j0 + 64 * kBatch + ((u + rot) % kBatch) * 64 + jrow, p.nb_max - 1) * kD;
-#pragma unroll
-          for (int i = 0; i < kNch; ++i) r[u][i] = *reinterpret_cast<const float4*>(row + i * 4 * kScoreLanes);
+    bool score_alone = !share_scores;
+    if (share_scores) {
+      // this workgroup's share (nb <= 1024 = 16 passes, at least two splits: one batch), then
+      // the others' keys: a key is valid once its word carries this call's tag.  The wait is
+      // bounded; a workgroup that runs out of patience scores everything itself.
+      batch(split, p.n_splits, false, false, true, true);
+      const int j0 = tid, j1 = tid + kThreads;
+      bool need0 = j0 < nb && ((j0 >> 6) % p.n_splits) != split;
+      bool need1 = j1 < nb && ((j1 >> 6) % p.n_splits) != split;
+      const bool mine0 = need0, mine1 = need1;
+      uint32_t got0 = 0, got1 = 0;
+      for (int it = 0; it < p.poll_budget; ++it) {
+        if (need0) {
+          const uint64_t w = __hip_atomic_load(xk + j0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if ((uint32_t)(w >> 32) == tag) { got0 = (uint32_t)w; need0 = false; }
         }
+        if (need1) {
+          const uint64_t w = __hip_atomic_load(xk + j1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if ((uint32_t)(w >> 32) == tag) { got1 = (uint32_t)w; need1 = false; }
+        }
+        if (!__any(need0 || need1)) break;
       }
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const int j = j0 + ((u + rot) % kBatch) * 64 + jrow;
-        if (sub == 0 && j < nb)
-          s_keys[j] = (j < p.n_sink || j >= nb - p.n_local) ? 0xffffffffu : score_key(v[u] + 0.0f);
+      if (need0 || need1) s_exchange_failed = 1;
+      if (mine0 && !need0) s_keys[j0] = got0;
+      if (mine1 && !need1) s_keys[j1] = got1;
+      __syncthreads();
+      score_alone = s_exchange_failed != 0;
+    }
+    if (score_alone) {
+      const bool loaded = !share_scores;               // the up-front batch was this one
+      for (int f = 0; f * 64 < nb; f += kBatch) {
+        batch(f, 1, true, !(loaded && f == 0), true, false);
       }
     }
     __syncthreads();
@@ -595,7 +662,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     }
     __syncthreads();                 // the last reads of the staged page table are done
   } else {
-    cnt = min(max(p.sel_cnt[pair], 0), p.k_blocks);
+    cnt = __builtin_amdgcn_readfirstlane(min(max(p.sel_cnt[pair + vzero], 0), p.k_blocks));
   }
   const int n_prefix = cnt * p.block_size;
   const int tiles = tiles_d + (n_prefix + kTile - 1) / kTile;
@@ -835,6 +902,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   // written-through data.  Local writers only (the normal case): this XCD's L2 is their common
   // coherence point, loads that bypass the per-CU cache are enough.
   const int64_t g_row = (int64_t)pair * p.n_splits * p.Mpad + orow_row;
+  // every workgroup of the group is past the exchange of block keys: the next call gets a new tag
+  if (MODE == kSelect && share_scores && tid == 0) p.epochs[group] = tag;
   if (last_kind == 2) {
     merge_splits<true>(p, g_row, orow, rok, cg);
   } else {

@@ -275,6 +275,29 @@ def test_repeated_calls_are_bit_stable():
         assert torch.equal(run.out.view(torch.int16), out0.view(torch.int16))
 
 
+@pytest.mark.parametrize("cfg_id,T", [(3, 8192), (5, 65536), (4, 131072)])
+def test_anchor_retrieval_same_bits_with_and_without_key_exchange(cfg_id, T):
+    """The workgroups of a group share the block scoring through memory, with a bounded wait; a
+    wait of zero or one poll sends some or all of them down the score-everything path."""
+    cfg = W.shrink(W.CONFIGS[cfg_id], T)
+    x = W.make_layer(cfg)
+    run = GpuRun(cfg, to_gpu(x))
+    run.block_reps().score_select().verify_attn().sync()
+    out0, idx0, cnt0 = run.out.clone(), run.sel_idx.clone(), run.sel_cnt.clone()
+    try:
+        for polls in (0, 1, 2, 64):
+            S.svf_set_exchange_polls(polls)
+            for _ in range(3):                     # the tag moves on from call to call
+                run.out.fill_(float("nan"))
+                run.sel_idx.fill_(-7)
+                run.sel_cnt.fill_(-7)
+                run.verify_step(S.SVF_STEP_ANCHOR).sync()
+                assert torch.equal(run.sel_idx, idx0) and torch.equal(run.sel_cnt, cnt0), f"polls={polls}"
+                assert torch.equal(run.out.view(torch.int16), out0.view(torch.int16)), f"polls={polls}"
+    finally:
+        S.svf_set_exchange_polls(64)
+
+
 def test_budget_helper_matches_oracle():
     for L, L0, rho, bs in [(32768, 4096, 0.1, 64), (4096, 4096, 0.1, 64), (131072, 1024, 0.1, 128), (777, 100, 0.5, 7)]:
         assert S.svf_budget_blocks(L, L0, rho, bs) == O.budget_blocks(L, L0, rho, bs)
