@@ -128,14 +128,25 @@ __device__ __forceinline__ void store_coherent2(float* p, float a, float b) {
   const uint64_t bits = (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32);
   __hip_atomic_store(reinterpret_cast<uint64_t*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// 8-byte load of a partial.  LOCAL: the data is known to sit in, or behind, this XCD's L2, so
-// only the per-CU cache has to be bypassed, which is what a relaxed atomic load at workgroup
-// scope compiles to; otherwise a plain load (after a device-scope acquire).
-template <bool LOCAL>
-__device__ __forceinline__ uint64_t load_partial8(const void* p) {
-  if (LOCAL)
-    return __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-  return *reinterpret_cast<const uint64_t*>(p);
+// Loads of a partial by the merging workgroup when the data is known to sit in, or behind,
+// this XCD's L2: only the per-CU cache has to be bypassed (sc0).  Issued by hand; the values are
+// not valid until merge_loads_wait() has been given the registers.
+__device__ __forceinline__ u32x4 load16_bypass_l1(const void* p) {
+  u32x4 v;
+  asm volatile("global_load_dwordx4 %0, %1, off sc0" : "=v"(v) : "v"(p) : "memory");
+  return v;
+}
+__device__ __forceinline__ u32x2 load8_bypass_l1(const void* p) {
+  u32x2 v;
+  asm volatile("global_load_dwordx2 %0, %1, off sc0" : "=v"(v) : "v"(p) : "memory");
+  return v;
+}
+__device__ __forceinline__ void merge_loads_wait(u32x4 (&o)[8], u32x2 (&ml)[8]) {
+  asm volatile("s_waitcnt vmcnt(0)"
+               : "+v"(o[0]), "+v"(o[1]), "+v"(o[2]), "+v"(o[3]), "+v"(o[4]), "+v"(o[5]), "+v"(o[6]), "+v"(o[7]),
+                 "+v"(ml[0]), "+v"(ml[1]), "+v"(ml[2]), "+v"(ml[3]), "+v"(ml[4]), "+v"(ml[5]), "+v"(ml[6]), "+v"(ml[7])
+               :
+               : "memory");
 }
 
 // One 32-token tile against the workgroup's 32 query rows.  stage: LDS address of the stage;
@@ -262,26 +273,28 @@ __device__ __forceinline__ void merge_splits(const AttnParams& p, int64_t g_row,
   for (int c = 0; c < 8; ++c) acc[c] = 0.f;
   float m_acc = -INFINITY, l_acc = 0.f;
   for (int s0 = 0; s0 < p.n_splits; s0 += kMergeBatch) {
-    float pm[kMergeBatch], pl[kMergeBatch];
-    uint32_t t[kMergeBatch][4];
+    u32x4 t[kMergeBatch];
+    u32x2 ml[kMergeBatch];
+    // (straight-line code between the hand-issued loads and their wait)
 #pragma unroll
     for (int u = 0; u < kMergeBatch; ++u) {
       // entries past the last split (index clamped) get weight 0 below
       const int64_t pr = g_row + (int64_t)min(s0 + u, p.n_splits - 1) * p.Mpad;
-      const uint64_t ml = load_partial8<LOCAL>(p.part_ml + 2 * pr);
-      pm[u] = __uint_as_float((uint32_t)ml);
-      pl[u] = __uint_as_float((uint32_t)(ml >> 32));
-#pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        const uint64_t w = load_partial8<LOCAL>(part_o + pr * kD + cg * 8 + 4 * c);
-        t[u][2 * c] = (uint32_t)w;
-        t[u][2 * c + 1] = (uint32_t)(w >> 32);
+      if (LOCAL) {
+        ml[u] = load8_bypass_l1(p.part_ml + 2 * pr);
+        t[u] = load16_bypass_l1(part_o + pr * kD + cg * 8);
+      } else {
+        ml[u] = *reinterpret_cast<const u32x2*>(p.part_ml + 2 * pr);
+        t[u] = *reinterpret_cast<const u32x4*>(part_o + pr * kD + cg * 8);
       }
     }
+    if (LOCAL) merge_loads_wait(t, ml);
+    float pm[kMergeBatch], pl[kMergeBatch];
     float mb = m_acc;
 #pragma unroll
     for (int u = 0; u < kMergeBatch; ++u) {
-      if (s0 + u >= p.n_splits) pm[u] = -INFINITY;
+      pm[u] = s0 + u >= p.n_splits ? -INFINITY : __uint_as_float(ml[u][0]);
+      pl[u] = __uint_as_float(ml[u][1]);
       mb = fmaxf(mb, pm[u]);
     }
     const float fa = m_acc == -INFINITY ? 0.f : fast_exp2(m_acc - mb);
