@@ -319,7 +319,7 @@ __device__ __forceinline__ void merge_splits(const AttnParams& p, int64_t g_row,
     u32x4 o;
 #pragma unroll
     for (int c = 0; c < 4; ++c) o[c] = pack_bf16(acc[2 * c] * inv, acc[2 * c + 1] * inv);
-    *reinterpret_cast<u32x4*>(static_cast<__hip_bfloat16*>(p.out) + orow * kD + cg * 8) = o;
+    store_coherent16(static_cast<__hip_bfloat16*>(p.out) + orow * kD + cg * 8, o);
     if (p.lse && cg == 0) p.lse[orow] = (m_acc + log2f(l_acc)) * 0.6931471805599453f;
   }
 }
