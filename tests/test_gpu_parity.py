@@ -294,6 +294,14 @@ def test_anchor_retrieval_same_bits_with_and_without_key_exchange(cfg_id, T):
                 run.verify_step(S.SVF_STEP_ANCHOR).sync()
                 assert torch.equal(run.sel_idx, idx0) and torch.equal(run.sel_cnt, cnt0), f"polls={polls}"
                 assert torch.equal(run.out.view(torch.int16), out0.view(torch.int16)), f"polls={polls}"
+        # many calls in a row, no host synchronisation in between: tags keep moving, nothing stale is taken
+        outs = []
+        for _ in range(100):
+            run.verify_step(S.SVF_STEP_ANCHOR)
+            outs.append(run.out.clone())
+        torch.cuda.synchronize()
+        assert torch.equal(run.sel_idx, idx0)
+        assert all(torch.equal(o.view(torch.int16), out0.view(torch.int16)) for o in outs)
     finally:
         S.svf_set_exchange_polls(64)
 
