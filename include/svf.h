@@ -178,6 +178,66 @@ int svf_verify_step(const svf_shape_t* shape, int mode, const void* q, const flo
                     const uint64_t* draft_mask_or_null, int32_t* sel_idx, int32_t* sel_cnt,
                     void* out, float* lse_or_null, void* ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Retrieval analytics: the measurements the method's attention design rests on (Sec. 2.2 and
+ * Fig. 2: draft tokens of one step retrieve similar blocks; Sec. 3.3, Eq. 7-8: adjacent layers
+ * retrieve similar blocks, the least similar layers become anchor layers).  Block sets are bit
+ * masks: block j of a (sequence, KV head) is bit j % 64 of word j / 64, svf_mask_words(shape)
+ * uint64 words per mask, bits of blocks that do not exist are zero.  Counts come back as exact
+ * integers; the caller forms the ratios.
+ * ------------------------------------------------------------------------------------------ */
+
+/* ceil(ceil(max_seq_len / block_size) / 64); 0 if the shape is invalid. */
+int32_t svf_mask_words(const svf_shape_t* shape);
+
+/* Bytes of device workspace svf_select_per_draft needs (multiple of 256; 0 if invalid). */
+size_t svf_analytics_workspace_bytes(const svf_shape_t* shape);
+
+/*
+ * The blocks every draft token would retrieve with its own query (Sec. 2.2): the rule of
+ * svf_score_select (Eq. 5 score, first n_sink / last n_local blocks kept, top-N, lowest id on
+ * ties) applied to each of the gamma draft tokens' group-mean queries.  Draft 0's set is the one
+ * svf_score_select returns, bit for bit.
+ *   masks           uint64 [B][Hkv][gamma][svf_mask_words]   (device, out)
+ *   scores_or_null  fp32   [B][gamma][Hkv][nb_max]           (device, out, optional)
+ *   ws / ws_bytes   device scratch of svf_analytics_workspace_bytes (256-byte aligned)
+ */
+int svf_select_per_draft(const svf_shape_t* shape, const void* q, const float* reps,
+                         const int32_t* seq_lens, uint64_t* masks, float* scores_or_null,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/* masks [B][Hkv][svf_mask_words] (device, out) from the index lists svf_score_select writes. */
+int svf_masks_from_selection(const svf_shape_t* shape, const int32_t* sel_idx,
+                             const int32_t* sel_cnt, uint64_t* masks, void* stream);
+
+/*
+ * Overlap of the blocks retrieved by pairs of draft tokens, by positional distance (Sec. 2.2,
+ * Fig. 2).  pos[i] (device int32 [gamma]) is draft i's position (its depth in the draft tree;
+ * several drafts may share one).  For every sequence b and distance d < n_dist (1..64):
+ *   inter[b][d] = sum over KV heads and pairs i < i' with |pos[i] - pos[i']| = d of |M_i & M_i'|
+ * (device uint64 [B][n_dist], overwritten).  The caller divides by (kept blocks of b) x Hkv x
+ * (pairs at distance d) to get the figure's ratio.  Needs svf_mask_words <= 64.
+ */
+int svf_overlap_by_distance(const svf_shape_t* shape, const uint64_t* masks, const int32_t* pos,
+                            int32_t n_dist, uint64_t* inter, void* stream);
+
+/*
+ * Eq. 7 for one calibration sample: masks_by_layer is uint64 [n_layers][B][Hkv][svf_mask_words]
+ * (device), layer l's retrieved blocks over all candidate blocks of the sample; inter_union is
+ * uint64 [n_layers][2] (device, overwritten): |M_l & M_{l-1}| and |M_l | M_{l-1}|; layer 0 gets
+ * (0, 0): its similarity is 0 by definition.
+ */
+int svf_jaccard_adjacent(const svf_shape_t* shape, const uint64_t* masks_by_layer, int32_t n_layers,
+                         uint64_t* inter_union, void* stream);
+
+/*
+ * Eq. 8 (host): anchors[0..K) = the K layers with the largest 1 - J[l], ascending; equal values
+ * go to the lower layer.  J is a host array of n_layers similarities (J[0] = 0 by definition, so
+ * the first layer is always chosen).  SVF_ERR_NULL / SVF_ERR_SHAPE (K outside 1..n_layers, a J
+ * outside [0, 1] or not a number).
+ */
+int svf_topk_anchors(const double* J, int32_t n_layers, int32_t K, int32_t* anchors);
+
 #ifdef __cplusplus
 }
 #endif

@@ -41,7 +41,9 @@ class SvfError(RuntimeError):
 _lib = None
 
 EXPORTS = ["svf_version", "svf_strerror", "svf_budget_blocks", "svf_workspace_bytes", "svf_workspace_init",
-           "svf_block_reps", "svf_score_select", "svf_verify_attn", "svf_verify_step", "svf_set_exchange_polls"]
+           "svf_block_reps", "svf_score_select", "svf_verify_attn", "svf_verify_step", "svf_set_exchange_polls",
+           "svf_mask_words", "svf_analytics_workspace_bytes", "svf_select_per_draft", "svf_masks_from_selection",
+           "svf_overlap_by_distance", "svf_jaccard_adjacent", "svf_topk_anchors"]
 
 
 def lib() -> ctypes.CDLL:
@@ -57,6 +59,20 @@ def lib() -> ctypes.CDLL:
         L.svf_version.restype = ctypes.c_int
         L.svf_set_exchange_polls.restype = ctypes.c_int
         L.svf_set_exchange_polls.argtypes = [ctypes.c_int]
+        L.svf_mask_words.restype = i32
+        L.svf_mask_words.argtypes = [shp]
+        L.svf_analytics_workspace_bytes.restype = ctypes.c_size_t
+        L.svf_analytics_workspace_bytes.argtypes = [shp]
+        L.svf_select_per_draft.restype = ctypes.c_int
+        L.svf_select_per_draft.argtypes = [shp] + [vp] * 6 + [ctypes.c_size_t, vp]
+        L.svf_masks_from_selection.restype = ctypes.c_int
+        L.svf_masks_from_selection.argtypes = [shp] + [vp] * 4
+        L.svf_overlap_by_distance.restype = ctypes.c_int
+        L.svf_overlap_by_distance.argtypes = [shp, vp, vp, i32, vp, vp]
+        L.svf_jaccard_adjacent.restype = ctypes.c_int
+        L.svf_jaccard_adjacent.argtypes = [shp, vp, i32, vp, vp]
+        L.svf_topk_anchors.restype = ctypes.c_int
+        L.svf_topk_anchors.argtypes = [ctypes.POINTER(ctypes.c_double), i32, i32, ctypes.POINTER(i32)]
         L.svf_version.argtypes = []
         L.svf_strerror.restype = ctypes.c_char_p
         L.svf_strerror.argtypes = [ctypes.c_int]
@@ -169,3 +185,47 @@ def svf_verify_step(shape, mode, q, reps, K, V, block_table, seq_lens, k_draft, 
                                  _ptr(block_table), _ptr(seq_lens), _ptr(k_draft), _ptr(v_draft),
                                  _ptr(draft_mask), _ptr(sel_idx), _ptr(sel_cnt), _ptr(out), _ptr(lse),
                                  _ptr(ws), ws.numel(), _stream()), "svf_verify_step")
+
+
+# ---- retrieval analytics (argument marshalling only) ------------------------------------------
+
+def svf_mask_words(shape) -> int:
+    return int(lib().svf_mask_words(ctypes.byref(shape)))
+
+
+def new_analytics_workspace(shape, device="cuda"):
+    import torch
+    n = int(lib().svf_analytics_workspace_bytes(ctypes.byref(shape)))
+    if n == 0:
+        raise SvfError("svf_analytics_workspace_bytes: invalid shape")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def svf_select_per_draft(shape, q, reps, seq_lens, masks, ws=None, scores=None):
+    _check(lib().svf_select_per_draft(ctypes.byref(shape), _ptr(q), _ptr(reps), _ptr(seq_lens), _ptr(masks),
+                                      _ptr(scores), _ptr(ws), ws.numel() if ws is not None else 0, _stream()),
+           "svf_select_per_draft")
+
+
+def svf_masks_from_selection(shape, sel_idx, sel_cnt, masks):
+    _check(lib().svf_masks_from_selection(ctypes.byref(shape), _ptr(sel_idx), _ptr(sel_cnt), _ptr(masks), _stream()),
+           "svf_masks_from_selection")
+
+
+def svf_overlap_by_distance(shape, masks, pos, n_dist, inter):
+    _check(lib().svf_overlap_by_distance(ctypes.byref(shape), _ptr(masks), _ptr(pos), int(n_dist), _ptr(inter),
+                                         _stream()), "svf_overlap_by_distance")
+
+
+def svf_jaccard_adjacent(shape, masks_by_layer, n_layers, inter_union):
+    _check(lib().svf_jaccard_adjacent(ctypes.byref(shape), _ptr(masks_by_layer), int(n_layers), _ptr(inter_union),
+                                      _stream()), "svf_jaccard_adjacent")
+
+
+def svf_topk_anchors(J, K):
+    """Eq. 8 on the host: J is a sequence of per-layer similarities; returns the K anchor layers."""
+    n = len(J)
+    arr = (ctypes.c_double * n)(*[float(v) for v in J])
+    out = (ctypes.c_int32 * max(int(K), 1))()
+    _check(lib().svf_topk_anchors(arr, n, int(K), out), "svf_topk_anchors")
+    return [int(out[i]) for i in range(int(K))]

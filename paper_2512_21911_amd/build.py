@@ -10,7 +10,8 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libsvf.so")
 
-SOURCES = ["svf_api.hip", "block_reps.hip", "score_select.hip", "verify_attn_valu.hip", "verify_attn_mfma.hip"]
+SOURCES = ["svf_api.hip", "block_reps.hip", "score_select.hip", "verify_attn_valu.hip", "verify_attn_mfma.hip",
+           "analytics.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

@@ -71,7 +71,54 @@ __global__ __launch_bounds__(kThreads) void block_scores_kernel(SelectParams p) 
   }
 }
 
-// grid: (Hkv, B)
+// Scores of every draft token's query (Sec. 2.2: retrieval "based on their respective query
+// values"), one pass over the representatives: the rows a thread holds are scored against the
+// gamma mean queries in LDS, with the arithmetic of the kernel above (query 0 gives the same bits).
+// grid: (ceil(nb_max / (kPasses * blocks per pass)), Hkv, B); scores [B][gamma][Hkv][nb_max]
+constexpr int kMaxDrafts = 64;
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void block_scores_all_kernel(SelectParams p) {
+  constexpr int LPB = kScoreLanes;
+  constexpr int NCH = D / (4 * LPB);
+  constexpr int BPW = kThreads / LPB;
+  __shared__ __attribute__((aligned(16))) float qs[kMaxDrafts][D];
+
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int G = p.Hq / p.Hkv;
+  const int sub = threadIdx.x % LPB;
+  float4 r[kPasses][NCH];
+  int jj[kPasses];
+#pragma unroll
+  for (int u = 0; u < kPasses; ++u) {
+    const int j = (blockIdx.x * kPasses + u) * BPW + threadIdx.x / LPB;
+    jj[u] = j;
+    const int jc = j < p.nb_max ? j : p.nb_max - 1;
+    const float* row = p.reps + (((int64_t)b * p.Hkv + h) * p.nb_max + jc) * D + sub * 4;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) r[u][i] = *reinterpret_cast<const float4*>(row + i * 4 * LPB);
+  }
+  for (int idx = threadIdx.x; idx < p.gamma * D; idx += kThreads) {
+    const int i = idx / D, c = idx - i * D;
+    const T* qch = static_cast<const T*>(p.q) + (((int64_t)b * p.gamma + i) * p.Hq + (int64_t)h * G) * D + c;
+    qs[i][c] = mean_query_channel<T>(load_query_heads<T>(qch, G, D), qch, G, D);
+  }
+  const int L = clamped_len(p.seq_lens, b, p.max_seq_len);
+  const int nb = (L + p.block_size - 1) / p.block_size;
+  __syncthreads();
+  for (int i = 0; i < p.gamma; ++i) {
+    float4 qv[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) qv[c] = *reinterpret_cast<const float4*>(&qs[i][sub * 4 + c * 4 * LPB]);
+#pragma unroll
+    for (int u = 0; u < kPasses; ++u) {
+      const float v = block_score<NCH>(r[u], qv);
+      if (sub == 0 && jj[u] < p.nb_max)
+        p.scores[(((int64_t)b * p.gamma + i) * p.Hkv + h) * p.nb_max + jj[u]] = jj[u] < nb ? v + 0.0f : 0.0f;
+    }
+  }
+}
+
+// grid: (Hkv, B * nq)
 __global__ __launch_bounds__(kThreads) void select_kernel(SelectParams p) {
   __shared__ uint32_t hist[256];
   __shared__ uint32_t sh_prefix, sh_need;
@@ -79,14 +126,17 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectParams p) {
   __shared__ uint32_t base_eq, base_sel;
   __shared__ int32_t sh_sel[kMaxGatherBlocks];     // kept block ids, for the gather list
 
-  const int b = blockIdx.y, h = blockIdx.x;
+  const int bq = blockIdx.y, h = blockIdx.x;             // bq = b * nq + query
+  const int b = bq / p.nq;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int L = clamped_len(p.seq_lens, b, p.max_seq_len);
   const int nb = (L + p.block_size - 1) / p.block_size;
   const int cnt = min(p.k_blocks, nb);
-  const float* sc = p.scores + ((int64_t)b * p.Hkv + h) * p.nb_max;
-  int32_t* out = p.sel_idx + ((int64_t)b * p.Hkv + h) * p.k_blocks;
+  const float* sc = p.scores + ((int64_t)bq * p.Hkv + h) * p.nb_max;
+  int32_t* out = p.sel_idx ? p.sel_idx + ((int64_t)bq * p.Hkv + h) * p.k_blocks : nullptr;
+  // bit masks: a wavefront's ballot over 64 consecutive blocks is one word
+  uint64_t* mask = p.masks ? p.masks + (((int64_t)b * p.Hkv + h) * p.nq + (bq - b * p.nq)) * p.mask_words : nullptr;
 
   auto key_of = [&](int j) -> uint32_t {
     if (j < p.n_sink || j >= nb - p.n_local) return 0xffffffffu;
@@ -161,9 +211,10 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectParams p) {
     uint32_t pos = base_sel + (uint32_t)__popcll(m_sel & ((1ull << lane) - 1ull));
     for (int w = 0; w < wave; ++w) pos += wave_sel[w];
     if (keep) {
-      out[pos] = j;
+      if (out) out[pos] = j;
       if (pos < (uint32_t)kMaxGatherBlocks) sh_sel[pos] = j;
     }
+    if (mask && lane == 0 && (j0 >> 6) + wave < p.mask_words) mask[(j0 >> 6) + wave] = m_sel;
     __syncthreads();
     if (tid == 0) {
       uint32_t e = 0, s = 0;
@@ -173,8 +224,12 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectParams p) {
     }
     __syncthreads();
   }
-  for (int i = cnt + tid; i < p.k_blocks; i += kThreads) out[i] = -1;
-  if (tid == 0) p.sel_cnt[(int64_t)b * p.Hkv + h] = cnt;
+  if (out)
+    for (int i = cnt + tid; i < p.k_blocks; i += kThreads) out[i] = -1;
+  if (tid == 0 && p.sel_cnt) p.sel_cnt[(int64_t)bq * p.Hkv + h] = cnt;
+  // mask words past the last block's word group
+  if (mask)
+    for (int w = ((nb + kThreads - 1) / kThreads) * kWaves + tid; w < p.mask_words; w += kThreads) mask[w] = 0;
 
   // Gather list: where the K row of every fourth selected-token slot sits in the pool, and how
   // many of its four slots hold a real token.  (The last loop iteration ended with a barrier, so
@@ -204,7 +259,15 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectParams p) {
 hipError_t launch_score_select(const SelectParams& p, int dtype, hipStream_t st) {
   const int bpw = kPasses * (kThreads / kScoreLanes);
   dim3 g1((p.nb_max + bpw - 1) / bpw, p.Hkv, p.B);
-  if (dtype == SVF_F32) {
+  if (p.nq > 1) {
+    if (dtype == SVF_F32) {
+      if (p.d == 64) hipLaunchKernelGGL((block_scores_all_kernel<float, 64>), g1, dim3(kThreads), 0, st, p);
+      else hipLaunchKernelGGL((block_scores_all_kernel<float, 128>), g1, dim3(kThreads), 0, st, p);
+    } else {
+      if (p.d == 64) hipLaunchKernelGGL((block_scores_all_kernel<__hip_bfloat16, 64>), g1, dim3(kThreads), 0, st, p);
+      else hipLaunchKernelGGL((block_scores_all_kernel<__hip_bfloat16, 128>), g1, dim3(kThreads), 0, st, p);
+    }
+  } else if (dtype == SVF_F32) {
     if (p.d == 64) hipLaunchKernelGGL((block_scores_kernel<float, 64>), g1, dim3(kThreads), 0, st, p);
     else hipLaunchKernelGGL((block_scores_kernel<float, 128>), g1, dim3(kThreads), 0, st, p);
   } else {
@@ -213,7 +276,7 @@ hipError_t launch_score_select(const SelectParams& p, int dtype, hipStream_t st)
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(select_kernel, dim3(p.Hkv, p.B), dim3(kThreads), 0, st, p);
+  hipLaunchKernelGGL(select_kernel, dim3(p.Hkv, p.B * p.nq), dim3(kThreads), 0, st, p);
   return hipGetLastError();
 }
 

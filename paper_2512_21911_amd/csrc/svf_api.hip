@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include <atomic>
+#include <vector>
 
 #include "svf_device.h"
 
@@ -257,6 +258,9 @@ static int score_select_impl(const svf_shape_t* shape, const void* q, const floa
   p.n_local = shape->n_local;
   p.max_seq_len = shape->max_seq_len;
   const AttnPlan pl = plan_attn(*shape);
+  p.nq = 1;
+  p.masks = nullptr;
+  p.mask_words = 0;
   p.gather = nullptr;
   p.table = block_table;
   p.kv = layout_of(*shape);
@@ -392,6 +396,108 @@ int svf_verify_step(const svf_shape_t* shape, int mode, const void* q, const flo
   }
   return verify_attn_impl(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask_or_null, sel_idx,
                           sel_cnt, out, lse_or_null, ws, ws_bytes, stream, mode != SVF_STEP_REUSE);
+}
+
+// ---- retrieval analytics -------------------------------------------------------------------
+
+int32_t svf_mask_words(const svf_shape_t* shape) {
+  if (check_shape(shape) != SVF_OK) return 0;
+  return (nb_max_of(*shape) + 63) / 64;
+}
+
+size_t svf_analytics_workspace_bytes(const svf_shape_t* shape) {
+  if (check_shape(shape) != SVF_OK) return 0;
+  return align_up((size_t)shape->B * shape->gamma * shape->Hkv * nb_max_of(*shape) * sizeof(float));
+}
+
+int svf_select_per_draft(const svf_shape_t* shape, const void* q, const float* reps, const int32_t* seq_lens,
+                         uint64_t* masks, float* scores_or_null, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!q || !reps || !seq_lens || !masks) return SVF_ERR_NULL;
+  if (misaligned(q) || misaligned(reps)) return SVF_ERR_SHAPE;
+  if (!scores_or_null) {
+    if (!ws || reinterpret_cast<uintptr_t>(ws) % kAlign || ws_bytes < svf_analytics_workspace_bytes(shape))
+      return SVF_ERR_WORKSPACE;
+  }
+  SelectParams p;
+  p.q = q;
+  p.reps = reps;
+  p.seq_lens = seq_lens;
+  p.scores = scores_or_null ? scores_or_null : static_cast<float*>(ws);
+  p.sel_idx = nullptr;
+  p.sel_cnt = nullptr;
+  p.B = shape->B;
+  p.gamma = shape->gamma;
+  p.Hq = shape->Hq;
+  p.Hkv = shape->Hkv;
+  p.d = shape->d;
+  p.block_size = shape->block_size;
+  p.nb_max = nb_max_of(*shape);
+  p.k_blocks = shape->k_blocks;
+  p.n_sink = shape->n_sink;
+  p.n_local = shape->n_local;
+  p.max_seq_len = shape->max_seq_len;
+  p.nq = shape->gamma;
+  p.masks = masks;
+  p.mask_words = (p.nb_max + 63) / 64;
+  p.gather = nullptr;
+  p.table = nullptr;
+  p.kv = layout_of(*shape);
+  p.gather_groups = 0;
+  return hip_code(launch_score_select(p, shape->dtype, static_cast<hipStream_t>(stream)));
+}
+
+int svf_masks_from_selection(const svf_shape_t* shape, const int32_t* sel_idx, const int32_t* sel_cnt,
+                             uint64_t* masks, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!sel_idx || !sel_cnt || !masks) return SVF_ERR_NULL;
+  const int words = (nb_max_of(*shape) + 63) / 64;
+  if ((size_t)words * 8 > 48 * 1024) return SVF_ERR_SHAPE;          // the mask of one pair is built in LDS
+  return hip_code(launch_masks_from_selection(sel_idx, sel_cnt, masks, shape->B * shape->Hkv, shape->k_blocks, words,
+                                              static_cast<hipStream_t>(stream)));
+}
+
+int svf_overlap_by_distance(const svf_shape_t* shape, const uint64_t* masks, const int32_t* pos, int32_t n_dist,
+                            uint64_t* inter, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!masks || !pos || !inter) return SVF_ERR_NULL;
+  const int words = (nb_max_of(*shape) + 63) / 64;
+  if (n_dist < 1 || n_dist > 64 || words > 64 || shape->gamma > 64) return SVF_ERR_SHAPE;
+  return hip_code(launch_overlap_by_distance(masks, pos, inter, shape->B, shape->Hkv, shape->gamma, words, n_dist,
+                                             static_cast<hipStream_t>(stream)));
+}
+
+int svf_jaccard_adjacent(const svf_shape_t* shape, const uint64_t* masks_by_layer, int32_t n_layers,
+                         uint64_t* inter_union, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!masks_by_layer || !inter_union) return SVF_ERR_NULL;
+  if (n_layers < 1 || n_layers > 65535) return SVF_ERR_SHAPE;
+  const int64_t words = (int64_t)shape->B * shape->Hkv * ((nb_max_of(*shape) + 63) / 64);
+  return hip_code(launch_jaccard_adjacent(masks_by_layer, inter_union, n_layers, words,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+int svf_topk_anchors(const double* J, int32_t n_layers, int32_t K, int32_t* anchors) {
+  if (!J || !anchors) return SVF_ERR_NULL;
+  if (n_layers < 1 || K < 1 || K > n_layers) return SVF_ERR_SHAPE;
+  for (int32_t l = 0; l < n_layers; ++l)
+    if (!(J[l] >= 0.0 && J[l] <= 1.0)) return SVF_ERR_SHAPE;
+  // K rounds of "largest 1 - J not taken yet, lowest layer first" (n_layers is a layer count)
+  std::vector<char> taken((size_t)n_layers, 0);
+  for (int32_t r = 0; r < K; ++r) {
+    int32_t best = -1;
+    for (int32_t l = 0; l < n_layers; ++l)
+      if (!taken[l] && (best < 0 || 1.0 - J[l] > 1.0 - J[best])) best = l;
+    taken[best] = 1;
+  }
+  int32_t n = 0;
+  for (int32_t l = 0; l < n_layers; ++l)
+    if (taken[l]) anchors[n++] = l;
+  return SVF_OK;
 }
 
 }  // extern "C"

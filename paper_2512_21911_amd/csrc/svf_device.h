@@ -61,6 +61,13 @@ struct SelectParams {
   int32_t* sel_idx;         // [B][Hkv][k]
   int32_t* sel_cnt;         // [B][Hkv]
   int32_t B, gamma, Hq, Hkv, d, block_size, nb_max, k_blocks, n_sink, n_local, max_seq_len;
+  // Retrieval per draft token (analytics, Sec. 2.2): nq = gamma queries per (sequence, KV head)
+  // instead of the first one only; scores are then [B][nq][Hkv][nb_max], sel_idx (may be NULL)
+  // [B][nq][Hkv][k], and the kept blocks can come out as bit masks [B][Hkv][nq][mask_words]
+  // (block j = bit j % 64 of word j / 64).  nq = 1 is the method's own retrieval.
+  int32_t nq;
+  uint64_t* masks;          // NULL: none
+  int32_t mask_words;
   // optional gather list output (NULL: none); needs the cache addressing of the layer
   uint64_t* gather;         // [B][Hkv][gather_groups]
   const int32_t* table;
@@ -182,6 +189,13 @@ __device__ __forceinline__ float mean_query_channel(const QueryHeads<T>& h, cons
 // Launchers (each validates nothing: the C ABI layer has already done so).
 hipError_t launch_block_reps(const RepsParams& p, int dtype, int B, hipStream_t st);
 hipError_t launch_score_select(const SelectParams& p, int dtype, hipStream_t st);
+// retrieval analytics (analytics.hip)
+hipError_t launch_masks_from_selection(const int32_t* sel_idx, const int32_t* sel_cnt, uint64_t* masks, int pairs,
+                                       int k_blocks, int mask_words, hipStream_t st);
+hipError_t launch_overlap_by_distance(const uint64_t* masks, const int32_t* pos, uint64_t* inter, int B, int Hkv,
+                                      int gamma, int mask_words, int n_dist, hipStream_t st);
+hipError_t launch_jaccard_adjacent(const uint64_t* masks_by_layer, uint64_t* inter_union, int n_layers,
+                                   int64_t words_per_layer, hipStream_t st);
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st);
 
 // Host-side planning shared by svf_workspace_bytes and the attention launcher.

@@ -108,3 +108,43 @@ def test_contiguous_cache_needs_no_table():
     args = [ok] * 13
     args[3] = None
     assert S.lib().svf_verify_attn(ctypes.byref(sh), *args, 0, None) == -6
+
+
+def test_analytics_entry_points_validate_before_launching():
+    sh = good_shape()
+    L = S.lib()
+    ok, null = ctypes.c_void_p(0x10000), None
+    assert S.svf_mask_words(sh) == -(-(sh.max_seq_len // sh.block_size) // 64)
+    need = L.svf_analytics_workspace_bytes(ctypes.byref(sh))
+    assert need > 0 and need % 256 == 0
+    assert L.svf_select_per_draft(ctypes.byref(sh), null, ok, ok, ok, ok, ok, need, None) == -1
+    assert L.svf_select_per_draft(ctypes.byref(sh), ok, ok, ok, ok, null, null, 0, None) == -6      # needs scores or ws
+    assert L.svf_select_per_draft(ctypes.byref(sh), ok, ok, ok, ok, null, ok, need - 1, None) == -6
+    assert L.svf_masks_from_selection(ctypes.byref(sh), ok, null, ok, None) == -1
+    assert L.svf_overlap_by_distance(ctypes.byref(sh), ok, ok, 0, ok, None) == -2
+    assert L.svf_overlap_by_distance(ctypes.byref(sh), ok, ok, 65, ok, None) == -2
+    assert L.svf_overlap_by_distance(ctypes.byref(sh), ok, null, 4, ok, None) == -1
+    assert L.svf_jaccard_adjacent(ctypes.byref(sh), ok, 0, ok, None) == -2
+    assert L.svf_jaccard_adjacent(ctypes.byref(sh), null, 4, ok, None) == -1
+
+
+def test_topk_anchors_matches_the_oracle():
+    """Eq. 8 runs on the host: compare with the oracle on random similarities, ties included."""
+    import numpy as np
+    from oracle import svf_analytics_oracle as A
+    rng = np.random.default_rng(3)
+    for trial in range(50):
+        n = int(rng.integers(1, 40))
+        J = np.round(rng.random(n), 1 if trial % 2 else 6)     # coarse rounding makes ties
+        J[0] = 0.0
+        for K in {1, n, int(rng.integers(1, n + 1))}:
+            assert S.svf_topk_anchors(J.tolist(), K) == A.topk_anchors(J, K)
+    L = S.lib()
+    arr = (ctypes.c_double * 3)(0.0, 0.5, 1.5)
+    out = (ctypes.c_int32 * 3)()
+    assert L.svf_topk_anchors(arr, 3, 2, out) == -2            # a similarity above 1
+    arr = (ctypes.c_double * 3)(0.0, float("nan"), 0.5)
+    assert L.svf_topk_anchors(arr, 3, 2, out) == -2
+    arr = (ctypes.c_double * 3)(0.0, 0.5, 0.5)
+    assert L.svf_topk_anchors(arr, 3, 0, out) == -2 and L.svf_topk_anchors(arr, 3, 4, out) == -2
+    assert L.svf_topk_anchors(None, 3, 1, out) == -1

@@ -1,0 +1,175 @@
+"""GPU parity of the retrieval analytics (Sec. 2.2 / Fig. 2; Sec. 3.3, Eq. 7-8) against the oracle:
+bit masks and integer counts are compared exactly (near-ties of the block scores excused and counted,
+as for the main path's selection)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_21911_amd as S
+import workloads as W
+from oracle import svf_analytics_oracle as A
+from oracle import svf_oracle as O
+from svf_harness import TIE_GAP, GpuRun, shape_for, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def small(dtype="bf16", **kw):
+    base = dict(name="edge", cfg_id=9, dtype=dtype, B=2, Hq=8, Hkv=2, d=128, T=1024, block_size=64, gamma=4,
+                k_blocks=4, page_size=16, planted=2, shift=1.5)
+    base.update(kw)
+    return W.VerifyConfig(**base)
+
+
+CASES = {
+    "cfg3_8k": W.shrink(W.CONFIGS[3], 8192),
+    "cfg4_tree_32k": W.shrink(W.CONFIGS[4], 32768),
+    "cfg5_ragged_16k": W.shrink(W.CONFIGS[5], 16384),
+    "cfg1_f32": W.CONFIGS[1],
+    "sink_local_ragged": small(n_sink=1, n_local=2, k_blocks=5, min_len=500, gamma=6),
+    "gamma64": small(gamma=64, B=1, T=4096, k_blocks=8),
+    "d64_f32": small(dtype="f32", d=64, min_len=64, gamma=5),
+    "blocks_1300": small(B=1, Hq=4, Hkv=1, T=20800, block_size=16, k_blocks=40, planted=6, gamma=3),
+}
+
+
+def unpack(words: np.ndarray, nb: int) -> np.ndarray:
+    bits = ((words[..., :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(bool)
+    return bits.reshape(words.shape[:-1] + (-1,))[..., :nb]
+
+
+def positions(cfg):
+    parents = W.draft_tree(cfg)
+    if parents is None:
+        return list(range(cfg.gamma))
+    pos = [0] * cfg.gamma
+    for i, p in enumerate(parents.tolist()):
+        pos[i] = 0 if p < 0 else pos[p] + 1
+    return pos
+
+
+def gpu_masks(cfg, x):
+    run = GpuRun(cfg, to_gpu(x))
+    run.block_reps()
+    W64 = S.svf_mask_words(run.shape)
+    assert W64 == -(-cfg.nb_max // 64)
+    masks = torch.full((cfg.B, cfg.Hkv, cfg.gamma, W64), -1, dtype=torch.int64, device="cuda")
+    scores = torch.full((cfg.B, cfg.gamma, cfg.Hkv, cfg.nb_max), float("nan"), device="cuda")
+    ws = S.new_analytics_workspace(run.shape)
+    S.svf_select_per_draft(run.shape, run.x["q"], run.reps, run.x["seq_lens"], masks, ws, scores)
+    masks2 = torch.full_like(masks, -1)
+    S.svf_select_per_draft(run.shape, run.x["q"], run.reps, run.x["seq_lens"], masks2, ws, None)   # scores in ws
+    torch.cuda.synchronize()
+    assert torch.equal(masks, masks2)
+    return run, masks, scores
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_per_draft_retrieval_overlap_and_similarity(name):
+    cfg = CASES[name]
+    x = W.make_layer(cfg)
+    run, masks_g, scores_g = gpu_masks(cfg, x)
+    reps_ref = O.block_reps(x["k_pool"], x["block_table"], x["seq_lens"], cfg.block_size, cfg.nb_max)
+    s_ref = A.per_draft_scores(x["q"], reps_ref)
+    m_ref = A.per_draft_masks(s_ref, x["seq_lens"], cfg.block_size, cfg.k_blocks, cfg.n_sink, cfg.n_local)
+    lens = x["seq_lens"].tolist()
+
+    # scores (fp32 dot of fp32 means against an fp64 oracle)
+    sg = scores_g.double().cpu().numpy()
+    for b, L in enumerate(lens):
+        nb = -(-L // cfg.block_size)
+        err = np.abs(sg[b, :, :, :nb] - s_ref[b, :, :, :nb]) / np.maximum(1.0, np.abs(s_ref[b, :, :, :nb]))
+        assert err.max() <= 2e-5, f"per-draft scores b={b}: {err.max():.2e}"
+
+    # masks: exact, near-ties of the oracle scores excused and counted
+    mg = unpack(masks_g.cpu().numpy().view(np.uint64), cfg.nb_max)
+    near = 0
+    for b, L in enumerate(lens):
+        nb = -(-L // cfg.block_size)
+        assert not mg[b, :, :, nb:].any(), "bits of blocks that do not exist must be zero"
+        for h in range(cfg.Hkv):
+            for i in range(cfg.gamma):
+                assert mg[b, h, i].sum() == min(cfg.k_blocks, nb)
+                diff = set(np.flatnonzero(mg[b, h, i] ^ m_ref[b, h, i]).tolist())
+                if diff:
+                    chosen = np.flatnonzero(m_ref[b, h, i]).tolist()
+                    ties = set(O.near_tie_blocks(s_ref[b, i, h], nb, chosen, TIE_GAP))
+                    assert diff <= ties, f"mask mismatch at (b={b}, h={h}, draft={i}): {sorted(diff)}"
+                    near += len(diff)
+    print(f"[{name}] per-draft near-ties excused: {near}")
+
+    # draft 0 is the method's own retrieval, bit for bit
+    run.score_select().sync()
+    m0 = torch.full((cfg.B, cfg.Hkv, masks_g.shape[-1]), -1, dtype=torch.int64, device="cuda")
+    S.svf_masks_from_selection(run.shape, run.sel_idx, run.sel_cnt, m0)
+    torch.cuda.synchronize()
+    assert torch.equal(m0, masks_g[:, :, 0])
+    ref0 = A.pack_masks(A.masks_from_selection(run.sel_idx.cpu(), run.sel_cnt.cpu(), cfg.nb_max))
+    np.testing.assert_array_equal(m0.cpu().numpy().view(np.uint64), ref0)
+
+    # overlap by distance: integer counts on the masks the GPU produced
+    pos = positions(cfg)
+    n_dist = min(64, max(pos) + 2)                       # one distance that no pair has
+    inter = torch.full((cfg.B, n_dist), -1, dtype=torch.int64, device="cuda")
+    S.svf_overlap_by_distance(run.shape, masks_g, torch.tensor(pos, dtype=torch.int32, device="cuda"), n_dist, inter)
+    torch.cuda.synchronize()
+    inter_ref, pairs_ref, mean_ref = A.overlap_by_distance(mg, pos, x["seq_lens"], cfg.block_size, cfg.k_blocks, n_dist)
+    np.testing.assert_array_equal(inter.cpu().numpy(), inter_ref)
+    if n_dist == max(pos) + 2:
+        assert inter_ref[:, -1].sum() == 0 and pairs_ref[-1] == 0
+    live = np.isfinite(mean_ref)
+    assert ((mean_ref[live] >= 0) & (mean_ref[live] <= 1)).all()
+
+
+def test_jaccard_of_adjacent_layers_and_anchor_choice():
+    """Eq. 7 on the first-draft masks of six layers (the workload plants the same blocks inside a reuse
+    group of two layers), then Eq. 8."""
+    cfg = W.shrink(W.CONFIGS[3], 8192)
+    n_layers = 6
+    shape = None
+    stack = []
+    for layer in range(n_layers):
+        x = W.make_layer(cfg, layer)
+        run = GpuRun(cfg, to_gpu(x))
+        shape = run.shape
+        run.block_reps().score_select()
+        m = torch.empty((cfg.B, cfg.Hkv, S.svf_mask_words(shape)), dtype=torch.int64, device="cuda")
+        S.svf_masks_from_selection(shape, run.sel_idx, run.sel_cnt, m)
+        stack.append(m)
+    masks = torch.stack(stack).contiguous()
+    iu = torch.full((n_layers, 2), -1, dtype=torch.int64, device="cuda")
+    S.svf_jaccard_adjacent(shape, masks, n_layers, iu)
+    torch.cuda.synchronize()
+    bits = unpack(masks.cpu().numpy().view(np.uint64), cfg.nb_max)
+    inter_ref, union_ref, J_ref = A.jaccard_adjacent(bits)
+    got = iu.cpu().numpy()
+    np.testing.assert_array_equal(got[:, 0], inter_ref)
+    np.testing.assert_array_equal(got[:, 1], union_ref)
+    assert got[0].tolist() == [0, 0]
+    J = [0.0] + [got[l, 0] / got[l, 1] for l in range(1, n_layers)]
+    np.testing.assert_allclose(J, J_ref, rtol=0, atol=0)
+    assert S.svf_topk_anchors(J, 3) == A.topk_anchors(J_ref, 3) == [0, 2, 4]
+
+
+def test_constructed_masks_give_closed_form_counts():
+    """Masks written by hand: the kernels must return the counts known by construction."""
+    cfg = small(B=1, Hkv=2, Hq=4, gamma=4, T=2048, k_blocks=4)
+    shape = shape_for(cfg, to_gpu(W.make_layer(cfg)))
+    Wd = S.svf_mask_words(shape)
+    m = np.zeros((1, 2, 4, cfg.nb_max), dtype=bool)
+    m[:, :, 0, [0, 1, 2, 3]] = True
+    m[:, :, 1, [0, 1, 2, 3]] = True
+    m[:, :, 2, [2, 3, 4, 5]] = True
+    m[:, :, 3, [10, 11, 12, 13]] = True
+    words = torch.from_numpy(A.pack_masks(m).view(np.int64)).cuda()
+    assert words.shape[-1] == Wd
+    inter = torch.empty((1, 4), dtype=torch.int64, device="cuda")
+    S.svf_overlap_by_distance(shape, words, torch.tensor([0, 1, 2, 3], dtype=torch.int32, device="cuda"), 4, inter)
+    layers = torch.stack([words[:, :, 0], words[:, :, 1], words[:, :, 2], words[:, :, 3]]).contiguous()
+    iu = torch.empty((4, 2), dtype=torch.int64, device="cuda")
+    S.svf_jaccard_adjacent(shape, layers, 4, iu)
+    torch.cuda.synchronize()
+    assert inter.cpu().tolist() == [[0, 12, 4, 0]]
+    assert iu.cpu().tolist() == [[0, 0], [8, 8], [4, 12], [0, 16]]
