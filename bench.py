@@ -48,7 +48,118 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=8, help="layers the CPU oracle is timed on")
     ap.add_argument("--profile-only", default="", help="run only this many steps of the timed loop (for rocprofv3)")
+    ap.add_argument("--analytics", action="store_true",
+                    help="time the retrieval analytics (per-draft block sets, overlap, Jaccard) instead of the step")
     return ap.parse_args()
+
+
+def analytics(args):
+    """Retrieval analytics on a 60-draft tree (the shape Sec. 2.2 analyses) over cfg 3's cache:
+    per-draft block sets of one layer, their overlap by positional distance, and the Jaccard counts of
+    32 layers' first-draft masks.  One JSON line; the roofline object is for the per-draft retrieval
+    (one pass over the fp32 representatives)."""
+    import dataclasses
+    import numpy as np
+    import torch
+    import paper_2512_21911_amd as S
+    import workloads as W
+    from oracle import svf_analytics_oracle as A
+    from oracle import svf_oracle as O
+
+    torch.cuda.set_device(0)
+    S.lib()
+    base = W.CONFIGS[3]
+    cfg = dataclasses.replace(base, name="cfg3_cache_tree60", gamma=60, tree_depth=6, n_layers=1)
+    n_rep = 16                                            # independent layers, so no launch re-reads a cached one
+    layers = [W.make_layer(cfg, l, device="cuda") for l in range(n_rep)]
+    x0 = layers[0]
+    shape = S.make_shape(B=cfg.B, gamma=cfg.gamma, Hq=cfg.Hq, Hkv=cfg.Hkv, d=cfg.d, dtype=cfg.dtype,
+                         block_size=cfg.block_size, max_seq_len=cfg.T, k_blocks=cfg.k_blocks, k_pool=x0["k_pool"],
+                         page_size=cfg.page_size, max_pages_per_seq=x0["block_table"].shape[1],
+                         n_sink=cfg.n_sink, n_local=cfg.n_local)
+    Wd = S.svf_mask_words(shape)
+    reps = [torch.zeros(cfg.B, cfg.Hkv, cfg.nb_max, cfg.d, device="cuda") for _ in range(n_rep)]
+    for l, x in enumerate(layers):
+        S.svf_block_reps(shape, x["k_pool"], x["block_table"], x["seq_lens"], reps[l])
+    masks = [torch.zeros(cfg.B, cfg.Hkv, cfg.gamma, Wd, dtype=torch.int64, device="cuda") for _ in range(n_rep)]
+    ws = S.new_analytics_workspace(shape)
+    parents = W.draft_tree(cfg).tolist()
+    pos = [0] * cfg.gamma
+    for i, p in enumerate(parents):
+        pos[i] = 0 if p < 0 else pos[p] + 1
+    n_dist = max(pos) + 1
+    pos_d = torch.tensor(pos, dtype=torch.int32, device="cuda")
+    inter = torch.zeros(cfg.B, n_dist, dtype=torch.int64, device="cuda")
+    n_jl = 32
+    layer_masks = torch.stack([masks[l % n_rep][:, :, 0] for l in range(n_jl)]).contiguous()
+    iu = torch.zeros(n_jl, 2, dtype=torch.int64, device="cuda")
+
+    def timed(fn, iters, warm):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(iters):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / iters * 1e3            # us per call of fn
+
+    def select_all():
+        for l, x in enumerate(layers):
+            S.svf_select_per_draft(shape, x["q"], reps[l], x["seq_lens"], masks[l], ws)
+
+    us_select = timed(select_all, args.steps, args.warmup) / n_rep
+    us_overlap = timed(lambda: S.svf_overlap_by_distance(shape, masks[0], pos_d, n_dist, inter), args.steps, args.warmup)
+    us_jaccard = timed(lambda: S.svf_jaccard_adjacent(shape, layer_masks, n_jl, iu), args.steps, args.warmup)
+
+    # algorithmic bytes of the per-draft retrieval: representatives once, queries, masks out
+    nb = cfg.nb_max
+    bytes_select = (cfg.B * cfg.Hkv * nb * cfg.d * 4 + cfg.B * cfg.gamma * cfg.Hq * cfg.d * 2
+                    + cfg.B * cfg.Hkv * cfg.gamma * Wd * 8)
+    gbps = bytes_select / (us_select * 1e-6) / 1e9
+
+    # CPU oracle on the same layer (CPU-generated tensors of the same recipe), checked against the GPU
+    xc = W.make_layer(cfg, 0, device="cpu")
+    w0, c0 = time.perf_counter(), time.process_time()
+    reps_ref = O.block_reps(xc["k_pool"], xc["block_table"], xc["seq_lens"], cfg.block_size, cfg.nb_max)
+    t_reps = time.perf_counter() - w0
+    w1 = time.perf_counter()
+    s_ref = A.per_draft_scores(xc["q"], reps_ref)
+    m_ref = A.per_draft_masks(s_ref, xc["seq_lens"], cfg.block_size, cfg.k_blocks)
+    inter_ref, pairs_ref, mean_ref = A.overlap_by_distance(m_ref, pos, xc["seq_lens"], cfg.block_size, cfg.k_blocks, n_dist)
+    wall = time.perf_counter() - w1
+    cpu_t = time.process_time() - c0
+    xg = {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in xc.items()}
+    rg = torch.zeros_like(reps[0])
+    mg = torch.zeros_like(masks[0])
+    S.svf_block_reps(shape, xg["k_pool"], xg["block_table"], xg["seq_lens"], rg)
+    S.svf_select_per_draft(shape, xg["q"], rg, xg["seq_lens"], mg, ws)
+    S.svf_overlap_by_distance(shape, mg, pos_d, n_dist, inter)
+    torch.cuda.synchronize()
+    same_masks = bool(np.array_equal(mg.cpu().numpy().view(np.uint64), A.pack_masks(m_ref)))
+    same_inter = bool(np.array_equal(inter.cpu().numpy(), inter_ref))
+    if not (same_masks and same_inter):
+        raise SystemExit("bench --analytics: GPU masks / overlap counts differ from the oracle on the sampled layer")
+    line = {
+        "metric": "per-draft retrieval us/layer (60-draft tree, 32k ctx)", "value": round(us_select, 2), "unit": "us/layer",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us_select * 1e-3, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "d": cfg.d, "T": cfg.T,
+                   "block_size": cfg.block_size, "gamma": cfg.gamma, "tree_depth": cfg.tree_depth,
+                   "k_blocks": cfg.k_blocks, "launch": "stream"},
+        "roofline": {"bound": "hbm", "kernel": "block_scores_all_kernel + select_kernel", "achieved": round(gbps, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": bytes_select, "avg_launch_us": round(us_select, 3)},
+        "cpu_baseline": {"value": round(wall * 1e6, 1), "unit": "us/layer",
+                         "cores": max(1, int(round(cpu_t / max(wall + t_reps, 1e-9)))), "kind": "oracle",
+                         "sample": "oracle per-draft scores + masks + overlap on layer 0 (representatives excluded); "
+                                   "GPU masks and overlap counts identical"},
+        "extra": {"overlap_by_distance_us": round(us_overlap, 2), "jaccard_32_layers_us": round(us_jaccard, 2),
+                  "mean_overlap_by_distance": [None if not np.isfinite(v) else round(float(v), 4) for v in mean_ref]},
+    }
+    print(json.dumps(line))
 
 
 def main():
@@ -63,6 +174,9 @@ def main():
     import workloads as W
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.analytics:
+        analytics(args)
+        return
     S.lib()                      # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
     cfg = W.CONFIGS[args.cfg]

@@ -74,38 +74,44 @@ __global__ __launch_bounds__(kThreads) void block_scores_kernel(SelectParams p) 
 // Scores of every draft token's query (Sec. 2.2: retrieval "based on their respective query
 // values"), one pass over the representatives: the rows a thread holds are scored against the
 // gamma mean queries in LDS, with the arithmetic of the kernel above (query 0 gives the same bits).
-// grid: (ceil(nb_max / (kPasses * blocks per pass)), Hkv, B); scores [B][gamma][Hkv][nb_max]
-constexpr int kMaxDrafts = 64;
+// grid: (ceil(nb_max / (kPasses * blocks per pass)) * ceil(gamma / kDraftsPerGroup), Hkv, B): a
+// workgroup scores its rows against one group of drafts (the rows' other readers find them in L2);
+// scores [B][gamma][Hkv][nb_max]
+constexpr int kDraftsPerGroup = 8;
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void block_scores_all_kernel(SelectParams p) {
   constexpr int LPB = kScoreLanes;
   constexpr int NCH = D / (4 * LPB);
   constexpr int BPW = kThreads / LPB;
-  __shared__ __attribute__((aligned(16))) float qs[kMaxDrafts][D];
+  __shared__ __attribute__((aligned(16))) float qs[kDraftsPerGroup][D];
 
   const int b = blockIdx.z, h = blockIdx.y;
+  const int n_chunks = (p.nb_max + kPasses * BPW - 1) / (kPasses * BPW);
+  const int chunk = blockIdx.x % n_chunks;
+  const int i0 = (blockIdx.x / n_chunks) * kDraftsPerGroup;      // first draft of this workgroup's group
+  const int n_i = min(kDraftsPerGroup, p.gamma - i0);
   const int G = p.Hq / p.Hkv;
   const int sub = threadIdx.x % LPB;
   float4 r[kPasses][NCH];
   int jj[kPasses];
 #pragma unroll
   for (int u = 0; u < kPasses; ++u) {
-    const int j = (blockIdx.x * kPasses + u) * BPW + threadIdx.x / LPB;
+    const int j = (chunk * kPasses + u) * BPW + threadIdx.x / LPB;
     jj[u] = j;
     const int jc = j < p.nb_max ? j : p.nb_max - 1;
     const float* row = p.reps + (((int64_t)b * p.Hkv + h) * p.nb_max + jc) * D + sub * 4;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) r[u][i] = *reinterpret_cast<const float4*>(row + i * 4 * LPB);
   }
-  for (int idx = threadIdx.x; idx < p.gamma * D; idx += kThreads) {
+  for (int idx = threadIdx.x; idx < n_i * D; idx += kThreads) {
     const int i = idx / D, c = idx - i * D;
-    const T* qch = static_cast<const T*>(p.q) + (((int64_t)b * p.gamma + i) * p.Hq + (int64_t)h * G) * D + c;
+    const T* qch = static_cast<const T*>(p.q) + (((int64_t)b * p.gamma + i0 + i) * p.Hq + (int64_t)h * G) * D + c;
     qs[i][c] = mean_query_channel<T>(load_query_heads<T>(qch, G, D), qch, G, D);
   }
   const int L = clamped_len(p.seq_lens, b, p.max_seq_len);
   const int nb = (L + p.block_size - 1) / p.block_size;
   __syncthreads();
-  for (int i = 0; i < p.gamma; ++i) {
+  for (int i = 0; i < n_i; ++i) {
     float4 qv[NCH];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) qv[c] = *reinterpret_cast<const float4*>(&qs[i][sub * 4 + c * 4 * LPB]);
@@ -113,7 +119,7 @@ __global__ __launch_bounds__(kThreads) void block_scores_all_kernel(SelectParams
     for (int u = 0; u < kPasses; ++u) {
       const float v = block_score<NCH>(r[u], qv);
       if (sub == 0 && jj[u] < p.nb_max)
-        p.scores[(((int64_t)b * p.gamma + i) * p.Hkv + h) * p.nb_max + jj[u]] = jj[u] < nb ? v + 0.0f : 0.0f;
+        p.scores[(((int64_t)b * p.gamma + i0 + i) * p.Hkv + h) * p.nb_max + jj[u]] = jj[u] < nb ? v + 0.0f : 0.0f;
     }
   }
 }
@@ -260,6 +266,7 @@ hipError_t launch_score_select(const SelectParams& p, int dtype, hipStream_t st)
   const int bpw = kPasses * (kThreads / kScoreLanes);
   dim3 g1((p.nb_max + bpw - 1) / bpw, p.Hkv, p.B);
   if (p.nq > 1) {
+    g1.x *= (unsigned)((p.gamma + kDraftsPerGroup - 1) / kDraftsPerGroup);
     if (dtype == SVF_F32) {
       if (p.d == 64) hipLaunchKernelGGL((block_scores_all_kernel<float, 64>), g1, dim3(kThreads), 0, st, p);
       else hipLaunchKernelGGL((block_scores_all_kernel<float, 128>), g1, dim3(kThreads), 0, st, p);
