@@ -420,6 +420,202 @@ __device__ __forceinline__ void workgroup_select(const uint32_t* keys, SelectScr
   }
 }
 
+// ---- retrieval inside the attention kernel (anchor layers) ------------------------------------
+// q0 = mean first-draft query of the group, key[j] = order-preserving key of q0 . rep[j] (forced
+// sink / local blocks get the largest key), top-cnt by the workgroup.  With more than one split
+// the workgroups of an exchange group share the scoring: each scores every n_splits-th pass of 64
+// blocks and publishes its keys as 64-bit words (key, tag of this call); the others poll those
+// words.  The tag is a per-group counter in the workspace that moves on by one per call.
+constexpr int kScoreChunks = kD / (4 * kScoreLanes);   // 16-byte chunks of a representative per lane
+constexpr int kScoreBatch = 8;                         // passes (of 64 blocks) in flight
+
+// What a retrieving workgroup loads up front, together with its query loads.
+struct RetrievalLoads {
+  QueryHeads<__hip_bfloat16> q0h;       // channel tid mod 128 of the group's first-draft query heads
+  const __hip_bfloat16* q0ch;
+  const int32_t* table_row;             // the sequence's page-table row ...
+  int32_t tbl[kTableLoads];             // ... and this thread's entries of it, on their way to LDS
+  bool table_in_lds;
+  bool share_scores;
+  uint32_t tag;                         // the group's counter as loaded; retrieve_blocks() adds one
+  int rot;                              // first pass of a workgroup that scores alone
+  float4 r[kScoreBatch][kScoreChunks];  // first batch of representative rows
+};
+
+__device__ __forceinline__ const float* reps_lane_ptr(const AttnParams& p, int pair, int tid) {
+  return p.reps + (int64_t)pair * p.nb_max * kD + (tid % kScoreLanes) * 4;
+}
+
+// Loads the representative rows of passes first, first + stride, ... into r (pass = 64 blocks).
+__device__ __forceinline__ void load_score_batch(const AttnParams& p, const float* rp, int jrow, int first, int stride,
+                                                 bool rotate, int rot, float4 (&r)[kScoreBatch][kScoreChunks]) {
+#pragma unroll
+  for (int u = 0; u < kScoreBatch; ++u) {
+    const int ps = first + stride * (rotate ? (u + rot) % kScoreBatch : u);
+    if (ps * 64 < p.nb_max) {
+      const float* row = rp + (int64_t)min(ps * 64 + jrow, p.nb_max - 1) * kD;
+#pragma unroll
+      for (int i = 0; i < kScoreChunks; ++i) r[u][i] = *reinterpret_cast<const float4*>(row + i * 4 * kScoreLanes);
+    }
+  }
+}
+
+__device__ __forceinline__ RetrievalLoads issue_retrieval_loads(const AttnParams& p, int b, int h, int pair, int split,
+                                                                int xgroup, int rot, int tid, int vzero) {
+  RetrievalLoads R;
+  // first in the queue, so that nothing slower has to come back before it
+  R.q0ch = static_cast<const __hip_bfloat16*>(p.q) + ((int64_t)b * p.gamma * p.Hq + (int64_t)h * p.G) * kD + (tid & (kD - 1));
+  R.q0h = load_query_heads<__hip_bfloat16>(R.q0ch, p.G, kD);
+  // the page-table row goes to LDS while the scores are computed, so that turning kept blocks
+  // into addresses afterwards costs no further trip to memory
+  R.table_row = p.table + (int64_t)b * p.kv.max_pages;
+  R.table_in_lds = p.kv.page_size != 0 && p.kv.max_pages <= kTableLoads * kThreads;
+  R.share_scores = p.n_splits >= 2 && p.poll_budget > 0;
+  R.tag = p.epochs[xgroup + vzero];
+  R.rot = rot;
+  if (R.table_in_lds) {
+#pragma unroll
+    for (int u = 0; u < kTableLoads; ++u)
+      if (u * kThreads < p.kv.max_pages) R.tbl[u] = R.table_row[min(tid + u * kThreads, p.kv.max_pages - 1)];
+  }
+  return R;
+}
+
+// The first batch of representative rows: this workgroup's share, or the first passes of all.
+__device__ __forceinline__ void issue_first_score_batch(const AttnParams& p, RetrievalLoads& R, int pair, int split,
+                                                        int tid) {
+  const float* rp = reps_lane_ptr(p, pair, tid);
+  if (R.share_scores) load_score_batch(p, rp, tid / kScoreLanes, split, p.n_splits, false, R.rot, R.r);
+  else load_score_batch(p, rp, tid / kScoreLanes, 0, 1, true, R.rot, R.r);
+}
+
+struct Retrieved {
+  int L, cnt;
+  uint32_t tag;
+  const int32_t* s_table;               // the page-table row in LDS (valid if table_in_lds)
+};
+
+// Scores, exchange, selection.  On return s_sel[0 .. cnt) holds the kept blocks (ascending) and
+// every thread has passed the barrier behind the selection.  The scratch arrays live in stage 0
+// and the page-table row in the stages after it; the caller must not stream into them before
+// its own next barrier.  L_raw: the sequence length as loaded (per lane, not yet uniform).
+__device__ __forceinline__ Retrieved retrieve_blocks(const AttnParams& p, RetrievalLoads& R, unsigned char* smem,
+                                                     int32_t* s_sel, int* s_exchange_failed, int L_raw, int pair,
+                                                     int split, int xgroup, int tid, int lane, int wave) {
+  int32_t* s_table = reinterpret_cast<int32_t*>(smem + kStageBytes);
+  float* s_q0 = reinterpret_cast<float*>(smem);
+  uint32_t* s_keys = reinterpret_cast<uint32_t*>(smem + kD * 4);
+  SelectScratch* s_sc = reinterpret_cast<SelectScratch*>(smem + kD * 4 + kMaxSelectBlocks * 4);
+  const int sub = tid % kScoreLanes, jrow = tid / kScoreLanes;
+  const float* rp = reps_lane_ptr(p, pair, tid);
+  uint64_t* const xk = p.xkeys + (int64_t)xgroup * p.nb_max;
+
+  if (tid < kD) s_q0[tid] = mean_query_channel<__hip_bfloat16>(R.q0h, R.q0ch, p.G, kD);
+  for (int i = tid; i < 4 * 256; i += kThreads) (&s_sc->hist[0][0])[i] = 0;
+  if (tid == 0) *s_exchange_failed = 0;
+  if (R.table_in_lds) {
+#pragma unroll
+    for (int u = 0; u < kTableLoads; ++u)
+      if (tid + u * kThreads < p.kv.max_pages) s_table[tid + u * kThreads] = R.tbl[u];
+  }
+  __syncthreads();
+  Retrieved out;
+  out.L = __builtin_amdgcn_readfirstlane(L_raw);
+  out.s_table = s_table;
+  const int nb = (out.L + p.block_size - 1) / p.block_size;
+  out.cnt = min(p.k_blocks, nb);
+  out.tag = (uint32_t)__builtin_amdgcn_readfirstlane((int)R.tag) + 1u;
+  const uint32_t tag = out.tag;
+  float4 qv[kScoreChunks];
+#pragma unroll
+  for (int i = 0; i < kScoreChunks; ++i) qv[i] = *reinterpret_cast<const float4*>(s_q0 + sub * 4 + i * 4 * kScoreLanes);
+  // scores the rows in R.r (passes first, first + stride, ...): keys go to LDS and, if published,
+  // tagged to the group's exchange array through a write-through store
+  auto score_batch = [&](int first, int stride, bool rotate, bool publish) {
+#pragma unroll
+    for (int u = 0; u < kScoreBatch; ++u) {
+      const int ps = first + stride * (rotate ? (u + R.rot) % kScoreBatch : u);
+      if (ps * 64 < nb) {                              // uniform
+        const float v = block_score<kScoreChunks>(R.r[u], qv);
+        const int j = ps * 64 + jrow;
+        if (sub == 0 && j < nb) {
+          const uint32_t key = (j < p.n_sink || j >= nb - p.n_local) ? 0xffffffffu : score_key(v + 0.0f);
+          s_keys[j] = key;
+          if (publish)
+            __hip_atomic_store(xk + j, (uint64_t)key | ((uint64_t)tag << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+    }
+  };
+  bool score_alone = !R.share_scores;
+  if (R.share_scores) {
+    // this workgroup's share (nb <= 1024 = 16 passes, at least two splits: one batch), then
+    // the others' keys: a key is valid once its word carries this call's tag.  The wait is
+    // bounded; a workgroup that runs out of patience scores everything itself.
+    score_batch(split, p.n_splits, false, true);
+    const int j0 = tid, j1 = tid + kThreads;
+    bool need0 = j0 < nb && ((j0 >> 6) % p.n_splits) != split;
+    bool need1 = j1 < nb && ((j1 >> 6) % p.n_splits) != split;
+    const bool mine0 = need0, mine1 = need1;
+    uint32_t got0 = 0, got1 = 0;
+    for (int it = 0; it < p.poll_budget; ++it) {
+      if (need0) {
+        const uint64_t w = __hip_atomic_load(xk + j0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((uint32_t)(w >> 32) == tag) { got0 = (uint32_t)w; need0 = false; }
+      }
+      if (need1) {
+        const uint64_t w = __hip_atomic_load(xk + j1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((uint32_t)(w >> 32) == tag) { got1 = (uint32_t)w; need1 = false; }
+      }
+      if (!__any(need0 || need1)) break;
+    }
+    if (need0 || need1) *s_exchange_failed = 1;
+    if (mine0 && !need0) s_keys[j0] = got0;
+    if (mine1 && !need1) s_keys[j1] = got1;
+    __syncthreads();
+    score_alone = *s_exchange_failed != 0;
+  }
+  if (score_alone) {
+    const bool loaded = !R.share_scores;               // the up-front batch was this one
+    for (int f = 0; f * 64 < nb; f += kScoreBatch) {
+      if (!(loaded && f == 0)) load_score_batch(p, rp, jrow, f, 1, true, R.rot, R.r);
+      score_batch(f, 1, true, false);
+    }
+  }
+  __syncthreads();
+  if (out.cnt > 0) workgroup_select(s_keys, s_sc, nb, out.cnt, s_sel, tid, lane, wave);
+  __syncthreads();
+  return out;
+}
+
+// Gather entry of the four selected-token slots 4e .. 4e+3 from the selection in LDS.
+__device__ __forceinline__ uint64_t gather_entry_of(const AttnParams& p, const int32_t* s_sel, const Retrieved& rt,
+                                                    const RetrievalLoads& R, int e, int b, int h) {
+  const int slot0 = 4 * e;
+  if (slot0 >= rt.cnt * p.block_size) return 0ull;
+  const int bi = p.block_shift >= 0 ? slot0 >> p.block_shift : slot0 / p.block_size;
+  const int tok0 = s_sel[bi] * p.block_size + (slot0 - bi * p.block_size);
+  const int nv = min(max(rt.L - tok0, 0), 4);
+  if (nv <= 0) return 0ull;
+  int64_t row;                                         // element offset of the token's row of head 0
+  if (p.kv.page_size == 0) {
+    row = (int64_t)b * p.kv.stride_page + (int64_t)tok0 * p.kv.stride_tok;
+  } else {
+    const int pg = p.kv.page_shift >= 0 ? tok0 >> p.kv.page_shift : tok0 / p.kv.page_size;
+    const int phys = R.table_in_lds ? rt.s_table[pg] : R.table_row[pg];
+    row = (int64_t)phys * p.kv.stride_page + (int64_t)(tok0 - pg * p.kv.page_size) * p.kv.stride_tok;
+  }
+  const uint64_t off = (uint64_t)((row + (int64_t)h * p.kv.stride_head) * 2);
+  return (off & kGatherOffsetMask) | ((uint64_t)nv << kGatherCountShift);
+}
+
+// One workgroup of the pair publishes the selection for the layers that reuse it.
+__device__ __forceinline__ void publish_selection(const AttnParams& p, const int32_t* s_sel, int cnt, int pair, int tid) {
+  int32_t* out_idx = p.sel_idx_out + (int64_t)pair * p.k_blocks;
+  for (int i = tid; i < p.k_blocks; i += kThreads) out_idx[i] = i < cnt ? s_sel[i] : -1;
+  if (tid == 0) p.sel_cnt_out[pair] = cnt;
+}
+
 // What the main loop has to know about a tile whose loads have been issued.
 struct TileInfo {
   uint32_t valid;      // bit s set: slot s holds a real token
@@ -495,27 +691,11 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     qi = (int)(((uint64_t)(uint32_t)row * p.g_magic) >> 32);            // row / G
     qj = row - qi * p.G;
   }
-  // (retrieval only) channel tid of the group's mean first-draft query: first in the queue, so
-  // that nothing slower has to come back before it
-  const __hip_bfloat16* const q0ch =
-      static_cast<const __hip_bfloat16*>(p.q) + ((int64_t)b * p.gamma * p.Hq + (int64_t)h * p.G) * kD + (tid & (kD - 1));
-  QueryHeads<__hip_bfloat16> q0h;
-  if (MODE == kSelect) q0h = load_query_heads<__hip_bfloat16>(q0ch, p.G, kD);
-  // (retrieval only) the sequence's page-table row goes to LDS while the scores are computed, so
-  // that turning kept blocks into addresses afterwards costs no further trip to memory
+  // (retrieval only) what the retrieval needs goes out first, ahead of the query fragments
+  RetrievalLoads rl;
+  if (MODE == kSelect)
+    rl = issue_retrieval_loads(p, b, h, pair, split, group, (split + rg * p.n_splits) % kScoreBatch, tid, vzero);
   const int32_t* const table_row = p.table + (int64_t)b * p.kv.max_pages;
-  const bool table_in_lds = MODE == kSelect && p.kv.page_size != 0 && p.kv.max_pages <= kTableLoads * kThreads;
-  // (retrieval only) with more than one split the workgroups of a group share the scoring; the
-  // tag marks the keys of this call (the group's counter moves on by one per call)
-  const bool share_scores = MODE == kSelect && p.n_splits >= 2 && p.poll_budget > 0;
-  uint32_t tag = 0;
-  if (MODE == kSelect) tag = p.epochs[group + vzero];              // + 1 once it has arrived
-  int32_t tbl[kTableLoads];
-  if (MODE == kSelect && table_in_lds) {
-#pragma unroll
-    for (int u = 0; u < kTableLoads; ++u)
-      if (u * kThreads < p.kv.max_pages) tbl[u] = table_row[min(tid + u * kThreads, p.kv.max_pages - 1)];
-  }
   bf16x8 qf[8];
   {
     const __hip_bfloat16* qrow = static_cast<const __hip_bfloat16*>(p.q) +
@@ -535,141 +715,23 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   }
   int L = 0;
   if (MODE != kGather) L = clamped_len(p.seq_lens, b + vzero, p.max_seq_len);
+  if (MODE == kSelect) issue_first_score_batch(p, rl, pair, split, tid);
   int cnt;
+  uint32_t tag = 0;                  // (retrieval only) this call's tag of the key exchange
   if (MODE == kSelect) {
-    // ---- retrieval: q0 = mean first-draft query of the group, key[j] = order-preserving key of
-    // q0 . rep[j] (forced sink / local blocks get the largest key), top-cnt by wavefront 0.
-    // The scratch arrays live in stage 0 and the page-table row in the stages after it; nobody
-    // streams into them before the last barrier of this part.
-    int32_t* s_table = reinterpret_cast<int32_t*>(smem + kStageBytes);
-    float* s_q0 = reinterpret_cast<float*>(smem);
-    uint32_t* s_keys = reinterpret_cast<uint32_t*>(smem + kD * 4);
-    SelectScratch* s_sc = reinterpret_cast<SelectScratch*>(smem + kD * 4 + kMaxSelectBlocks * 4);
-    int nb = 0;                                        // known once the length has arrived
-    constexpr int kNch = kD / (4 * kScoreLanes);       // 16-byte chunks of a representative per lane
-    constexpr int kBatch = 8;                          // passes (of 64 blocks) in flight
-    const int sub = tid % kScoreLanes, jrow = tid / kScoreLanes;
-    const float* rp = p.reps + (int64_t)pair * p.nb_max * kD + sub * 4;
-    uint64_t* const xk = p.xkeys + (int64_t)group * p.nb_max;
-    // workgroups that walk the same rows each start at another pass, so that they do not all
-    // queue at the same memory channel
-    const int rot = (split + rg * p.n_splits) % kBatch;
-    float4 r[kBatch][kNch];
-    float4 qv[kNch];
-    // One batch of passes first, first + stride, ... (pass = 64 consecutive blocks): optionally
-    // load the rows, then score them; keys go to LDS and, if published, tagged to the group's
-    // exchange array through a write-through store.
-    auto batch = [&](int first, int stride, bool rotate, bool load, bool score, bool publish) {
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const int ps = first + stride * (rotate ? (u + rot) % kBatch : u);
-        if (load && ps * 64 < p.nb_max) {
-          const float* row = rp + (int64_t)min(ps * 64 + jrow, p.nb_max - 1) * kD;
-#pragma unroll
-          for (int i = 0; i < kNch; ++i) r[u][i] = *reinterpret_cast<const float4*>(row + i * 4 * kScoreLanes);
-        }
-      }
-      if (!score) return;
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const int ps = first + stride * (rotate ? (u + rot) % kBatch : u);
-        if (ps * 64 < nb) {                            // uniform
-          const float v = block_score<kNch>(r[u], qv);
-          const int j = ps * 64 + jrow;
-          if (sub == 0 && j < nb) {
-            const uint32_t key = (j < p.n_sink || j >= nb - p.n_local) ? 0xffffffffu : score_key(v + 0.0f);
-            s_keys[j] = key;
-            if (publish)
-              __hip_atomic_store(xk + j, (uint64_t)key | ((uint64_t)tag << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          }
-        }
-      }
-    };
-    // the first batch goes out with the query loads
-    if (share_scores) batch(split, p.n_splits, false, true, false, false);
-    else batch(0, 1, true, true, false, false);
-    if (tid < kD) s_q0[tid] = mean_query_channel<__hip_bfloat16>(q0h, q0ch, p.G, kD);
-    for (int i = tid; i < 4 * 256; i += kThreads) (&s_sc->hist[0][0])[i] = 0;
-    if (tid == 0) s_exchange_failed = 0;
-    if (table_in_lds) {
-#pragma unroll
-      for (int u = 0; u < kTableLoads; ++u)
-        if (tid + u * kThreads < p.kv.max_pages) s_table[tid + u * kThreads] = tbl[u];
-    }
-    __syncthreads();
-    L = __builtin_amdgcn_readfirstlane(L);
-    nb = (L + p.block_size - 1) / p.block_size;
-    cnt = min(p.k_blocks, nb);
-    tag = (uint32_t)__builtin_amdgcn_readfirstlane((int)tag) + 1u;
-#pragma unroll
-    for (int i = 0; i < kNch; ++i) qv[i] = *reinterpret_cast<const float4*>(s_q0 + sub * 4 + i * 4 * kScoreLanes);
-    bool score_alone = !share_scores;
-    if (share_scores) {
-      // this workgroup's share (nb <= 1024 = 16 passes, at least two splits: one batch), then
-      // the others' keys: a key is valid once its word carries this call's tag.  The wait is
-      // bounded; a workgroup that runs out of patience scores everything itself.
-      batch(split, p.n_splits, false, false, true, true);
-      const int j0 = tid, j1 = tid + kThreads;
-      bool need0 = j0 < nb && ((j0 >> 6) % p.n_splits) != split;
-      bool need1 = j1 < nb && ((j1 >> 6) % p.n_splits) != split;
-      const bool mine0 = need0, mine1 = need1;
-      uint32_t got0 = 0, got1 = 0;
-      for (int it = 0; it < p.poll_budget; ++it) {
-        if (need0) {
-          const uint64_t w = __hip_atomic_load(xk + j0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          if ((uint32_t)(w >> 32) == tag) { got0 = (uint32_t)w; need0 = false; }
-        }
-        if (need1) {
-          const uint64_t w = __hip_atomic_load(xk + j1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          if ((uint32_t)(w >> 32) == tag) { got1 = (uint32_t)w; need1 = false; }
-        }
-        if (!__any(need0 || need1)) break;
-      }
-      if (need0 || need1) s_exchange_failed = 1;
-      if (mine0 && !need0) s_keys[j0] = got0;
-      if (mine1 && !need1) s_keys[j1] = got1;
-      __syncthreads();
-      score_alone = s_exchange_failed != 0;
-    }
-    if (score_alone) {
-      const bool loaded = !share_scores;               // the up-front batch was this one
-      for (int f = 0; f * 64 < nb; f += kBatch) {
-        batch(f, 1, true, !(loaded && f == 0), true, false);
-      }
-    }
-    __syncthreads();
-    if (cnt > 0) workgroup_select(s_keys, s_sc, nb, cnt, s_sel, tid, lane, wave);
-    __syncthreads();
-    // one workgroup of the pair publishes the selection (the one with the least other work)
-    if (split == p.n_splits - 1 && rg == 0) {
-      int32_t* out_idx = p.sel_idx_out + (int64_t)pair * p.k_blocks;
-      for (int i = tid; i < p.k_blocks; i += kThreads) out_idx[i] = i < cnt ? s_sel[i] : -1;
-      if (tid == 0) p.sel_cnt_out[pair] = cnt;
-    }
+    const Retrieved rt = retrieve_blocks(p, rl, smem, s_sel, &s_exchange_failed, L, pair, split, group, tid, lane, wave);
+    L = rt.L;
+    cnt = rt.cnt;
+    tag = rt.tag;
+    // the workgroup with the least other work publishes the selection
+    if (split == p.n_splits - 1 && rg == 0) publish_selection(p, s_sel, cnt, pair, tid);
     // gather entries of this wavefront's tiles (lane 8u + n: group n of its u-th tile), kept for
     // the loads below and written out for the layers that reuse the selection
     {
-      const int tc = gw + (lane >> 3) * NW - (p.gamma + kTile - 1) / kTile;     // cache tile index
+      const int tc = gw + (lane >> 3) * NW - tiles_d;                          // cache tile index
       const int e = tc * 8 + (lane & 7);
       if (lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups) {
-        const int slot0 = 4 * e;
-        if (slot0 < cnt * p.block_size) {
-          const int bi = p.block_shift >= 0 ? slot0 >> p.block_shift : slot0 / p.block_size;
-          const int tok0 = s_sel[bi] * p.block_size + (slot0 - bi * p.block_size);
-          const int nv = min(max(L - tok0, 0), 4);
-          if (nv > 0) {
-            int64_t row;                               // element offset of the token's row of head 0
-            if (p.kv.page_size == 0) {
-              row = (int64_t)b * p.kv.stride_page + (int64_t)tok0 * p.kv.stride_tok;
-            } else {
-              const int pg = p.kv.page_shift >= 0 ? tok0 >> p.kv.page_shift : tok0 / p.kv.page_size;
-              const int phys = table_in_lds ? s_table[pg] : table_row[pg];
-              row = (int64_t)phys * p.kv.stride_page + (int64_t)(tok0 - pg * p.kv.page_size) * p.kv.stride_tok;
-            }
-            const uint64_t off = (uint64_t)((row + (int64_t)h * p.kv.stride_head) * 2);
-            gent = (off & kGatherOffsetMask) | ((uint64_t)nv << kGatherCountShift);
-          }
-        }
+        gent = gather_entry_of(p, s_sel, rt, rl, e, b, h);
         if (rg == 0) p.gather_out[(int64_t)pair * p.gather_groups + e] = gent;
       }
     }
@@ -916,7 +978,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   // coherence point, loads that bypass the per-CU cache are enough.
   const int64_t g_row = (int64_t)pair * p.n_splits * p.Mpad + orow_row;
   // every workgroup of the group is past the exchange of block keys: the next call gets a new tag
-  if (MODE == kSelect && share_scores && tid == 0) p.epochs[group] = tag;
+  if (MODE == kSelect && rl.share_scores && tid == 0) p.epochs[group] = tag;
   if (last_kind == 2) {
     merge_splits<true>(p, g_row, orow, rok, cg);
   } else {
