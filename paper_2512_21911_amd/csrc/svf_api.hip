@@ -14,6 +14,8 @@ hipError_t launch_verify_attn_valu(const AttnParams& p, int dtype, hipStream_t s
 hipError_t launch_verify_attn_mfma(const AttnParams& p, hipStream_t st);
 bool mfma_supported(const svf_shape_t& s);
 int mfma_splits(const svf_shape_t& s);
+bool mfma_rows_mode(const svf_shape_t& s);
+int mfma_rows_splits(const svf_shape_t& s);
 
 namespace {
 
@@ -87,7 +89,7 @@ AttnPlan plan_attn(const svf_shape_t& s) {
   pl.Mpad = (pl.M + 31) / 32 * 32;
   pl.mfma = mfma_supported(s);
   if (pl.mfma) {
-    pl.n_splits = mfma_splits(s);
+    pl.n_splits = mfma_rows_mode(s) ? mfma_rows_splits(s) : mfma_splits(s);
   } else {
     const int64_t tiles = ((int64_t)s.k_blocks * s.block_size + 31) / 32 + (s.gamma + 31) / 32;
     const int64_t groups = (int64_t)s.B * s.Hkv * (pl.Mpad / 32);

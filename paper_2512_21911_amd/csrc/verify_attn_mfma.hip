@@ -105,6 +105,15 @@ __device__ __forceinline__ void lds_wait8(T (&r)[8]) {
 }
 
 template <typename T>
+__device__ __forceinline__ void lds_wait2(T (&r)[2]) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0]), "+v"(r[1]) : : "memory");
+}
+// LDS store issued by hand (a compiler-issued one would first wait for every direct-to-LDS load in flight)
+__device__ __forceinline__ void lds_write4(uint32_t addr, uint32_t value) {
+  asm volatile("ds_write_b32 %0, %1" : : "v"(addr), "v"(value) : "memory");
+}
+
+template <typename T>
 __device__ __forceinline__ void lds_wait4(T (&r)[4]) {
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) : : "memory");
 }
@@ -121,13 +130,36 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // Stores of data exchanged between workgroups: device-scope write-through stores, so making
 // them visible across the chip's L2 slices needs no bulk write-back, only a wait for the
 // stores' acknowledgement.
+// (A store of more than eight bytes still reads its data registers in the cycle after it issues:
+// the wait state keeps whatever the compiler schedules next from overwriting them.  The compiler
+// inserts it by itself for its own stores, not behind an inline one.)
 __device__ __forceinline__ void store_coherent16(void* p, u32x4 bits) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(bits) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(bits) : "memory");
 }
 __device__ __forceinline__ void store_coherent2(float* p, float a, float b) {
   const uint64_t bits = (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32);
   __hip_atomic_store(reinterpret_cast<uint64_t*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void store_coherent8(void* p, u32x2 bits) {
+  const uint64_t w = (uint64_t)bits[0] | ((uint64_t)bits[1] << 32);
+  __hip_atomic_store(reinterpret_cast<uint64_t*>(p), w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// s_waitcnt vmcnt(n) for an even run-time n in 0 .. 16 (the count is an immediate of the instruction).
+__device__ __forceinline__ void wait_vmcnt_upto16(int n) {
+  switch (n) {
+    case 0: wait_vmcnt<0>(); break;
+    case 2: wait_vmcnt<2>(); break;
+    case 4: wait_vmcnt<4>(); break;
+    case 6: wait_vmcnt<6>(); break;
+    case 8: wait_vmcnt<8>(); break;
+    case 10: wait_vmcnt<10>(); break;
+    case 12: wait_vmcnt<12>(); break;
+    case 14: wait_vmcnt<14>(); break;
+    default: wait_vmcnt<16>(); break;
+  }
+}
+
 // Loads of a partial by the merging workgroup when the data is known to sit in, or behind,
 // this XCD's L2: only the per-CU cache has to be bypassed (sc0).  Issued by hand; the values are
 // not valid until merge_loads_wait() has been given the registers.
@@ -987,6 +1019,399 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   }
 }
 
+
+// ---- many query rows per KV head (more than two row groups, e.g. a 60-node draft tree) ----------
+// One workgroup per (pair, set of up to eight row groups, split); wavefront w owns row group w and
+// all wavefronts walk the same tiles, so a key/value row is fetched once for up to 256 query rows
+// instead of once per row group.  A tile is fetched by the eight wavefronts together (wavefront w
+// fetches the four-token group w: one K and one V load) into a ring of nine 16 KB stages; one
+// barrier per tile (after each wavefront has seen its own two loads land).  No combination through
+// LDS at the end: every wavefront writes its rows' partial itself, takes its row group's ticket
+// and, if it is the last, merges that row group's splits.
+constexpr int kRowStages = kWaves + 1;
+constexpr int kMaxRowTiles = 64;             // tiles per workgroup: one gather entry per lane
+
+// Merge of one row group's splits by one wavefront (rows kernel): two lanes per row, 64 channels
+// each, splits in order.  LOCAL: every partial was written through this XCD's L2 (hand-issued loads
+// that bypass the per-CU cache; a compile-time switch, so that no value of such a load meets a
+// compiler-tracked one at a join before its wait).
+template <bool LOCAL>
+__device__ __forceinline__ void merge_row_group(const AttnParams& p, int S, int pair, int row0, int64_t orow_pair,
+                                                int lane) {
+    const int r = lane >> 1, half = lane & 1;
+    const int mrow = row0 + r;
+    const uint16_t* part_o = reinterpret_cast<const uint16_t*>(p.part_o);
+    float acc[64];
+#pragma unroll
+    for (int c = 0; c < 64; ++c) acc[c] = 0.f;
+    float m_acc = -INFINITY, l_acc = 0.f;
+    for (int s0 = 0; s0 < S; s0 += 2) {
+      u32x4 t[2][8];
+      u32x2 ml[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int64_t pr = ((int64_t)pair * S + min(s0 + u, S - 1)) * p.Mpad + mrow;
+        const uint16_t* src = part_o + pr * kD + half * 64;
+        if (LOCAL) {
+          ml[u] = load8_bypass_l1(p.part_ml + 2 * pr);
+#pragma unroll
+          for (int c = 0; c < 8; ++c) t[u][c] = load16_bypass_l1(src + 8 * c);
+        } else {
+          ml[u] = *reinterpret_cast<const u32x2*>(p.part_ml + 2 * pr);
+#pragma unroll
+          for (int c = 0; c < 8; ++c) t[u][c] = *reinterpret_cast<const u32x4*>(src + 8 * c);
+        }
+      }
+      if (LOCAL) {                   // the hand-issued loads: all eighteen registers pass through the wait
+        asm volatile("s_waitcnt vmcnt(0)"
+                     : "+v"(t[0][0]), "+v"(t[0][1]), "+v"(t[0][2]), "+v"(t[0][3]), "+v"(t[0][4]), "+v"(t[0][5]),
+                       "+v"(t[0][6]), "+v"(t[0][7]), "+v"(t[1][0]), "+v"(t[1][1]), "+v"(t[1][2]), "+v"(t[1][3]),
+                       "+v"(t[1][4]), "+v"(t[1][5]), "+v"(t[1][6]), "+v"(t[1][7]), "+v"(ml[0]), "+v"(ml[1])
+                     :
+                     : "memory");
+      }
+      float pm[2], pl[2];
+      float mb = m_acc;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        pm[u] = s0 + u >= S ? -INFINITY : __uint_as_float(ml[u][0]);
+        pl[u] = __uint_as_float(ml[u][1]);
+        mb = fmaxf(mb, pm[u]);
+      }
+      const float fa = m_acc == -INFINITY ? 0.f : fast_exp2(m_acc - mb);
+      l_acc *= fa;
+#pragma unroll
+      for (int c = 0; c < 64; ++c) acc[c] *= fa;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const float w = pm[u] != -INFINITY ? fast_exp2(pm[u] - mb) * pl[u] : 0.f;
+        l_acc += w;
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            acc[8 * c + 2 * k] += w * bf16_lo(t[u][c][k]);
+            acc[8 * c + 2 * k + 1] += w * bf16_hi(t[u][c][k]);
+          }
+      }
+      m_acc = mb;
+    }
+    if (mrow < p.M) {
+      const int oi = (int)(((uint64_t)(uint32_t)mrow * p.g_magic) >> 32);
+      const int oj = mrow - oi * p.G;
+      const int64_t mo = orow_pair + (int64_t)oi * p.Hq + oj;
+      const float minv = 1.0f / l_acc;
+      __hip_bfloat16* o = static_cast<__hip_bfloat16*>(p.out) + mo * kD + half * 64;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        u32x4 w;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) w[k] = pack_bf16(acc[8 * c + 2 * k] * minv, acc[8 * c + 2 * k + 1] * minv);
+        store_coherent16(o + 8 * c, w);
+      }
+      if (p.lse && half == 0) p.lse[mo] = (m_acc + log2f(l_acc)) * 0.6931471805599453f;
+    }
+}
+
+// What a wavefront of the rows kernel needs to fetch its part of a tile.
+struct RowTileIssue {
+  unsigned char* smem;
+  const char* Kc;
+  const char* kd_pair;
+  int64_t dv_c, dv_d;
+  uint64_t gent;                 // lane u: gather entry of (u-th tile, this wavefront's group)
+  int split, S, tiles_d, gamma, wave, lane;
+  uint32_t lrow, cx, tok_bytes, drow_bytes, nv_lds;
+};
+
+// This wavefront's two loads of the workgroup's i-th tile (slots 4 * wave .. 4 * wave + 3), and the
+// number of real tokens among them, left in LDS for everybody.
+__device__ __forceinline__ void issue_row_tile(const RowTileIssue& c, int i) {
+  const int t = c.split + i * c.S;
+  const int st = i % kRowStages;
+  unsigned char* dst = c.smem + st * kStageBytes;
+  int nv;
+  const char* kb;
+  bool from_draft;
+  uint32_t row_bytes;
+  if (t < c.tiles_d) {
+    const int d0 = t * kTile + 4 * c.wave;
+    nv = min(max(c.gamma - d0, 0), 4);
+    kb = c.kd_pair + (int64_t)(nv > 0 ? d0 : 0) * c.drow_bytes;
+    from_draft = true;
+    row_bytes = c.drow_bytes;
+  } else {
+    const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)c.gent, i);
+    const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(c.gent >> 32), i);
+    const uint64_t ge = ((uint64_t)hi << 32) | lo;
+    nv = (int)(ge >> kGatherCountShift);
+    // (selections between two struct members are written with masks: as conditional loads they
+    // would pin the whole struct in scratch memory)
+    const uint64_t has = (uint64_t)0 - (uint64_t)(nv > 0);
+    kb = reinterpret_cast<const char*>(((uint64_t)(uintptr_t)c.Kc + (ge & kGatherOffsetMask)) & has |
+                                       (uint64_t)(uintptr_t)c.kd_pair & ~has);
+    from_draft = nv == 0;
+    row_bytes = c.tok_bytes;
+  }
+  const uint64_t fd = (uint64_t)0 - (uint64_t)from_draft;
+  const char* vb = kb + (int64_t)(((uint64_t)c.dv_d & fd) | ((uint64_t)c.dv_c & ~fd));
+  const uint32_t r = min(c.lrow, (uint32_t)max(nv - 1, 0));
+  const uint32_t off = r * row_bytes + ((c.cx ^ (uint32_t)((4 * c.wave) & 15)) << 4);
+  __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(kb + off), SVF_LDS_PTR(dst + c.wave * 1024), 16, 0, 0);
+  __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(vb + off), SVF_LDS_PTR(dst + kTileBytes + c.wave * 1024), 16, 0, 0);
+  if (c.lane == 0) lds_write4(c.nv_lds + (uint32_t)(st * kWaves + c.wave) * 4u, (uint32_t)nv);
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnParams p, int pairs) {
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[kRowStages * kStageBytes];
+  __shared__ __attribute__((aligned(16))) int32_t s_nv[kRowStages][kWaves];   // valid rows per four-token group
+  __shared__ int32_t s_sel[MODE == kSelect ? kMaxSelectBlocks : 1];
+  __shared__ int s_exchange_failed;
+
+  {
+    const __attribute__((address_space(4))) uint32_t* ka =
+        (const __attribute__((address_space(4))) uint32_t*)__builtin_amdgcn_kernarg_segment_ptr();
+    const uint32_t w0 = ka[0], w1 = ka[16], w2 = ka[32], w3 = ka[48], w4 = ka[64], w5 = ka[80];
+    asm volatile("" : : "s"(w0), "s"(w1), "s"(w2), "s"(w3), "s"(w4), "s"(w5));
+  }
+  int vzero;
+  asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
+  const int S = p.n_splits;
+  const int split = blockIdx.x / kXcds;
+  const int pair = blockIdx.y * kXcds + blockIdx.x % kXcds;
+  const int zs = blockIdx.z;                                   // which set of eight row groups
+  if (pair >= pairs) return;
+  const int b = (int)(((uint64_t)(uint32_t)pair * p.hkv_magic) >> 32), h = pair - b * p.Hkv;
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int rgw = zs * kWaves + wave;                          // this wavefront's row group
+  const bool has_rows = rgw < p.Mpad / 32;                     // wave-uniform
+  const int row0 = rgw * 32;
+  const int xgroup = zs * pairs + pair;                        // key-exchange group
+  const int tiles_d = (p.gamma + kTile - 1) / kTile;
+
+  const char* Kc = static_cast<const char*>(p.K);
+  const char* Vc = static_cast<const char*>(p.V);
+  const char* Kd = static_cast<const char*>(p.k_draft);
+  const char* Vd = static_cast<const char*>(p.v_draft);
+  const int32_t* __restrict__ sel_g = p.sel_idx + (int64_t)pair * p.k_blocks;
+  const int32_t* const table_row = p.table + (int64_t)b * p.kv.max_pages;
+
+  const int row = row0 + l32;
+  const bool row_valid = has_rows && row < p.M;
+  int qi = 0, qj = 0;
+  if (row_valid) {
+    qi = (int)(((uint64_t)(uint32_t)row * p.g_magic) >> 32);
+    qj = row - qi * p.G;
+  }
+  RetrievalLoads rl;
+  if (MODE == kSelect)
+    rl = issue_retrieval_loads(p, b, h, pair, split, xgroup, (split + zs * S) % kScoreBatch, tid, vzero);
+  bf16x8 qf[8];
+  {
+    const __hip_bfloat16* qrow = static_cast<const __hip_bfloat16*>(p.q) +
+                                 (((int64_t)b * p.gamma + qi) * p.Hq + h * p.G + qj) * kD + g * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
+  }
+  uint64_t rmask = 0;
+  if (p.draft_mask) rmask = p.draft_mask[p.mask_per_batch ? (int64_t)b * p.gamma + qi : qi];
+
+  // gather entries: lane u holds (the workgroup's u-th tile, group = this wavefront)
+  const int tc_u = split + lane * S - tiles_d;                 // cache tile index of this lane's tile
+  const int e_u = tc_u * 8 + wave;
+  const bool e_ok = tc_u >= 0 && e_u < p.gather_groups;
+  uint64_t gent = 0;
+  if (MODE == kGather && e_ok) gent = p.gather[(int64_t)pair * p.gather_groups + e_u];
+  int L = 0;
+  if (MODE != kGather) L = clamped_len(p.seq_lens, b + vzero, p.max_seq_len);
+  if (MODE == kSelect) issue_first_score_batch(p, rl, pair, split, tid);
+  int cnt;
+  uint32_t tag = 0;
+  if (MODE == kSelect) {
+    const Retrieved rt = retrieve_blocks(p, rl, smem, s_sel, &s_exchange_failed, L, pair, split, xgroup, tid, lane, wave);
+    L = rt.L;
+    cnt = rt.cnt;
+    tag = rt.tag;
+    if (split == S - 1 && zs == 0) publish_selection(p, s_sel, cnt, pair, tid);
+    if (e_ok) {
+      gent = gather_entry_of(p, s_sel, rt, rl, e_u, b, h);
+      if (zs == 0) p.gather_out[(int64_t)pair * p.gather_groups + e_u] = gent;
+    }
+    __syncthreads();                 // the last reads of the staged page table are done
+  } else {
+    cnt = __builtin_amdgcn_readfirstlane(min(max(p.sel_cnt[pair + vzero], 0), p.k_blocks));
+    if (MODE == kResolve && tc_u >= 0 && 4 * e_u < cnt * p.block_size) {
+      // sel_idx -> page table -> address, one tile per lane
+      const int slot0 = 4 * e_u;
+      const int bi = p.block_shift >= 0 ? slot0 >> p.block_shift : slot0 / p.block_size;
+      const int blk = sel_g[bi];
+      const int tok0 = blk * p.block_size + (slot0 - bi * p.block_size);
+      const int nv = blk >= 0 ? min(max(L - tok0, 0), 4) : 0;
+      if (nv > 0) {
+        int64_t rowoff;
+        if (p.kv.page_size == 0) {
+          rowoff = (int64_t)b * p.kv.stride_page + (int64_t)tok0 * p.kv.stride_tok;
+        } else {
+          const int pg = p.kv.page_shift >= 0 ? tok0 >> p.kv.page_shift : tok0 / p.kv.page_size;
+          rowoff = (int64_t)table_row[pg] * p.kv.stride_page + (int64_t)(tok0 - pg * p.kv.page_size) * p.kv.stride_tok;
+        }
+        const uint64_t off = (uint64_t)((rowoff + (int64_t)h * p.kv.stride_head) * 2);
+        gent = (off & kGatherOffsetMask) | ((uint64_t)nv << kGatherCountShift);
+      }
+    }
+  }
+  const int n_prefix = cnt * p.block_size;
+  const int tiles = tiles_d + (n_prefix + kTile - 1) / kTile;
+  int n_my = 0;
+  if (split < tiles) n_my = min((tiles - split + S - 1) / S, kMaxRowTiles);
+
+  const int lrow = lane >> 4;
+  const uint32_t cx = (uint32_t)((lane & 15) ^ lrow);
+  const uint32_t tok_bytes = (uint32_t)p.kv.stride_tok * 2u;
+  const uint32_t drow_bytes = (uint32_t)p.Hkv * kRowBytes;
+  const int64_t dv_c = Vc - Kc, dv_d = Vd - Kd;
+  const char* const kd_pair = Kd + (((int64_t)b * p.gamma) * p.Hkv + h) * kRowBytes;
+  const int64_t orow_pair = (int64_t)b * p.gamma * p.Hq + h * p.G;
+  const uint32_t nv_lds = (uint32_t)(uintptr_t)SVF_LDS_PTR(&s_nv[0][0]);
+
+  RowTileIssue ic;
+  ic.smem = smem;
+  ic.Kc = Kc;
+  ic.kd_pair = kd_pair;
+  ic.dv_c = dv_c;
+  ic.dv_d = dv_d;
+  ic.gent = gent;
+  ic.split = split;
+  ic.S = S;
+  ic.tiles_d = tiles_d;
+  ic.gamma = p.gamma;
+  ic.wave = wave;
+  ic.lane = lane;
+  ic.lrow = (uint32_t)lrow;
+  ic.cx = cx;
+  ic.tok_bytes = tok_bytes;
+  ic.drow_bytes = drow_bytes;
+  ic.nv_lds = nv_lds;
+
+  float m_run = -INFINITY, l_run = 0.f;
+  floatx16 oacc[4];
+#pragma unroll
+  for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) oacc[nt][v] = 0.f;
+
+  wait_vmcnt<0>();
+  if (!p.draft_mask) rmask = qi >= 63 ? ~0ull : ((2ull << qi) - 1ull);
+  if (!row_valid) rmask = 0;
+
+  // ---- main loop: up to nine tiles in flight ----------------------------------------------------
+  int issued = 0;
+  for (; issued < min(n_my, kRowStages); ++issued) issue_row_tile(ic, issued);
+  for (int i = 0; i < n_my; ++i) {
+    // this wavefront's loads of tile i have landed (two loads per tile, issued in order); the
+    // count of the group it fetched is on its way to LDS
+    wait_vmcnt_upto16(2 * (issued - i - 1));
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    // everybody is done with tile i - 1: its stage takes tile i + 8
+    if (i >= 1 && issued < n_my) {
+      issue_row_tile(ic, issued);
+      ++issued;
+    }
+    const int t = split + i * S;
+    const int st = i % kRowStages;
+    u32x4 nvq[2];
+    nvq[0] = lds_read16<0>(nv_lds + (uint32_t)st * (kWaves * 4));
+    nvq[1] = lds_read16<16>(nv_lds + (uint32_t)st * (kWaves * 4));
+    lds_wait2(nvq);
+    uint32_t valid = 0;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) valid |= ((1u << nvq[n >> 2][n & 3]) - 1u) << (4 * n);
+    valid = (uint32_t)__builtin_amdgcn_readfirstlane((int)valid);
+    if (has_rows) {
+      const int draft_base = t < tiles_d ? t * kTile : -1;
+      uint32_t allowed = valid;
+      if (draft_base >= 0) allowed &= (uint32_t)(rmask >> (draft_base & 63));
+      const bool all_visible = draft_base < 0 && valid == 0xffffffffu;
+      const uint32_t stage = (uint32_t)(uintptr_t)SVF_LDS_PTR(smem + st * kStageBytes);
+      process_tile(stage, qf, allowed, all_visible, p.scale_log2, l32, g, m_run, l_run, oacc);
+    }
+  }
+  if (!has_rows) return;             // no barrier from here on
+
+  // ---- this wavefront's 32 rows: output or partial ------------------------------------------------
+  // The normalised rows go through LDS once (bf16, [row][128 channels], 16-byte chunk c of row r
+  // at position c ^ (r & 15)) so that they leave in whole 256-byte rows: a lane's registers hold
+  // 8-byte pieces of 32 different rows.  The stage used is one nobody reads any more: no load
+  // is in flight after the last barrier, and only the last tile's stage may still be read.
+  l_run += __shfl_xor(l_run, 32, 64);
+  const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
+  {
+    const int last_st = n_my > 0 ? (n_my - 1) % kRowStages : 0;
+    unsigned char* mine = smem + ((last_st + 1 + wave) % kRowStages) * kStageBytes;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int i = 8 * (v >> 2) + 4 * g + (v & 3);            // dims 4*i .. 4*i+3
+      const u32x2 w = {pack_bf16(oacc[0][v] * inv, oacc[1][v] * inv), pack_bf16(oacc[2][v] * inv, oacc[3][v] * inv)};
+      *reinterpret_cast<u32x2*>(mine + l32 * kRowBytes + ((((i >> 1) ^ (l32 & 15)) << 4) | ((i & 1) << 3))) = w;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int rr = 4 * k + (lane >> 4), c = lane & 15;       // row of the group, 16-byte chunk
+      const u32x4 w = *reinterpret_cast<const u32x4*>(mine + rr * kRowBytes + ((c ^ (rr & 15)) << 4));
+      const int grow = row0 + rr;
+      if (S == 1) {
+        if (grow < p.M) {
+          const int oi = (int)(((uint64_t)(uint32_t)grow * p.g_magic) >> 32);
+          const int oj = grow - oi * p.G;
+          store_coherent16(static_cast<__hip_bfloat16*>(p.out) + (orow_pair + (int64_t)oi * p.Hq + oj) * kD + c * 8, w);
+        }
+      } else {
+        const int64_t pr = ((int64_t)pair * S + split) * p.Mpad + grow;
+        store_coherent16(reinterpret_cast<uint16_t*>(p.part_o) + pr * kD + c * 8, w);
+      }
+    }
+  }
+  if (S == 1) {
+    if (row_valid && p.lse && g == 0)
+      p.lse[orow_pair + (int64_t)qi * p.Hq + qj] = (m_run + log2f(l_run)) * 0.6931471805599453f;
+    return;
+  }
+  if (g == 0) store_coherent2(p.part_ml + 2 * (((int64_t)pair * S + split) * p.Mpad + row), m_run, l_run);
+  // ticket of this row group, taken by the wavefront on its own
+  wait_vmcnt<0>();
+  const int group_t = rgw * pairs + pair;
+  uint64_t prev = 0;
+  uint32_t xcc;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+  const int field = 16 + 6 * (int)(xcc & 7u);
+  if (lane == 0)
+    prev = __hip_atomic_fetch_add(&p.tickets[group_t], 1ull | (1ull << field), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const uint32_t prev_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)prev);
+  const uint32_t prev_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(prev >> 32));
+  const uint64_t pv = ((uint64_t)prev_hi << 32) | prev_lo;
+  const bool last = (pv & 0xffffull) == (uint64_t)(S - 1);
+  const bool same_xcd = S <= 63 && ((pv >> field) & 63ull) == (uint64_t)(S - 1);
+  if (!last) return;
+  if (lane == 0) __hip_atomic_store(&p.tickets[group_t], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  // wavefront 0 of every workgroup of the group has arrived: all of them are past the key exchange
+  if (MODE == kSelect && rl.share_scores && wave == 0 && lane == 0) p.epochs[xgroup] = tag;
+  if (same_xcd) {
+    merge_row_group<true>(p, S, pair, row0, orow_pair, lane);
+  } else {
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    merge_row_group<false>(p, S, pair, row0, orow_pair, lane);
+  }
+}
+
 }  // namespace
 
 // bf16, d = 128, and groups of four consecutive tokens never straddle a block or a page
@@ -1011,9 +1436,37 @@ int mfma_splits(const svf_shape_t& s) {
   return (int)want;
 }
 
+// More than two row groups: one workgroup takes up to eight of them (see the rows kernel).
+bool mfma_rows_mode(const svf_shape_t& s) {
+  const int M = s.gamma * (s.Hq / s.Hkv);
+  return (M + 31) / 32 >= 3;
+}
+
+// Splits per (sequence, KV head, set of eight row groups) of the rows kernel: cover the compute
+// units; at least one tile and at most kMaxRowTiles tiles per workgroup.
+int mfma_rows_splits(const svf_shape_t& s) {
+  const int M = s.gamma * (s.Hq / s.Hkv);
+  const int row_groups = (M + 31) / 32;
+  const int64_t groups = (int64_t)s.B * s.Hkv * ((row_groups + kWaves - 1) / kWaves);
+  const int64_t tiles = ((int64_t)s.k_blocks * s.block_size + kTile - 1) / kTile + (s.gamma + kTile - 1) / kTile;
+  const int64_t lo = (tiles + kMaxRowTiles - 1) / kMaxRowTiles;
+  int64_t want = (256 + groups - 1) / groups;
+  if (want > tiles) want = tiles;
+  if (want < lo) want = lo;
+  return (int)want;
+}
+
 hipError_t launch_verify_attn_mfma(const AttnParams& p, hipStream_t st) {
   const int row_groups = (p.M + 31) / 32;
   const int pairs = p.B * p.Hkv;
+  if (row_groups >= 3) {
+    const dim3 grid((unsigned)(kXcds * p.n_splits), (unsigned)((pairs + kXcds - 1) / kXcds),
+                    (unsigned)((row_groups + kWaves - 1) / kWaves));
+    if (p.reps) hipLaunchKernelGGL(verify_attn_mfma_rows_kernel<kSelect>, grid, dim3(kThreads), 0, st, p, pairs);
+    else if (p.gather) hipLaunchKernelGGL(verify_attn_mfma_rows_kernel<kGather>, grid, dim3(kThreads), 0, st, p, pairs);
+    else hipLaunchKernelGGL(verify_attn_mfma_rows_kernel<kResolve>, grid, dim3(kThreads), 0, st, p, pairs);
+    return hipGetLastError();
+  }
   const dim3 grid((unsigned)(kXcds * p.n_splits), (unsigned)((pairs + kXcds - 1) / kXcds), (unsigned)row_groups);
   if (p.reps) hipLaunchKernelGGL(verify_attn_mfma_kernel<kSelect>, grid, dim3(kThreads), 0, st, p, pairs);
   else if (p.gather) hipLaunchKernelGGL(verify_attn_mfma_kernel<kGather>, grid, dim3(kThreads), 0, st, p, pairs);

@@ -120,6 +120,12 @@ EDGE = {
     "blocks_768": small(B=1, Hq=4, Hkv=1, T=49152, k_blocks=24, planted=5, min_len=40000),
     "long_page_table": small(B=1, Hq=4, Hkv=1, T=20480, page_size=4, k_blocks=8, planted=3),
     "two_row_groups": small(Hq=16, Hkv=2, gamma=7, n_sink=1, n_local=1),
+    # more than two row groups of 32 query rows: one workgroup walks the tiles for up to eight row groups
+    "rows_gamma24_tree": small(gamma=24, tree_depth=5),
+    "rows_ring_of_stages": small(B=8, Hq=32, Hkv=8, gamma=24, T=4096, k_blocks=32, tree_depth=4, min_len=3000),
+    "rows_single_split": small(B=32, Hq=32, Hkv=8, gamma=20, T=1024, k_blocks=4),
+    "rows_gamma60_tree": small(gamma=60, tree_depth=6, T=4096, k_blocks=16, n_sink=1, n_local=1),
+    "rows_two_sets_of_eight": small(B=1, Hq=16, Hkv=2, gamma=64, T=2048, k_blocks=8),
     # shapes that leave the fused path: more than 1024 blocks (two retrieval kernels + gather list),
     # more than 1024 kept blocks (no gather list)
     "blocks_2048": small(B=1, Hq=4, Hkv=1, T=32768, block_size=16, k_blocks=40, planted=6),
