@@ -1026,92 +1026,10 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
 // instead of once per row group.  A tile is fetched by the eight wavefronts together (wavefront w
 // fetches the four-token group w: one K and one V load) into a ring of nine 16 KB stages; one
 // barrier per tile (after each wavefront has seen its own two loads land).  No combination through
-// LDS at the end: every wavefront writes its rows' partial itself, takes its row group's ticket
-// and, if it is the last, merges that row group's splits.
+// LDS at the end: every wavefront writes its rows itself: the output if there is one split, else
+// a partial that merge_rows_kernel combines.
 constexpr int kRowStages = kWaves + 1;
 constexpr int kMaxRowTiles = 64;             // tiles per workgroup: one gather entry per lane
-
-// Merge of one row group's splits by one wavefront (rows kernel): two lanes per row, 64 channels
-// each, splits in order.  LOCAL: every partial was written through this XCD's L2 (hand-issued loads
-// that bypass the per-CU cache; a compile-time switch, so that no value of such a load meets a
-// compiler-tracked one at a join before its wait).
-template <bool LOCAL>
-__device__ __forceinline__ void merge_row_group(const AttnParams& p, int S, int pair, int row0, int64_t orow_pair,
-                                                int lane) {
-    const int r = lane >> 1, half = lane & 1;
-    const int mrow = row0 + r;
-    const uint16_t* part_o = reinterpret_cast<const uint16_t*>(p.part_o);
-    float acc[64];
-#pragma unroll
-    for (int c = 0; c < 64; ++c) acc[c] = 0.f;
-    float m_acc = -INFINITY, l_acc = 0.f;
-    for (int s0 = 0; s0 < S; s0 += 2) {
-      u32x4 t[2][8];
-      u32x2 ml[2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int64_t pr = ((int64_t)pair * S + min(s0 + u, S - 1)) * p.Mpad + mrow;
-        const uint16_t* src = part_o + pr * kD + half * 64;
-        if (LOCAL) {
-          ml[u] = load8_bypass_l1(p.part_ml + 2 * pr);
-#pragma unroll
-          for (int c = 0; c < 8; ++c) t[u][c] = load16_bypass_l1(src + 8 * c);
-        } else {
-          ml[u] = *reinterpret_cast<const u32x2*>(p.part_ml + 2 * pr);
-#pragma unroll
-          for (int c = 0; c < 8; ++c) t[u][c] = *reinterpret_cast<const u32x4*>(src + 8 * c);
-        }
-      }
-      if (LOCAL) {                   // the hand-issued loads: all eighteen registers pass through the wait
-        asm volatile("s_waitcnt vmcnt(0)"
-                     : "+v"(t[0][0]), "+v"(t[0][1]), "+v"(t[0][2]), "+v"(t[0][3]), "+v"(t[0][4]), "+v"(t[0][5]),
-                       "+v"(t[0][6]), "+v"(t[0][7]), "+v"(t[1][0]), "+v"(t[1][1]), "+v"(t[1][2]), "+v"(t[1][3]),
-                       "+v"(t[1][4]), "+v"(t[1][5]), "+v"(t[1][6]), "+v"(t[1][7]), "+v"(ml[0]), "+v"(ml[1])
-                     :
-                     : "memory");
-      }
-      float pm[2], pl[2];
-      float mb = m_acc;
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        pm[u] = s0 + u >= S ? -INFINITY : __uint_as_float(ml[u][0]);
-        pl[u] = __uint_as_float(ml[u][1]);
-        mb = fmaxf(mb, pm[u]);
-      }
-      const float fa = m_acc == -INFINITY ? 0.f : fast_exp2(m_acc - mb);
-      l_acc *= fa;
-#pragma unroll
-      for (int c = 0; c < 64; ++c) acc[c] *= fa;
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const float w = pm[u] != -INFINITY ? fast_exp2(pm[u] - mb) * pl[u] : 0.f;
-        l_acc += w;
-#pragma unroll
-        for (int c = 0; c < 8; ++c)
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            acc[8 * c + 2 * k] += w * bf16_lo(t[u][c][k]);
-            acc[8 * c + 2 * k + 1] += w * bf16_hi(t[u][c][k]);
-          }
-      }
-      m_acc = mb;
-    }
-    if (mrow < p.M) {
-      const int oi = (int)(((uint64_t)(uint32_t)mrow * p.g_magic) >> 32);
-      const int oj = mrow - oi * p.G;
-      const int64_t mo = orow_pair + (int64_t)oi * p.Hq + oj;
-      const float minv = 1.0f / l_acc;
-      __hip_bfloat16* o = static_cast<__hip_bfloat16*>(p.out) + mo * kD + half * 64;
-#pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        u32x4 w;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) w[k] = pack_bf16(acc[8 * c + 2 * k] * minv, acc[8 * c + 2 * k + 1] * minv);
-        store_coherent16(o + 8 * c, w);
-      }
-      if (p.lse && half == 0) p.lse[mo] = (m_acc + log2f(l_acc)) * 0.6931471805599453f;
-    }
-}
 
 // What a wavefront of the rows kernel needs to fetch its part of a tile.
 struct RowTileIssue {
@@ -1386,30 +1304,33 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
     return;
   }
   if (g == 0) store_coherent2(p.part_ml + 2 * (((int64_t)pair * S + split) * p.Mpad + row), m_run, l_run);
-  // ticket of this row group, taken by the wavefront on its own
-  wait_vmcnt<0>();
-  const int group_t = rgw * pairs + pair;
-  uint64_t prev = 0;
-  uint32_t xcc;
-  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-  const int field = 16 + 6 * (int)(xcc & 7u);
-  if (lane == 0)
-    prev = __hip_atomic_fetch_add(&p.tickets[group_t], 1ull | (1ull << field), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  const uint32_t prev_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)prev);
-  const uint32_t prev_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(prev >> 32));
-  const uint64_t pv = ((uint64_t)prev_hi << 32) | prev_lo;
-  const bool last = (pv & 0xffffull) == (uint64_t)(S - 1);
-  const bool same_xcd = S <= 63 && ((pv >> field) & 63ull) == (uint64_t)(S - 1);
-  if (!last) return;
-  if (lane == 0) __hip_atomic_store(&p.tickets[group_t], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  // wavefront 0 of every workgroup of the group has arrived: all of them are past the key exchange
-  if (MODE == kSelect && rl.share_scores && wave == 0 && lane == 0) p.epochs[xgroup] = tag;
-  if (same_xcd) {
-    merge_row_group<true>(p, S, pair, row0, orow_pair, lane);
-  } else {
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    merge_row_group<false>(p, S, pair, row0, orow_pair, lane);
+  // (the splits are merged by merge_rows_kernel, launched behind this one: merging 32 rows x S
+  // splits by the one wavefront that happens to arrive last costs ten times what 512 threads need)
+}
+
+// Merge of the rows kernel's split partials: one workgroup per (pair, row group), sixteen threads
+// per row, splits in order (bit-stable).  Runs behind the rows kernel on the same stream; it also
+// moves the key-exchange tag of a retrieving call on (every workgroup of that call has finished).
+// grid: (pairs, row groups)
+__global__ __launch_bounds__(kThreads) void merge_rows_kernel(AttnParams p, int pairs, int advance_tags) {
+  const int pair = blockIdx.x, rg = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int r = tid >> 4, cg = tid & 15;
+  const int b = (int)(((uint64_t)(uint32_t)pair * p.hkv_magic) >> 32), h = pair - b * p.Hkv;
+  const int orow_row = rg * 32 + r;
+  const bool rok = orow_row < p.M;
+  int oi = 0, oj = 0;
+  if (rok) {
+    oi = (int)(((uint64_t)(uint32_t)orow_row * p.g_magic) >> 32);
+    oj = orow_row - oi * p.G;
   }
+  const int64_t orow = (int64_t)b * p.gamma * p.Hq + h * p.G + (int64_t)oi * p.Hq + oj;
+  const int64_t g_row = (int64_t)pair * p.n_splits * p.Mpad + orow_row;
+  if (advance_tags && tid == 0 && rg % kWaves == 0) {
+    uint32_t* e = p.epochs + (int64_t)(rg / kWaves) * pairs + pair;
+    *e = *e + 1u;
+  }
+  merge_splits<false>(p, g_row, orow, rok, cg);
 }
 
 }  // namespace
@@ -1465,6 +1386,11 @@ hipError_t launch_verify_attn_mfma(const AttnParams& p, hipStream_t st) {
     if (p.reps) hipLaunchKernelGGL(verify_attn_mfma_rows_kernel<kSelect>, grid, dim3(kThreads), 0, st, p, pairs);
     else if (p.gather) hipLaunchKernelGGL(verify_attn_mfma_rows_kernel<kGather>, grid, dim3(kThreads), 0, st, p, pairs);
     else hipLaunchKernelGGL(verify_attn_mfma_rows_kernel<kResolve>, grid, dim3(kThreads), 0, st, p, pairs);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || p.n_splits == 1) return e;
+    const int advance_tags = p.reps != nullptr && p.n_splits >= 2 && p.poll_budget > 0;
+    hipLaunchKernelGGL(merge_rows_kernel, dim3((unsigned)pairs, (unsigned)row_groups), dim3(kThreads), 0, st, p, pairs,
+                       advance_tags);
     return hipGetLastError();
   }
   const dim3 grid((unsigned)(kXcds * p.n_splits), (unsigned)((pairs + kXcds - 1) / kXcds), (unsigned)row_groups);
