@@ -166,7 +166,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 "
-              "(the path shards over batch / KV heads with no exchange, see DESIGN.md)", file=sys.stderr)
+              "(the path shards over sequences / KV heads with no exchange)", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -388,7 +388,7 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x) {
 // ascending.  Requires 1 <= cnt <= nb; all threads of the workgroup must call.
 struct SelectScratch {
   uint32_t hist[4][256];
-  uint32_t seg[2 * kWaves][2];     // per (round, wavefront): blocks above / equal to the threshold
+  uint32_t seg[2 * kWaves][2];     // per (key slot, wavefront): blocks above / equal to the threshold
 };
 __device__ __forceinline__ void workgroup_select(const uint32_t* keys, SelectScratch* sc, int nb, int cnt,
                                                  int32_t* sel, int tid, int lane, int wave) {
@@ -437,7 +437,7 @@ __device__ __forceinline__ void workgroup_select(const uint32_t* keys, SelectScr
     sc->seg[kWaves + wave][1] = (uint32_t)__popcll(eq1);
   }
   __syncthreads();
-  uint32_t gt_before = 0, eq_before = 0;             // over the segments in front of (round 0, this wavefront)
+  uint32_t gt_before = 0, eq_before = 0;             // over the segments in front of (first key, this wavefront)
   for (int w = 0; w < wave; ++w) { gt_before += sc->seg[w][0]; eq_before += sc->seg[w][1]; }
   {
     const uint32_t e = eq_before + (uint32_t)__popcll(eq0 & below);
