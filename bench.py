@@ -50,6 +50,9 @@ def parse():
     ap.add_argument("--profile-only", default="", help="run only this many steps of the timed loop (for rocprofv3)")
     ap.add_argument("--analytics", action="store_true",
                     help="time the retrieval analytics (per-draft block sets, overlap, Jaccard) instead of the step")
+    ap.add_argument("--variants", action="store_true",
+                    help="time the retrieval variants (min/max and bf16 summaries, group maximum, budget over all "
+                         "KV heads) on the headline configuration instead of the step")
     return ap.parse_args()
 
 
@@ -162,6 +165,133 @@ def analytics(args):
     print(json.dumps(line))
 
 
+def variants(args):
+    """Retrieval variants on cfg 3 (one layer's retrieval = summaries already in HBM -> scores -> kept
+    blocks, then the attention over what was kept).  One JSON line: the headline value is the retrieval
+    with bf16 min/max summaries, group maximum and the budget over all KV heads; `extra` has every
+    combination timed, and the roofline object is the variant scores kernel (one pass over the summaries)."""
+    import numpy as np
+    import torch
+    import paper_2512_21911_amd as S
+    import workloads as W
+    from oracle import svf_oracle as O
+    from oracle import svf_variants_oracle as V
+
+    torch.cuda.set_device(0)
+    S.lib()
+    cfg = W.CONFIGS[3]
+    n_rep = 16
+    layers = [W.make_layer(cfg, l, device="cuda") for l in range(n_rep)]
+    x0 = layers[0]
+    n_total = cfg.k_blocks * cfg.Hkv                       # Eq. 6: the budget counts all KV heads
+    k_row = min(cfg.nb_max, n_total)
+
+    def shape_with(k_blocks):
+        return S.make_shape(B=cfg.B, gamma=cfg.gamma, Hq=cfg.Hq, Hkv=cfg.Hkv, d=cfg.d, dtype=cfg.dtype,
+                            block_size=cfg.block_size, max_seq_len=cfg.T, k_blocks=k_blocks, k_pool=x0["k_pool"],
+                            page_size=cfg.page_size, max_pages_per_seq=x0["block_table"].shape[1])
+
+    def timed(fn, iters, warm):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(iters):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / iters * 1e3 / n_rep    # us per layer
+
+    names = {(0, 0): "mean_f32", (0, 1): "mean_bf16", (1, 0): "minmax_f32", (1, 1): "minmax_bf16"}
+    combos = [(0, 0, 0, 0), (0, 1, 0, 0), (1, 0, 0, 0), (1, 1, 0, 0), (1, 1, 1, 0), (0, 0, 0, 1), (1, 1, 1, 1)]
+    table = {}
+    kept = {}
+    for summary, sdt, group, budget in combos:
+        shape = shape_with(k_row if budget else cfg.k_blocks)
+        rt = S.SvfRetrieval(summary, sdt, group, budget, n_total if budget else 0)
+        tdt = torch.bfloat16 if sdt else torch.float32
+        summ = [torch.zeros(cfg.B, cfg.Hkv, cfg.nb_max, 2 if summary else 1, cfg.d, device="cuda", dtype=tdt)
+                for _ in range(n_rep)]
+        idx = [torch.zeros(cfg.B, cfg.Hkv, shape.k_blocks, dtype=torch.int32, device="cuda") for _ in range(n_rep)]
+        cnt = [torch.zeros(cfg.B, cfg.Hkv, dtype=torch.int32, device="cuda") for _ in range(n_rep)]
+        out = torch.zeros(cfg.B, cfg.gamma, cfg.Hq, cfg.d, device="cuda", dtype=cfg.torch_dtype)
+        ws = S.new_workspace(shape)
+
+        def do_summaries():
+            for l, x in enumerate(layers):
+                S.svf_block_summaries(shape, rt, x["k_pool"], x["block_table"], x["seq_lens"], summ[l])
+
+        def do_retrieve():
+            for l, x in enumerate(layers):
+                S.svf_retrieve(shape, rt, x["q"], summ[l], x["seq_lens"], idx[l], cnt[l], ws)
+
+        def do_attn():
+            for l, x in enumerate(layers):
+                S.svf_verify_attn(shape, x["q"], x["k_pool"], x["v_pool"], x["block_table"], x["seq_lens"],
+                                  x["k_draft"], x["v_draft"], x["draft_mask"], idx[l], cnt[l], out, ws)
+
+        us_sum = timed(do_summaries, max(2, args.steps // 10), 1)
+        us_ret = timed(do_retrieve, args.steps, args.warmup)
+        us_att = timed(do_attn, args.steps, args.warmup)
+        key = f"{names[(summary, sdt)]}/{'group_max' if group else 'group_mean'}/{'global' if budget else 'per_head'}"
+        sum_bytes = cfg.B * cfg.Hkv * cfg.nb_max * (2 if summary else 1) * cfg.d * (2 if sdt else 4)
+        table[key] = {"summaries_us": round(us_sum, 2), "retrieve_us": round(us_ret, 2), "attention_us": round(us_att, 2),
+                      "summary_bytes": sum_bytes,
+                      "kept_per_head_min_max": [int(torch.stack(cnt).min()), int(torch.stack(cnt).max())]}
+        kept[key] = (shape, rt, summ[0], idx[0], cnt[0], us_ret, sum_bytes)
+
+    # CPU oracle of the headline variant on layer 0, and the GPU's kept blocks checked against it
+    head = "minmax_bf16/group_max/global"
+    shape, rt, _, _, _, us_head, sum_bytes = kept[head]
+    xc = W.make_layer(cfg, 0, device="cpu")
+    w0, c0 = time.perf_counter(), time.process_time()
+    mn, mx = V.block_minmax(xc["k_pool"], xc["block_table"], xc["seq_lens"], cfg.block_size, cfg.nb_max)
+    t_sum = time.perf_counter() - w0
+    w1 = time.perf_counter()
+    s_ref = V.group_scores(V.head_scores(xc["q"], mn=V.round_bf16(mn), mx=V.round_bf16(mx)), cfg.Hkv, V.GROUP_MAX)
+    i_ref, c_ref = V.select_global(s_ref, xc["seq_lens"], cfg.block_size, n_total, k_row)
+    wall = time.perf_counter() - w1
+    cpu_t = time.process_time() - c0
+    xg = {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in xc.items()}
+    sg = torch.zeros(cfg.B, cfg.Hkv, cfg.nb_max, 2, cfg.d, device="cuda", dtype=torch.bfloat16)
+    ig = torch.zeros(cfg.B, cfg.Hkv, k_row, dtype=torch.int32, device="cuda")
+    cg = torch.zeros(cfg.B, cfg.Hkv, dtype=torch.int32, device="cuda")
+    wsg = S.new_workspace(shape)
+    S.svf_block_summaries(shape, rt, xg["k_pool"], xg["block_table"], xg["seq_lens"], sg)
+    S.svf_retrieve(shape, rt, xg["q"], sg, xg["seq_lens"], ig, cg, wsg)
+    torch.cuda.synchronize()
+    ig, cg = ig.cpu().numpy(), cg.cpu().numpy()
+    excused = 0
+    for b in range(cfg.B):
+        got = {(h, int(j)) for h in range(cfg.Hkv) for j in ig[b, h, :cg[b, h]]}
+        ref = {(h, int(j)) for h in range(cfg.Hkv) for j in i_ref[b, h, :c_ref[b, h]]}
+        diff = got ^ ref
+        nb = -(-int(xc["seq_lens"][b]) // cfg.block_size)
+        if diff and not diff <= set(V.near_tie_pairs(s_ref[b], nb, i_ref[b], c_ref[b])):
+            raise SystemExit("bench --variants: the GPU's kept blocks differ from the oracle's beyond near-ties")
+        excused += len(diff)
+    alg = sum_bytes + cfg.B * cfg.Hq * cfg.d * 2 + cfg.B * cfg.Hkv * cfg.nb_max * 4
+    line = {
+        "metric": "retrieval us/layer (bf16 min/max summaries, group max, budget over all KV heads; 32k ctx)",
+        "value": round(us_head, 2), "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(us_head * 1e-3, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "cfg3_long_batch_32k", "B": cfg.B, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "d": cfg.d, "T": cfg.T,
+                   "block_size": cfg.block_size, "n_total_blocks": n_total, "launch": "stream"},
+        "roofline": {"bound": "hbm", "kernel": "variant_scores_kernel + select_global_kernel",
+                     "achieved": round(alg / (us_head * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(alg / (us_head * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": alg, "avg_launch_us": round(us_head, 3)},
+        "cpu_baseline": {"value": round(wall * 1e6, 1), "unit": "us/layer",
+                         "cores": max(1, int(round(cpu_t / max(wall + t_sum, 1e-9)))), "kind": "oracle",
+                         "sample": f"oracle scores + global top-N on layer 0 (summaries excluded: {t_sum:.1f} s); "
+                                   f"GPU kept blocks identical up to {excused} near-tie pairs"},
+        "extra": table,
+    }
+    print(json.dumps(line))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -176,6 +306,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.analytics:
         analytics(args)
+        return
+    if args.variants:
+        variants(args)
         return
     S.lib()                      # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)

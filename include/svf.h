@@ -238,6 +238,56 @@ int svf_jaccard_adjacent(const svf_shape_t* shape, const uint64_t* masks_by_laye
  */
 int svf_topk_anchors(const double* J, int32_t n_layers, int32_t K, int32_t* anchors);
 
+/* ------------------------------------------------------------------------------------------
+ * Retrieval variants: the same pipeline (block summaries -> block scores -> kept blocks ->
+ * svf_verify_attn) with one of its rules exchanged.  Sec. 3.1 takes its block retrieval from
+ * Quest, whose block summary is the per-channel minimum and maximum of the keys; Eq. 6 counts the
+ * budget over all H KV heads of a sequence.  The default of every field is the rule of
+ * svf_block_reps / svf_score_select, and with all defaults the two calls below ARE those.
+ * ------------------------------------------------------------------------------------------ */
+#define SVF_SUMMARY_MEAN 0    /* the mean key (block term of Eq. 5): summaries [B][Hkv][nb_max][d]      */
+#define SVF_SUMMARY_MINMAX 1  /* per-channel minimum and maximum: summaries [B][Hkv][nb_max][2][d],
+                                 minimum row first; score of a query head =
+                                 sum over channels c of max(q_c * min_c, q_c * max_c), an upper bound
+                                 of q . k over the keys of the block                                    */
+#define SVF_GROUP_MEAN 0      /* score of a KV head = mean of its Hq/Hkv query heads' scores            */
+#define SVF_GROUP_MAX 1       /* ... = their maximum                                                    */
+#define SVF_BUDGET_PER_HEAD 0 /* every (sequence, KV head) keeps min(k_blocks, nb) blocks               */
+#define SVF_BUDGET_GLOBAL 1   /* every sequence keeps min(n_total, Hkv * nb) (KV head, block) pairs,
+                                 the highest scores over all its KV heads (Eq. 6 with its factor H);
+                                 equal scores: lower KV head, then lower block.  n_sink / n_local
+                                 blocks are kept in every KV head and count inside n_total.  sel_cnt
+                                 then differs per KV head; shape.k_blocks is the row length of
+                                 sel_idx and must be >= min(nb_max, n_total).                           */
+typedef struct svf_retrieval {
+  int32_t summary;        /* SVF_SUMMARY_*                                                        */
+  int32_t summary_dtype;  /* element type of the summaries: SVF_F32, or SVF_BF16 (rounded to nearest
+                             even from the fp32 value; half the bytes for the scores to read)     */
+  int32_t group_rule;     /* SVF_GROUP_*                                                          */
+  int32_t budget_rule;    /* SVF_BUDGET_*                                                         */
+  int32_t n_total;        /* SVF_BUDGET_GLOBAL only: pairs kept per sequence, >= Hkv * (n_sink + n_local) */
+} svf_retrieval_t;
+
+/*
+ * Block summaries of blocks first_block .. first_block + n_blocks (as svf_block_reps: -1 = all,
+ * a partial last block summarises the tokens it has, rows of blocks that do not exist are left
+ * untouched).  `retrieval` is a HOST pointer; `summaries` has the layout and element type it names.
+ */
+int svf_block_summaries(const svf_shape_t* shape, const svf_retrieval_t* retrieval, const void* K,
+                        const int32_t* block_table, const int32_t* seq_lens, int32_t first_block,
+                        int32_t n_blocks, void* summaries, void* stream);
+
+/*
+ * Scores of the first draft token's query heads against the summaries, combined per KV head
+ * (group_rule), then the kept blocks (budget_rule), written as svf_score_select writes them
+ * (sel_idx ascending per KV head, -1 padded; scores_or_null fp32 [B][Hkv][nb_max]).  The result
+ * feeds svf_verify_attn with the same shape.  SVF_ERR_BUDGET: n_total or k_blocks too small for
+ * the rule; SVF_ERR_SHAPE: an unknown rule.  `ws` is the workspace of svf_workspace_bytes(shape).
+ */
+int svf_retrieve(const svf_shape_t* shape, const svf_retrieval_t* retrieval, const void* q,
+                 const void* summaries, const int32_t* seq_lens, int32_t* sel_idx, int32_t* sel_cnt,
+                 float* scores_or_null, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -7,4 +7,6 @@ from .binding import (SVF_BF16, SVF_F32, SVF_STEP_ANCHOR, SVF_STEP_REUSE, SVF_ST
                       svf_block_reps, svf_budget_blocks, svf_score_select, svf_set_exchange_polls, svf_verify_attn, svf_verify_step,
                       svf_version, svf_workspace_bytes, svf_workspace_init,
                       new_analytics_workspace, svf_jaccard_adjacent, svf_mask_words, svf_masks_from_selection,
-                      svf_overlap_by_distance, svf_select_per_draft, svf_topk_anchors)
+                      svf_overlap_by_distance, svf_select_per_draft, svf_topk_anchors,
+                      SVF_BUDGET_GLOBAL, SVF_BUDGET_PER_HEAD, SVF_GROUP_MAX, SVF_GROUP_MEAN, SVF_SUMMARY_MEAN,
+                      SVF_SUMMARY_MINMAX, SvfRetrieval, svf_block_summaries, svf_retrieve)

@@ -32,6 +32,17 @@ class SvfShape(ctypes.Structure):
     ]
 
 
+class SvfRetrieval(ctypes.Structure):
+    """Mirror of svf_retrieval_t."""
+    _fields_ = [("summary", ctypes.c_int32), ("summary_dtype", ctypes.c_int32), ("group_rule", ctypes.c_int32),
+                ("budget_rule", ctypes.c_int32), ("n_total", ctypes.c_int32)]
+
+
+SVF_SUMMARY_MEAN, SVF_SUMMARY_MINMAX = 0, 1
+SVF_GROUP_MEAN, SVF_GROUP_MAX = 0, 1
+SVF_BUDGET_PER_HEAD, SVF_BUDGET_GLOBAL = 0, 1
+
+
 class SvfError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -43,7 +54,8 @@ _lib = None
 EXPORTS = ["svf_version", "svf_strerror", "svf_budget_blocks", "svf_workspace_bytes", "svf_workspace_init",
            "svf_block_reps", "svf_score_select", "svf_verify_attn", "svf_verify_step", "svf_set_exchange_polls",
            "svf_mask_words", "svf_analytics_workspace_bytes", "svf_select_per_draft", "svf_masks_from_selection",
-           "svf_overlap_by_distance", "svf_jaccard_adjacent", "svf_topk_anchors"]
+           "svf_overlap_by_distance", "svf_jaccard_adjacent", "svf_topk_anchors",
+           "svf_block_summaries", "svf_retrieve"]
 
 
 def lib() -> ctypes.CDLL:
@@ -73,6 +85,11 @@ def lib() -> ctypes.CDLL:
         L.svf_jaccard_adjacent.argtypes = [shp, vp, i32, vp, vp]
         L.svf_topk_anchors.restype = ctypes.c_int
         L.svf_topk_anchors.argtypes = [ctypes.POINTER(ctypes.c_double), i32, i32, ctypes.POINTER(i32)]
+        rtp = ctypes.POINTER(SvfRetrieval)
+        L.svf_block_summaries.restype = ctypes.c_int
+        L.svf_block_summaries.argtypes = [shp, rtp, vp, vp, vp, i32, i32, vp, vp]
+        L.svf_retrieve.restype = ctypes.c_int
+        L.svf_retrieve.argtypes = [shp, rtp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.svf_version.argtypes = []
         L.svf_strerror.restype = ctypes.c_char_p
         L.svf_strerror.argtypes = [ctypes.c_int]
@@ -229,3 +246,17 @@ def svf_topk_anchors(J, K):
     out = (ctypes.c_int32 * max(int(K), 1))()
     _check(lib().svf_topk_anchors(arr, n, int(K), out), "svf_topk_anchors")
     return [int(out[i]) for i in range(int(K))]
+
+
+# ---- retrieval variants (argument marshalling only) -------------------------------------------
+
+def svf_block_summaries(shape, retrieval, K, block_table, seq_lens, summaries, first_block=0, n_blocks=-1):
+    _check(lib().svf_block_summaries(ctypes.byref(shape), ctypes.byref(retrieval), _ptr(K), _ptr(block_table),
+                                     _ptr(seq_lens), first_block, n_blocks, _ptr(summaries), _stream()),
+           "svf_block_summaries")
+
+
+def svf_retrieve(shape, retrieval, q, summaries, seq_lens, sel_idx, sel_cnt, ws, scores=None):
+    _check(lib().svf_retrieve(ctypes.byref(shape), ctypes.byref(retrieval), _ptr(q), _ptr(summaries),
+                              _ptr(seq_lens), _ptr(sel_idx), _ptr(sel_cnt), _ptr(scores), _ptr(ws), ws.numel(),
+                              _stream()), "svf_retrieve")

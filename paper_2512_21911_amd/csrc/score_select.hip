@@ -263,6 +263,13 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectParams p) {
 }  // namespace
 
 hipError_t launch_score_select(const SelectParams& p, int dtype, hipStream_t st) {
+  hipError_t e = launch_scores_only(p, dtype, st);
+  if (e != hipSuccess) return e;
+  return launch_select_only(p, st);
+}
+
+// The scores alone (p.nq = 1: the first draft token's; otherwise every draft token's).
+hipError_t launch_scores_only(const SelectParams& p, int dtype, hipStream_t st) {
   const int bpw = kPasses * (kThreads / kScoreLanes);
   dim3 g1((p.nb_max + bpw - 1) / bpw, p.Hkv, p.B);
   if (p.nq > 1) {
@@ -281,8 +288,11 @@ hipError_t launch_score_select(const SelectParams& p, int dtype, hipStream_t st)
     if (p.d == 64) hipLaunchKernelGGL((block_scores_kernel<__hip_bfloat16, 64>), g1, dim3(kThreads), 0, st, p);
     else hipLaunchKernelGGL((block_scores_kernel<__hip_bfloat16, 128>), g1, dim3(kThreads), 0, st, p);
   }
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  return hipGetLastError();
+}
+
+// The selection alone, over scores that are already in p.scores.
+hipError_t launch_select_only(const SelectParams& p, hipStream_t st) {
   hipLaunchKernelGGL(select_kernel, dim3(p.Hkv, p.B * p.nq), dim3(kThreads), 0, st, p);
   return hipGetLastError();
 }

@@ -202,9 +202,9 @@ int svf_workspace_init(void* ws, size_t ws_bytes, void* stream) {
   return hip_code(launch_fill_zero(ws, ws_bytes, static_cast<hipStream_t>(stream)));
 }
 
-int svf_block_reps(const svf_shape_t* shape, const void* K, const int32_t* block_table,
-                   const int32_t* seq_lens, int32_t first_block, int32_t n_blocks, float* reps,
-                   void* stream) {
+static int block_reps_impl(const svf_shape_t* shape, const void* K, const int32_t* block_table,
+                           const int32_t* seq_lens, int32_t first_block, int32_t n_blocks, void* reps,
+                           void* stream, int minmax, int out_bf16) {
   int rc = check_shape(shape);
   if (rc) return rc;
   if (!K || !seq_lens || !reps || (shape->page_size > 0 && !block_table)) return SVF_ERR_NULL;
@@ -225,7 +225,15 @@ int svf_block_reps(const svf_shape_t* shape, const void* K, const int32_t* block
   p.first_block = first_block;
   p.max_seq_len = shape->max_seq_len;
   p.n_blocks = n_blocks;
+  p.minmax = minmax;
+  p.out_bf16 = out_bf16;
   return hip_code(launch_block_reps(p, shape->dtype, shape->B, static_cast<hipStream_t>(stream)));
+}
+
+int svf_block_reps(const svf_shape_t* shape, const void* K, const int32_t* block_table,
+                   const int32_t* seq_lens, int32_t first_block, int32_t n_blocks, float* reps,
+                   void* stream) {
+  return block_reps_impl(shape, K, block_table, seq_lens, first_block, n_blocks, reps, stream, 0, 0);
 }
 
 // block_table given (or the cache unpaged) and with_gather: the selection also leaves its gather
@@ -500,6 +508,103 @@ int svf_topk_anchors(const double* J, int32_t n_layers, int32_t K, int32_t* anch
   for (int32_t l = 0; l < n_layers; ++l)
     if (taken[l]) anchors[n++] = l;
   return SVF_OK;
+}
+
+/* ---- retrieval variants ------------------------------------------------------------------- */
+
+static int check_retrieval(const svf_shape_t* shape, const svf_retrieval_t* r) {
+  if (!r) return SVF_ERR_NULL;
+  if (r->summary != SVF_SUMMARY_MEAN && r->summary != SVF_SUMMARY_MINMAX) return SVF_ERR_SHAPE;
+  if (r->summary_dtype != SVF_F32 && r->summary_dtype != SVF_BF16) return SVF_ERR_DTYPE;
+  if (r->group_rule != SVF_GROUP_MEAN && r->group_rule != SVF_GROUP_MAX) return SVF_ERR_SHAPE;
+  if (r->budget_rule != SVF_BUDGET_PER_HEAD && r->budget_rule != SVF_BUDGET_GLOBAL) return SVF_ERR_SHAPE;
+  if (r->budget_rule == SVF_BUDGET_GLOBAL) {
+    const int64_t nb_max = nb_max_of(*shape);
+    if (r->n_total < 1 || ((int64_t)shape->n_sink + shape->n_local) * shape->Hkv > r->n_total) return SVF_ERR_BUDGET;
+    if (shape->k_blocks < (nb_max < r->n_total ? nb_max : (int64_t)r->n_total)) return SVF_ERR_BUDGET;
+  }
+  return SVF_OK;
+}
+
+static bool default_scores(const svf_retrieval_t& r) {
+  return r.summary == SVF_SUMMARY_MEAN && r.summary_dtype == SVF_F32 && r.group_rule == SVF_GROUP_MEAN;
+}
+
+int svf_block_summaries(const svf_shape_t* shape, const svf_retrieval_t* retrieval, const void* K,
+                        const int32_t* block_table, const int32_t* seq_lens, int32_t first_block,
+                        int32_t n_blocks, void* summaries, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  rc = check_retrieval(shape, retrieval);
+  if (rc) return rc;
+  return block_reps_impl(shape, K, block_table, seq_lens, first_block, n_blocks, summaries, stream,
+                         retrieval->summary == SVF_SUMMARY_MINMAX, retrieval->summary_dtype == SVF_BF16);
+}
+
+int svf_retrieve(const svf_shape_t* shape, const svf_retrieval_t* retrieval, const void* q,
+                 const void* summaries, const int32_t* seq_lens, int32_t* sel_idx, int32_t* sel_cnt,
+                 float* scores_or_null, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  rc = check_retrieval(shape, retrieval);
+  if (rc) return rc;
+  const svf_retrieval_t& r = *retrieval;
+  if (default_scores(r) && r.budget_rule == SVF_BUDGET_PER_HEAD)
+    return svf_score_select(shape, q, static_cast<const float*>(summaries), seq_lens, sel_idx, sel_cnt,
+                            scores_or_null, ws, ws_bytes, stream);
+  if (!q || !summaries || !seq_lens || !sel_idx || !sel_cnt) return SVF_ERR_NULL;
+  if (misaligned(q) || misaligned(summaries)) return SVF_ERR_SHAPE;
+  rc = check_ws(shape, ws, ws_bytes);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* scores = scores_or_null ? scores_or_null
+                                 : reinterpret_cast<float*>(static_cast<char*>(ws) + plan_attn(*shape).bytes);
+  VariantParams v;
+  v.q = q;
+  v.summaries = summaries;
+  v.seq_lens = seq_lens;
+  v.scores = scores;
+  v.sel_idx = sel_idx;
+  v.sel_cnt = sel_cnt;
+  v.B = shape->B;
+  v.gamma = shape->gamma;
+  v.Hq = shape->Hq;
+  v.Hkv = shape->Hkv;
+  v.d = shape->d;
+  v.block_size = shape->block_size;
+  v.nb_max = nb_max_of(*shape);
+  v.k_blocks = shape->k_blocks;
+  v.n_sink = shape->n_sink;
+  v.n_local = shape->n_local;
+  v.max_seq_len = shape->max_seq_len;
+  v.minmax = r.summary == SVF_SUMMARY_MINMAX;
+  v.summary_bf16 = r.summary_dtype == SVF_BF16;
+  v.group_max = r.group_rule == SVF_GROUP_MAX;
+  v.n_total = r.n_total;
+  // the main path's own kernels wherever the rule is the main path's (same bits as svf_score_select)
+  SelectParams p;
+  p.q = q;
+  p.reps = static_cast<const float*>(summaries);
+  p.seq_lens = seq_lens;
+  p.scores = scores;
+  p.sel_idx = sel_idx;
+  p.sel_cnt = sel_cnt;
+  p.B = v.B; p.gamma = v.gamma; p.Hq = v.Hq; p.Hkv = v.Hkv; p.d = v.d;
+  p.block_size = v.block_size; p.nb_max = v.nb_max; p.k_blocks = v.k_blocks;
+  p.n_sink = v.n_sink; p.n_local = v.n_local; p.max_seq_len = v.max_seq_len;
+  p.nq = 1;
+  p.masks = nullptr;
+  p.mask_words = 0;
+  p.gather = nullptr;
+  p.table = nullptr;
+  p.kv = layout_of(*shape);
+  p.gather_groups = 0;
+  hipError_t e;
+  if (default_scores(r)) e = launch_scores_only(p, shape->dtype, st);
+  else e = launch_variant_scores(v, shape->dtype, st);
+  if (e != hipSuccess) return SVF_ERR_HIP;
+  if (r.budget_rule == SVF_BUDGET_PER_HEAD) return hip_code(launch_select_only(p, st));
+  return hip_code(launch_select_global(v, st));
 }
 
 }  // extern "C"

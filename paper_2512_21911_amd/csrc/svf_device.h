@@ -39,8 +39,9 @@ struct RepsParams {
   const void* K;
   const int32_t* table;
   const int32_t* seq_lens;
-  float* reps;
+  void* reps;               // [B][Hkv][nb_max][d], or [B][Hkv][nb_max][2][d] (minimum, maximum)
   int32_t Hkv, d, block_size, nb_max, first_block, n_blocks, max_seq_len;
+  int32_t minmax, out_bf16;  // 0, 0: fp32 mean keys
 };
 
 // Gather list (an optional by-product of block selection that the matrix-core attention kernel
@@ -185,6 +186,25 @@ __device__ __forceinline__ float mean_query_channel(const QueryHeads<T>& h, cons
   for (int g = 8; g < G; ++g) s += query_value(q[(int64_t)g * D]);
   return s / (float)G;
 }
+
+// Retrieval variants (retrieval_variants.hip): scores of the first draft token per query head
+// against mean-key or min/max summaries (fp32 or bf16), combined per KV head by mean or maximum;
+// kept blocks per KV head (the selection kernel of score_select.hip) or over all KV heads of a
+// sequence.
+struct VariantParams {
+  const void* q;            // [B][gamma][Hq][d]
+  const void* summaries;
+  const int32_t* seq_lens;
+  float* scores;            // [B][Hkv][nb_max]
+  int32_t* sel_idx;         // [B][Hkv][k_blocks]
+  int32_t* sel_cnt;         // [B][Hkv]
+  int32_t B, gamma, Hq, Hkv, d, block_size, nb_max, k_blocks, n_sink, n_local, max_seq_len;
+  int32_t minmax, summary_bf16, group_max, n_total;
+};
+hipError_t launch_variant_scores(const VariantParams& p, int dtype, hipStream_t st);
+hipError_t launch_select_global(const VariantParams& p, hipStream_t st);
+hipError_t launch_scores_only(const SelectParams& p, int dtype, hipStream_t st);
+hipError_t launch_select_only(const SelectParams& p, hipStream_t st);
 
 // Launchers (each validates nothing: the C ABI layer has already done so).
 hipError_t launch_block_reps(const RepsParams& p, int dtype, int B, hipStream_t st);

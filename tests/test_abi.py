@@ -148,3 +148,35 @@ def test_topk_anchors_matches_the_oracle():
     arr = (ctypes.c_double * 3)(0.0, 0.5, 0.5)
     assert L.svf_topk_anchors(arr, 3, 0, out) == -2 and L.svf_topk_anchors(arr, 3, 4, out) == -2
     assert L.svf_topk_anchors(None, 3, 1, out) == -1
+
+
+def test_retrieval_variants_validate_before_launching():
+    sh = good_shape()                                   # nb_max = 16, k_blocks = 4, Hkv = 2
+    L = S.lib()
+    ok, null = ctypes.c_void_p(0x10000), None
+    need = S.svf_workspace_bytes(sh)
+
+    def retrieve(rt, shape=sh, q=ok, ws=ok, ws_bytes=need):
+        return L.svf_retrieve(ctypes.byref(shape), ctypes.byref(rt) if rt is not None else None, q, ok, ok, ok, ok,
+                              null, ws, ws_bytes, None)
+
+    def summaries(rt, out=ok):
+        return L.svf_block_summaries(ctypes.byref(sh), ctypes.byref(rt) if rt is not None else None, ok, ok, ok, 0,
+                                     -1, out, None)
+
+    good = S.SvfRetrieval(S.SVF_SUMMARY_MINMAX, S.SVF_BF16, S.SVF_GROUP_MAX, S.SVF_BUDGET_PER_HEAD, 0)
+    assert retrieve(None) == -1 and summaries(None) == -1
+    assert retrieve(S.SvfRetrieval(2, 0, 0, 0, 0)) == -2 and summaries(S.SvfRetrieval(2, 0, 0, 0, 0)) == -2
+    assert retrieve(S.SvfRetrieval(0, 2, 0, 0, 0)) == -3
+    assert retrieve(S.SvfRetrieval(0, 0, 2, 0, 0)) == -2
+    assert retrieve(S.SvfRetrieval(0, 0, 0, 2, 0)) == -2
+    assert retrieve(good, q=null) == -1 and summaries(good, out=null) == -1
+    assert retrieve(good, ws=null) == -6 and retrieve(good, ws_bytes=need - 1) == -6
+    # global budget: at least one pair, the forced pairs must fit, and sel_idx rows must hold a head's share
+    glob = lambda n: S.SvfRetrieval(0, 0, 0, S.SVF_BUDGET_GLOBAL, n)
+    assert retrieve(glob(0)) == -5
+    assert retrieve(glob(8)) == -5                                        # k_blocks 4 < min(16, 8)
+    assert retrieve(glob(4), ws_bytes=0) == -6                            # budget accepted, then the workspace check
+    sink = good_shape(n_sink=1, n_local=1, k_blocks=4)
+    assert retrieve(glob(3), shape=sink) == -5                            # 2 heads x 2 forced blocks > 3
+    assert retrieve(glob(4), shape=sink, ws_bytes=0) == -6
