@@ -43,6 +43,15 @@ SVF_GROUP_MEAN, SVF_GROUP_MAX = 0, 1
 SVF_BUDGET_PER_HEAD, SVF_BUDGET_GLOBAL = 0, 1
 
 
+class SvfFfnShape(ctypes.Structure):
+    """Mirror of svf_ffn_shape_t (include/svf_ffn.h)."""
+    _fields_ = [("M", ctypes.c_int32), ("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32), ("act", ctypes.c_int32),
+                ("tau", ctypes.c_float)]
+
+
+SVF_ACT_SILU, SVF_ACT_GELU = 0, 1
+
+
 class SvfError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -55,7 +64,7 @@ EXPORTS = ["svf_version", "svf_strerror", "svf_budget_blocks", "svf_workspace_by
            "svf_block_reps", "svf_score_select", "svf_verify_attn", "svf_verify_step", "svf_set_exchange_polls",
            "svf_mask_words", "svf_analytics_workspace_bytes", "svf_select_per_draft", "svf_masks_from_selection",
            "svf_overlap_by_distance", "svf_jaccard_adjacent", "svf_topk_anchors",
-           "svf_block_summaries", "svf_retrieve"]
+           "svf_block_summaries", "svf_retrieve", "svf_ffn_workspace_bytes", "svf_sparse_ffn"]
 
 
 def lib() -> ctypes.CDLL:
@@ -90,6 +99,11 @@ def lib() -> ctypes.CDLL:
         L.svf_block_summaries.argtypes = [shp, rtp, vp, vp, vp, i32, i32, vp, vp]
         L.svf_retrieve.restype = ctypes.c_int
         L.svf_retrieve.argtypes = [shp, rtp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        fsp = ctypes.POINTER(SvfFfnShape)
+        L.svf_ffn_workspace_bytes.restype = ctypes.c_size_t
+        L.svf_ffn_workspace_bytes.argtypes = [fsp]
+        L.svf_sparse_ffn.restype = ctypes.c_int
+        L.svf_sparse_ffn.argtypes = [fsp] + [vp] * 10 + [ctypes.c_size_t, vp]
         L.svf_version.argtypes = []
         L.svf_strerror.restype = ctypes.c_char_p
         L.svf_strerror.argtypes = [ctypes.c_int]
@@ -260,3 +274,28 @@ def svf_retrieve(shape, retrieval, q, summaries, seq_lens, sel_idx, sel_cnt, ws,
     _check(lib().svf_retrieve(ctypes.byref(shape), ctypes.byref(retrieval), _ptr(q), _ptr(summaries),
                               _ptr(seq_lens), _ptr(sel_idx), _ptr(sel_cnt), _ptr(scores), _ptr(ws), ws.numel(),
                               _stream()), "svf_retrieve")
+
+
+# ---- sparse feed-forward verification (argument marshalling only) ------------------------------
+
+def make_ffn_shape(*, M, d_model, d_ff, act="silu", tau=0.0) -> SvfFfnShape:
+    code = {"silu": SVF_ACT_SILU, "gelu": SVF_ACT_GELU}.get(act, act)
+    return SvfFfnShape(M, d_model, d_ff, code, tau)
+
+
+def svf_ffn_workspace_bytes(shape: SvfFfnShape) -> int:
+    return int(lib().svf_ffn_workspace_bytes(ctypes.byref(shape)))
+
+
+def new_ffn_workspace(shape: SvfFfnShape, device="cuda") -> torch.Tensor:
+    n = svf_ffn_workspace_bytes(shape)
+    if n == 0:
+        raise SvfError(-2, "svf_ffn_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def svf_sparse_ffn(shape, x, w_gate, w_up, w_down_t, y, ws, b_gate=None, b_up=None, b_down=None, active=None):
+    _check(lib().svf_sparse_ffn(ctypes.byref(shape), _ptr(x), _ptr(w_gate), _ptr(w_up), _ptr(w_down_t), _ptr(b_gate),
+                                _ptr(b_up), _ptr(b_down), _ptr(y), _ptr(active), _ptr(ws), ws.numel(), _stream()),
+           "svf_sparse_ffn")
+

@@ -1,0 +1,446 @@
+// Sparse feed-forward verification (Sec. 3.4, Eq. 10-14) for the M draft tokens of a step.
+//
+// Weight-bandwidth-bound: M <= 64 tokens against three [d_ff][d_model] bf16 matrices.  The
+// matrix cores do the arithmetic (32x32x16 bf16, tokens padded to 32 or 64 columns; they idle
+// most of the time), the work is organising the reads: every weight row is read at most once,
+// in long contiguous runs, and the rows of W_up / W_down of hidden channels that are inactive
+// for all M tokens are not read at all.
+//
+//   gate_up kernel  one workgroup of four wavefronts per tile of 32 hidden channels; the
+//                   wavefronts split the model dimension in chunks of 128.  A chunk of the
+//                   tile (32 rows x 256 bytes) goes straight from global memory to the
+//                   wavefront's own LDS stage (two stages, the next chunk is in flight while
+//                   this one is multiplied), the matching piece of x comes through registers.
+//                   Gate first: h = act(W_gate x + b_gate), the active bits |h| >= tau per
+//                   (channel, token); then the same walk over W_up, where a row that no token
+//                   needs is replaced by a row that is read anyway; h * up, masked per token,
+//                   goes out as bf16 [tokens][d_ff].
+//   down kernel     y^T = W_down^T-rows times h_up: one workgroup of eight wavefronts per
+//                   (128 output columns, slice of the hidden channels).  The weight rows are
+//                   contiguous along the output dimension while the matrix core wants its
+//                   operand contiguous along the reduction; each lane therefore loads four
+//                   output columns of eight channels and byte-permutes them into operands
+//                   (row i of sub-product nt = output column 4 i + nt).  Rows of channels
+//                   nobody needs are skipped.  Wavefront results are added in a fixed order
+//                   through LDS; the slices' partial sums are added, with b_down, by a third
+//                   small kernel (fixed order: the result does not depend on scheduling).
+#include <hip/hip_bf16.h>
+#include <hip/hip_runtime.h>
+
+#include "svf_ffn_device.h"
+
+namespace svf {
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float floatx2;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+
+#define FFN_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define FFN_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+constexpr int kTileRows = 32;                          // hidden channels per gate/up workgroup
+constexpr int kChunkK = 128;                           // model dimensions per chunk
+constexpr int kRowBytes = kChunkK * 2;                 // 256
+constexpr int kChunkBytes = kTileRows * kRowBytes;     // 8 KB
+constexpr int kGuWaves = 4;
+constexpr int kGuThreads = kGuWaves * 64;
+constexpr int kStages = 2;
+
+// s_waitcnt with only the vector-memory counter constrained
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+  asm volatile("" ::: "memory");
+}
+// LDS read issued by hand (a compiler-issued one would first wait for every direct-to-LDS load
+// in flight); valid once lds_wait has been given the registers
+__device__ __forceinline__ u32x4 lds_read16(uint32_t addr) {
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+  return v;
+}
+__device__ __forceinline__ void lds_wait(u32x4 (&r)[8]) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7])
+               :
+               : "memory");
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  const floatx2 f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));   // round to nearest even
+}
+
+__device__ __forceinline__ float activate(float z, int act) {
+  if (act == SVF_ACT_SILU) return z / (1.0f + __expf(-z));
+  return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+}
+
+// One walk of a wavefront over its chunks of a 32-row tile: acc[t] += W_tile(chunk) x^T(chunk).
+//   w_rows: address of row 0 of the tile; row_of(r): which tile row to read for row r (a row
+//   nobody needs is redirected, its products are thrown away); stage: the wavefront's two LDS stages.
+template <int NT, typename RowOf>
+__device__ __forceinline__ void walk_tile(const FfnParams& p, const char* w_rows, RowOf row_of, const char* x,
+                                          unsigned char* stage, int wave, int lane, floatx16 (&acc)[NT]) {
+  const int l32 = lane & 31, g = lane >> 5;
+  const int n_chunks = p.d_model / kChunkK;
+  const int64_t row_bytes = (int64_t)p.d_model * 2;
+  // direct-to-LDS loads: instruction n brings rows 4n .. 4n+3, 16 lanes per row; the 16-byte
+  // piece at position c of row r holds piece c ^ (r mod 16) of the chunk (bank spreading)
+  const int lrow = lane >> 4, lcol = lane & 15;
+  int64_t src_off[8];
+#pragma unroll
+  for (int n = 0; n < 8; ++n) {
+    const int r = 4 * n + lrow;
+    src_off[n] = (int64_t)row_of(r) * row_bytes + ((lcol ^ (r & 15)) << 4);
+  }
+  // x rows of this lane's token(s): eight 16-byte pieces per chunk (k-step ks, lane half g)
+  const char* xrow[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) xrow[t] = x + (int64_t)min(l32 + 32 * t, p.M - 1) * row_bytes + g * 16;
+
+  auto issue = [&](int kc, unsigned char* dst) {
+#pragma unroll
+    for (int n = 0; n < 8; ++n)
+      __builtin_amdgcn_global_load_lds(FFN_GLOBAL_PTR(w_rows + src_off[n] + (int64_t)kc * kRowBytes),
+                                       FFN_LDS_PTR(dst + n * 1024), 16, 0, 0);
+  };
+  u32x4 xa[NT][8], xb[NT][8];
+  auto load_x = [&](int kc, u32x4 (&xr)[NT][8]) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+        xr[t][ks] = *reinterpret_cast<const u32x4*>(xrow[t] + (int64_t)kc * kRowBytes + ks * 32);
+  };
+  auto compute = [&](const unsigned char* src, const u32x4 (&xr)[NT][8]) {
+    const uint32_t base = (uint32_t)(uintptr_t)FFN_LDS_PTR(src) + l32 * kRowBytes;
+    const uint32_t kx = (uint32_t)((g ^ (l32 & 15)) << 4);
+    u32x4 wf[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) wf[ks] = lds_read16(base + (kx ^ (uint32_t)(ks << 5)));
+    lds_wait(wf);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[ks]),
+                                                         __builtin_bit_cast(bf16x8, xr[t][ks]), acc[t], 0, 0, 0);
+  };
+
+  // chunks wave, wave + 4, ...: two at a time so that the register sets alternate without copies
+  int kc = wave;
+  if (kc >= n_chunks) return;
+  issue(kc, stage);
+  load_x(kc, xa);
+  // (each branch has its own wait and its own copy of the multiply, so that no wait has to
+  // serve both the path with loads in flight and the one without)
+  while (true) {
+    const int kn = kc + kGuWaves;
+    if (kn >= n_chunks) {
+      wait_vmcnt<0>();
+      compute(stage, xa);
+      break;
+    }
+    issue(kn, stage + kChunkBytes);
+    load_x(kn, xb);
+    wait_vmcnt<8 + 8 * NT>();
+    compute(stage, xa);
+    const int kn2 = kn + kGuWaves;
+    if (kn2 >= n_chunks) {
+      wait_vmcnt<0>();
+      compute(stage + kChunkBytes, xb);
+      break;
+    }
+    issue(kn2, stage);
+    load_x(kn2, xa);
+    wait_vmcnt<8 + 8 * NT>();
+    compute(stage + kChunkBytes, xb);
+    kc = kn2;
+  }
+}
+
+// grid: (d_ff / 32); block: 256
+template <int NT>
+__global__ __launch_bounds__(kGuThreads) void ffn_gate_up_kernel(FfnParams p) {
+  constexpr int RS = 32 * NT + 1;                        // row stride of the [channel][token] tiles in LDS
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[kGuWaves * kStages * kChunkBytes];
+  __shared__ float s_h[kTileRows * RS];
+  __shared__ uint64_t s_act[kTileRows];
+  static_assert(kTileRows * RS * 4 <= kStages * kChunkBytes, "a wavefront's partial tile fits its own stages");
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int c0 = blockIdx.x * kTileRows;
+  unsigned char* stage = smem + wave * (kStages * kChunkBytes);
+  float* red = reinterpret_cast<float*>(stage);         // this wavefront's partial [channel][token]
+  const char* x = static_cast<const char*>(p.x);
+  const int64_t row_bytes = (int64_t)p.d_model * 2;
+
+  auto put_partial = [&](const floatx16 (&acc)[NT]) {
+    // value v of a lane is channel 8 (v / 4) + 4 g + v % 4, token l32 (+ 32 t)
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) red[(8 * (v >> 2) + 4 * g + (v & 3)) * RS + l32 + 32 * t] = acc[t][v];
+  };
+  auto sum_partials = [&](int c, int m) {
+    float s = 0.f;
+#pragma unroll
+    for (int w = 0; w < kGuWaves; ++w)
+      s += reinterpret_cast<const float*>(smem + w * (kStages * kChunkBytes))[c * RS + m];
+    return s;
+  };
+
+  // ---- gate: h = act(W_gate x + b_gate), active bits (Eq. 10, 12) ----
+  floatx16 acc[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+  walk_tile<NT>(p, static_cast<const char*>(p.w_gate) + (int64_t)c0 * row_bytes, [](int r) { return r; }, x, stage,
+                wave, lane, acc);
+  put_partial(acc);
+  __syncthreads();
+  {
+    // thread: channel tid / 8, tokens (tid % 8) * 4 NT ... + 4 NT
+    const int c = tid >> 3, m0 = (tid & 7) * 4 * NT;
+    const float bg = p.b_gate ? p.b_gate[c0 + c] : 0.f;
+    uint64_t bits = 0;
+#pragma unroll
+    for (int i = 0; i < 4 * NT; ++i) {
+      const int m = m0 + i;
+      const float h = activate(sum_partials(c, m) + bg, p.act);
+      s_h[c * RS + m] = h;
+      if (m < p.M && !(fabsf(h) < p.tau)) bits |= 1ull << m;
+    }
+    // the eight threads of a channel are neighbours in a wavefront
+#pragma unroll
+    for (int o = 1; o < 8; o <<= 1) {
+      const uint32_t lo = __shfl_xor((uint32_t)bits, o, 64), hi = __shfl_xor((uint32_t)(bits >> 32), o, 64);
+      bits |= (uint64_t)lo | ((uint64_t)hi << 32);
+    }
+    if ((tid & 7) == 0) {
+      s_act[c] = bits;
+      if (p.active) p.active[c0 + c] = bits;
+    }
+  }
+  __syncthreads();                                        // partials read, s_h / s_act written
+
+  // ---- up: only rows some token needs are read; h * up per token (Eq. 13) ----
+  const uint64_t my_bits = s_act[l32];
+  const uint32_t rowmask = (uint32_t)__ballot(my_bits != 0 && lane < 32);
+  if (tid == 0) p.rowmask[blockIdx.x] = rowmask;
+  bf16x8 zero8;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) zero8[i] = 0;
+  // thread: token tid / 4, channels (tid % 4) * 8 ... + 8 (16 bytes of h_up)
+  const int om = tid >> 2, oc = (tid & 3) * 8;
+  char* out = static_cast<char*>(p.h_up) + ((int64_t)om * p.d_ff + c0 + oc) * 2;
+  if (rowmask == 0) {                                     // uniform: nothing of this tile is used
+    if (om < 32 * NT) *reinterpret_cast<bf16x8*>(out) = zero8;
+    return;
+  }
+  const int first = __builtin_ctz(rowmask);
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+  walk_tile<NT>(p, static_cast<const char*>(p.w_up) + (int64_t)c0 * row_bytes,
+                [=](int r) { return ((rowmask >> r) & 1u) ? r : first; }, x, stage, wave, lane, acc);
+  put_partial(acc);
+  __syncthreads();
+  if (om < 32 * NT) {
+    u32x4 w;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float hu[2];
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int c = oc + 2 * j + e;
+        const float up = sum_partials(c, om) + (p.b_up ? p.b_up[c0 + c] : 0.f);
+        hu[e] = ((s_act[c] >> om) & 1ull) ? s_h[c * RS + om] * up : 0.f;
+      }
+      w[j] = pack_bf16(hu[0], hu[1]);
+    }
+    *reinterpret_cast<u32x4*>(out) = w;
+  }
+}
+
+// ---- down projection ---------------------------------------------------------------------------
+constexpr int kDnWaves = 8;
+constexpr int kDnThreads = kDnWaves * 64;
+constexpr int kDnCols = 128;                             // output columns per workgroup
+constexpr int kDepth = 2;                                // k-steps of 16 channels loaded ahead
+
+template <int NT>
+struct DownLoads {
+  u32x2 w[8];                                            // four output columns of eight channels
+  u32x4 h[NT];                                           // h_up of this lane's token(s) for its eight channels
+  uint32_t bits;                                         // which of the step's 16 channels are needed
+};
+
+// grid: (d_model / 128, k_splits); block: 512
+template <int NT>
+__global__ __launch_bounds__(kDnThreads) void ffn_down_kernel(FfnParams p) {
+  __shared__ __attribute__((aligned(16))) float s_red[kDnWaves / 2][NT * 4 * 16 * 64];   // [slot][t][nt][v][lane]
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int n0 = blockIdx.x * kDnCols;
+  const int n_steps = p.d_ff / 16;
+  const int stride = kDnWaves * p.k_splits;
+  const int first = blockIdx.y * kDnWaves + wave;
+  const int64_t row_bytes = (int64_t)p.d_model * 2;
+  const char* wd = static_cast<const char*>(p.w_down_t) + (int64_t)(n0 + 4 * l32) * 2;
+  const char* hu = static_cast<const char*>(p.h_up);
+
+  floatx16 acc[NT][4];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[t][nt][v] = 0.f;
+
+  // k-slot e of lane half g in step s is channel 16 s + 8 g + e
+  auto load_step = [&](int s, DownLoads<NT>& d) {
+    d.bits = 0;
+    if (s < n_steps) d.bits = (p.rowmask[s >> 1] >> ((s & 1) * 16)) & 0xffffu;   // uniform
+    const uint32_t mine = (d.bits >> (8 * g)) & 0xffu;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      u32x2 v = {0u, 0u};
+      if ((mine >> e) & 1u) v = *reinterpret_cast<const u32x2*>(wd + (int64_t)(16 * s + 8 * g + e) * row_bytes);
+      d.w[e] = v;
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (d.bits != 0) v = *reinterpret_cast<const u32x4*>(hu + ((int64_t)(l32 + 32 * t) * p.d_ff + 16 * s + 8 * g) * 2);
+      d.h[t] = v;
+    }
+  };
+  auto compute_step = [&](const DownLoads<NT>& d) {
+    if (d.bits == 0) return;                              // uniform: no channel of the step is needed
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+      u32x4 w;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t a = nt < 2 ? d.w[2 * j][0] : d.w[2 * j][1];
+        const uint32_t b = nt < 2 ? d.w[2 * j + 1][0] : d.w[2 * j + 1][1];
+        w[j] = __builtin_amdgcn_perm(b, a, (nt & 1) ? 0x07060302u : 0x05040100u);
+      }
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+        acc[t][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w),
+                                                             __builtin_bit_cast(bf16x8, d.h[t]), acc[t][nt], 0, 0, 0);
+    }
+  };
+
+  // software pipeline, kDepth steps ahead (register sets rotate by full unrolling)
+  DownLoads<NT> ring[kDepth + 1];
+#pragma unroll
+  for (int i = 0; i < kDepth; ++i) load_step(first + i * stride, ring[i]);
+  for (int s = first; s < n_steps; s += (kDepth + 1) * stride) {
+#pragma unroll
+    for (int i = 0; i <= kDepth; ++i) {
+      load_step(s + (i + kDepth) * stride, ring[(i + kDepth) % (kDepth + 1)]);
+      compute_step(ring[i]);
+    }
+  }
+
+  // wavefronts 4..7 -> 0..3, 2..3 -> 0..1, 1 -> 0: a fixed order of additions
+  auto put = [&](int slot) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s_red[slot][((t * 4 + nt) * 16 + v) * 64 + lane] = acc[t][nt][v];
+  };
+  auto take = [&](int slot) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][nt][v] += s_red[slot][((t * 4 + nt) * 16 + v) * 64 + lane];
+  };
+#pragma unroll
+  for (int half = kDnWaves / 2; half >= 1; half >>= 1) {
+    if (wave >= half && wave < 2 * half) put(wave - half);
+    __syncthreads();
+    if (wave < half) take(wave);
+    __syncthreads();
+  }
+  if (wave == 0) {
+    // value v of a lane: output column n0 + 4 (8 (v / 4) + 4 g + v % 4) + nt, token l32 (+ 32 t)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int m = l32 + 32 * t;
+      if (m < p.M) {
+        float* dst = p.partial + ((int64_t)blockIdx.y * p.M + m) * p.d_model + n0;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          *reinterpret_cast<float4*>(dst + 4 * (8 * (v >> 2) + 4 * g + (v & 3))) =
+              make_float4(acc[t][0][v], acc[t][1][v], acc[t][2][v], acc[t][3][v]);
+      }
+    }
+  }
+}
+
+// y = bf16(sum over slices of partial + b_down); grid: ceil(M * d_model / (4 * 256))
+__global__ __launch_bounds__(256) void ffn_reduce_kernel(FfnParams p) {
+  const int64_t i4 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  const int64_t total = (int64_t)p.M * p.d_model;
+  if (i4 >= total) return;
+  const int n = (int)(i4 % p.d_model);
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int k = 0; k < p.k_splits; ++k) {
+    const float4 v = *reinterpret_cast<const float4*>(p.partial + (int64_t)k * total + i4);
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  if (p.b_down) {
+    const float4 b = *reinterpret_cast<const float4*>(p.b_down + n);
+    s.x += b.x; s.y += b.y; s.z += b.z; s.w += b.w;
+  }
+  u32x2 o = {pack_bf16(s.x, s.y), pack_bf16(s.z, s.w)};
+  *reinterpret_cast<u32x2*>(static_cast<char*>(p.y) + i4 * 2) = o;
+}
+
+}  // namespace
+
+int ffn_k_splits(int d_model, int d_ff) {
+  const int n_tiles = d_model / kDnCols;
+  int ks = 256 / (n_tiles > 0 ? n_tiles : 1);
+  const int max_ks = d_ff / (16 * kDnWaves) > 0 ? d_ff / (16 * kDnWaves) : 1;   // at least one step per wavefront
+  if (ks > max_ks) ks = max_ks;
+  return ks < 1 ? 1 : ks;
+}
+
+hipError_t launch_sparse_ffn(const FfnParams& p, hipStream_t st) {
+  if (p.M <= 32) hipLaunchKernelGGL(ffn_gate_up_kernel<1>, dim3(p.d_ff / kTileRows), dim3(kGuThreads), 0, st, p);
+  else hipLaunchKernelGGL(ffn_gate_up_kernel<2>, dim3(p.d_ff / kTileRows), dim3(kGuThreads), 0, st, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  dim3 gd(p.d_model / kDnCols, p.k_splits);
+  if (p.M <= 32) hipLaunchKernelGGL(ffn_down_kernel<1>, gd, dim3(kDnThreads), 0, st, p);
+  else hipLaunchKernelGGL(ffn_down_kernel<2>, gd, dim3(kDnThreads), 0, st, p);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int64_t quads = ((int64_t)p.M * p.d_model + 3) / 4;
+  hipLaunchKernelGGL(ffn_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, p);
+  return hipGetLastError();
+}
+
+}  // namespace svf

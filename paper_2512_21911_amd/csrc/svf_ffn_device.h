@@ -1,0 +1,33 @@
+// Internal declarations of the sparse feed-forward translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "svf.h"
+#include "svf_ffn.h"
+
+namespace svf {
+
+struct FfnParams {
+  const void* x;            // bf16 [M][d_model]
+  const void* w_gate;       // bf16 [d_ff][d_model]
+  const void* w_up;         // bf16 [d_ff][d_model]
+  const void* w_down_t;     // bf16 [d_ff][d_model]
+  const float* b_gate;      // fp32 [d_ff] or NULL
+  const float* b_up;        // fp32 [d_ff] or NULL
+  const float* b_down;      // fp32 [d_model] or NULL
+  void* y;                  // bf16 [M][d_model]
+  uint64_t* active;         // [d_ff] or NULL
+  void* h_up;               // bf16 [64][d_ff]: h * up per token, zero where the token does not use the channel
+  uint32_t* rowmask;        // [d_ff / 32]: bit r = channel 32 tile + r is used by some token
+  float* partial;           // fp32 [k_splits][M][d_model]
+  int32_t M, d_model, d_ff, act, k_splits;
+  float tau;
+};
+
+// Slices of the hidden dimension the down projection is cut into (partial sums in the workspace).
+int ffn_k_splits(int d_model, int d_ff);
+hipError_t launch_sparse_ffn(const FfnParams& p, hipStream_t st);
+
+}  // namespace svf

@@ -13,7 +13,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "svf.h")).read()
+    inc = os.path.join(ROOT, "include")
+    text = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(svf_[a-z_]+)\s*\(", text)))
 
@@ -180,3 +181,26 @@ def test_retrieval_variants_validate_before_launching():
     sink = good_shape(n_sink=1, n_local=1, k_blocks=4)
     assert retrieve(glob(3), shape=sink) == -5                            # 2 heads x 2 forced blocks > 3
     assert retrieve(glob(4), shape=sink, ws_bytes=0) == -6
+
+
+def test_sparse_ffn_validates_before_launching():
+    L = S.lib()
+    ok, null = ctypes.c_void_p(0x10000), None
+    sh = S.make_ffn_shape(M=8, d_model=256, d_ff=64, act="silu", tau=0.05)
+    need = S.svf_ffn_workspace_bytes(sh)
+    assert need > 0 and need % 256 == 0
+
+    def call(shape=sh, x=ok, y=ok, ws=ok, ws_bytes=need, b=null, active=null):
+        return L.svf_sparse_ffn(ctypes.byref(shape), x, ok, ok, ok, b, null, null, y, active, ws, ws_bytes, None)
+
+    for bad in (dict(M=0), dict(M=65), dict(d_model=192), dict(d_model=0), dict(d_ff=48), dict(d_ff=0), dict(act=2),
+                dict(tau=-0.1), dict(tau=float("nan")), dict(tau=float("inf"))):
+        kw = dict(M=8, d_model=256, d_ff=64, act="silu", tau=0.05)
+        kw.update(bad)
+        assert S.svf_ffn_workspace_bytes(S.make_ffn_shape(**kw)) == 0, bad
+        assert call(shape=S.make_ffn_shape(**kw)) == -2, bad
+    assert call(x=null) == -1 and call(y=null) == -1
+    assert call(x=ctypes.c_void_p(0x10008)) == -2 and call(b=ctypes.c_void_p(0x10004)) == -2
+    assert call(active=ctypes.c_void_p(0x10004)) == -2
+    assert call(ws=null) == -6 and call(ws=ctypes.c_void_p(0x10010)) == -6 and call(ws_bytes=need - 1) == -6
+
