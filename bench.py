@@ -53,6 +53,9 @@ def parse():
     ap.add_argument("--variants", action="store_true",
                     help="time the retrieval variants (min/max and bf16 summaries, group maximum, budget over all "
                          "KV heads) on the headline configuration instead of the step")
+    ap.add_argument("--sffn", action="store_true",
+                    help="time the sparse feed-forward verification (Sec. 3.4) on the 8B model's FFN shape instead of the step")
+    ap.add_argument("--sffn-cfg", type=int, default=3, help="FFN workload (3: 8 tokens, 4: 60-node tree)")
     return ap.parse_args()
 
 
@@ -292,6 +295,96 @@ def variants(args):
     print(json.dumps(line))
 
 
+def sffn(args):
+    """Sparse feed-forward verification of one layer (gate -> threshold set -> up -> down) for the draft
+    tokens of a step, on the feed-forward shape of the 8B target model, at the paper's thresholds.  Four
+    independent layers are cycled so that no launch finds its weights in a cache.  One JSON line: the
+    headline value is tau = 0.05; the roofline object prices the bytes that layer has to read (gate matrix,
+    the up / down rows some token needs, x, y) against the HBM peak."""
+    import numpy as np
+    import torch
+    import paper_2512_21911_amd as S
+    from oracle import sffn_oracle as FO
+    from workloads import ffn as WF
+
+    torch.cuda.set_device(0)
+    S.lib()
+    cfg = WF.FFN_CONFIGS[args.sffn_cfg]
+    n_rep = 4
+    layers = [WF.make_ffn(cfg, l, device="cuda") for l in range(n_rep)]
+    y = torch.zeros(cfg.M, cfg.d_model, device="cuda", dtype=torch.bfloat16)
+    active = torch.zeros(cfg.d_ff, device="cuda", dtype=torch.int64)
+
+    def timed(fn, iters, warm):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(iters):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / iters * 1e3 / n_rep    # us per layer
+
+    row = cfg.d_model * 2
+    table = {}
+    for tau in (0.0, 0.01, 0.05, 0.1):
+        shape = S.make_ffn_shape(M=cfg.M, d_model=cfg.d_model, d_ff=cfg.d_ff, act=cfg.act, tau=tau)
+        ws = S.new_ffn_workspace(shape)
+
+        def all_layers():
+            for w in layers:
+                S.svf_sparse_ffn(shape, w["x"], w["w_gate"], w["w_up"], w["w_down_t"], y, ws, w["b_gate"], w["b_up"],
+                                 w["b_down"], active)
+
+        us = timed(all_layers, max(3, args.steps // 2), max(1, args.warmup // 2))
+        w = layers[-1]
+        S.svf_sparse_ffn(shape, w["x"], w["w_gate"], w["w_up"], w["w_down_t"], y, ws, None, None, None, active)
+        torch.cuda.synchronize()
+        bits = active.cpu().numpy().view(np.uint64)
+        rows = float((bits != 0).mean())
+        per_tok = float(np.mean([((bits >> np.uint64(m)) & np.uint64(1)).mean() for m in range(cfg.M)]))
+        alg = int(cfg.d_ff * row * (1 + 2 * rows) + 2 * cfg.M * row)
+        table[f"tau={tau}"] = {"us_per_layer": round(us, 2), "token_sparsity": round(1 - per_tok, 3),
+                               "rows_read": round(rows, 3), "algorithmic_bytes": alg,
+                               "GBps": round(alg / (us * 1e-6) / 1e9, 1)}
+    head = table["tau=0.05"]
+
+    # CPU oracle on layer 0 (CPU-generated tensors of the same recipe), and the GPU checked against it
+    wc = WF.make_ffn(cfg, 0, device="cpu")
+    toks = list(range(cfg.M)) if cfg.M <= 8 else [0, cfg.M // 2, cfg.M - 1]
+    w0, c0 = time.perf_counter(), time.process_time()
+    y_ref, a_ref, _ = FO.sparse_ffn(wc["x"][toks], wc["w_gate"], wc["w_up"], wc["w_down_t"], None, None, None, cfg.act, 0.05)
+    wall, cpu_t = time.perf_counter() - w0, time.process_time() - c0
+    shape = S.make_ffn_shape(M=cfg.M, d_model=cfg.d_model, d_ff=cfg.d_ff, act=cfg.act, tau=0.05)
+    ws = S.new_ffn_workspace(shape)
+    g = {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in wc.items()}
+    S.svf_sparse_ffn(shape, g["x"], g["w_gate"], g["w_up"], g["w_down_t"], y, ws, None, None, None, active)
+    torch.cuda.synchronize()
+    err = float(np.abs(y.double().cpu().numpy()[toks] - y_ref).max())
+    if not err <= 2e-2 * max(1.0, float(np.abs(y_ref).max())):
+        raise SystemExit(f"bench --sffn: GPU output differs from the oracle on the sampled layer (max-abs {err:.3e})")
+    line = {
+        "metric": f"sparse FFN verification us/layer (tau=0.05, {cfg.M} tokens, d_model={cfg.d_model}, d_ff={cfg.d_ff})",
+        "value": head["us_per_layer"], "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(head["us_per_layer"] * 1e-3, 5), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "M": cfg.M, "d_model": cfg.d_model, "d_ff": cfg.d_ff, "act": cfg.act,
+                   "tau": 0.05, "launch": "stream"},
+        "roofline": {"bound": "hbm", "kernel": "ffn_gate_up_kernel + ffn_down_kernel + ffn_reduce_kernel",
+                     "achieved": head["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(head["GBps"] / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": head["algorithmic_bytes"], "avg_launch_us": head["us_per_layer"]},
+        "cpu_baseline": {"value": round(wall * 1e6 * cfg.M / len(toks), 1), "unit": "us/layer",
+                         "cores": max(1, int(round(cpu_t / max(wall, 1e-9)))), "kind": "oracle",
+                         "sample": f"oracle sparse FFN of {len(toks)} of {cfg.M} tokens of layer 0 ({wall:.1f} s wall), "
+                                   f"scaled to {cfg.M}; max-abs vs GPU {err:.2e}"},
+        "extra": table,
+    }
+    print(json.dumps(line))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -309,6 +402,9 @@ def main():
         return
     if args.variants:
         variants(args)
+        return
+    if args.sffn:
+        sffn(args)
         return
     S.lib()                      # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
