@@ -311,28 +311,26 @@ __global__ __launch_bounds__(kDnThreads) void ffn_down_kernel(FfnParams p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[t][nt][v] = 0.f;
 
-  // k-slot e of lane half g in step s is channel 16 s + 8 g + e.  No branches: a row nobody needs
-  // is replaced by row 0 of the matrix (one 256-byte piece per workgroup, it stays in cache), and
-  // since h_up is zero wherever a token does not use a channel, whatever such a row holds
-  // contributes nothing; a step past the end gets zero h_up.
+  // k-slot e of lane half g in step s is channel 16 s + 8 g + e
   auto load_step = [&](int s, DownLoads<NT>& d) {
-    const bool valid = s < n_steps;
-    const int sv = valid ? s : 0;
-    d.bits = valid ? (p.rowmask[sv >> 1] >> ((sv & 1) * 16)) & 0xffffu : 0u;
+    d.bits = 0;
+    if (s < n_steps) d.bits = (p.rowmask[s >> 1] >> ((s & 1) * 16)) & 0xffffu;   // uniform
     const uint32_t mine = (d.bits >> (8 * g)) & 0xffu;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const int row = ((mine >> e) & 1u) ? 16 * sv + 8 * g + e : 0;
-      d.w[e] = *reinterpret_cast<const u32x2*>(wd + (int64_t)row * row_bytes);
+      u32x2 v = {0u, 0u};
+      if ((mine >> e) & 1u) v = *reinterpret_cast<const u32x2*>(wd + (int64_t)(16 * s + 8 * g + e) * row_bytes);
+      d.w[e] = v;
     }
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      const u32x4 v = *reinterpret_cast<const u32x4*>(hu + ((int64_t)(l32 + 32 * t) * p.d_ff + 16 * sv + 8 * g) * 2);
-      const u32x4 zero = {0u, 0u, 0u, 0u};
-      d.h[t] = valid ? v : zero;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (d.bits != 0) v = *reinterpret_cast<const u32x4*>(hu + ((int64_t)(l32 + 32 * t) * p.d_ff + 16 * s + 8 * g) * 2);
+      d.h[t] = v;
     }
   };
   auto compute_step = [&](const DownLoads<NT>& d) {
+    if (d.bits == 0) return;                              // uniform: no channel of the step is needed
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt) {
       u32x4 w;
@@ -424,7 +422,7 @@ __global__ __launch_bounds__(256) void ffn_reduce_kernel(FfnParams p) {
 
 int ffn_k_splits(int d_model, int d_ff) {
   const int n_tiles = d_model / kDnCols;
-  int ks = 256 / (n_tiles > 0 ? n_tiles : 1);                                     // two workgroups per compute unit
+  int ks = 256 / (n_tiles > 0 ? n_tiles : 1);                                     // one workgroup per compute unit
   const int max_ks = d_ff / (16 * kDnWaves) > 0 ? d_ff / (16 * kDnWaves) : 1;   // at least one step per wavefront
   if (ks > max_ks) ks = max_ks;
   return ks < 1 ? 1 : ks;
