@@ -56,6 +56,9 @@ def parse():
     ap.add_argument("--sffn", action="store_true",
                     help="time the sparse feed-forward verification (Sec. 3.4) on the 8B model's FFN shape instead of the step")
     ap.add_argument("--sffn-cfg", type=int, default=3, help="FFN workload (3: 8 tokens, 4: 60-node tree)")
+    ap.add_argument("--rules", action="store_true",
+                    help="time the per-token rules (expert skipping, Sec. 3.5; acceptance / resampling, Sec. 2.1) instead "
+                         "of the step")
     return ap.parse_args()
 
 
@@ -385,6 +388,90 @@ def sffn(args):
     print(json.dumps(line))
 
 
+def rules(args):
+    """The two per-token rules on the shapes of Sec. 4.3 (8 of 256 experts per token, draft length 4, a
+    vocabulary of 129 280): acceptance / resampling of 64 sequences (headline), expert skipping of 4096
+    tokens, calibration of one layer's thresholds on 65 536 tokens.  Small latency-bound kernels; the
+    roofline object prices the bytes the acceptance kernel must read."""
+    import numpy as np
+    import torch
+    import paper_2512_21911_amd as S
+    from oracle import spec_rules_oracle as R
+    from workloads import rules as WR
+
+    torch.cuda.set_device(0)
+    S.lib()
+
+    def timed(fn, iters, warm):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(iters):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / iters * 1e3
+
+    B, gamma, V = 64, 4, 129280
+    xc = WR.acceptance_inputs(B, gamma, V, seed=1)
+    x = {k: v.cuda() for k, v in xc.items()}
+    n_acc = torch.zeros(B, dtype=torch.int32, device="cuda")
+    res = torch.zeros(B, dtype=torch.int32, device="cuda")
+    call = lambda: S.svf_accept_resample(x["p_target"], x["p_draft"], x["draft_tokens"], x["u_accept"], x["u_resample"],
+                                         n_acc, res)
+    us_acc = timed(call, args.steps, args.warmup)
+    w0, c0 = time.perf_counter(), time.process_time()
+    n_ref, r_ref, _ = R.accept_resample(*(xc[k].numpy() for k in ("p_target", "p_draft", "draft_tokens", "u_accept",
+                                                                   "u_resample")))
+    wall, cpu_t = time.perf_counter() - w0, time.process_time() - c0
+    same_n = bool(np.array_equal(n_acc.cpu().numpy(), n_ref))
+    same_r = int((res.cpu().numpy() == r_ref).sum())
+    if not same_n or same_r < B - 2:
+        raise SystemExit("bench --rules: acceptance differs from the oracle on the timed batch")
+    rejected = int((n_ref < gamma).sum())
+    alg = rejected * 2 * V * 4 + B * gamma * 4 * 4
+
+    T, k, m = 4096, 8, 3
+    wc = WR.routing_weights(T, k, seed=2)
+    cal = WR.routing_weights(65536, k, seed=3).cuda()
+    beta = torch.zeros(k - 1, device="cuda")
+    ws = torch.empty(int(S.lib().svf_moe_calibrate_workspace_bytes(65536, k)), dtype=torch.uint8, device="cuda")
+    us_cal = timed(lambda: S.svf_moe_calibrate(cal, beta, ws), max(5, args.steps // 5), 2)
+    wg = wc.cuda()
+    n_skip = torch.zeros(T, dtype=torch.int32, device="cuda")
+    mask = torch.zeros(T, dtype=torch.int32, device="cuda")
+    us_skip = timed(lambda: S.svf_moe_skip(wg, m, beta, n_skip, mask), args.steps, args.warmup)
+    t0 = time.perf_counter()
+    n_skip_ref, _ = R.moe_skip(wc.numpy(), beta.cpu().double().numpy(), m)
+    t_skip_cpu = time.perf_counter() - t0
+    differ = int((n_skip.cpu().numpy() != n_skip_ref).sum())
+    if differ > 4:
+        raise SystemExit("bench --rules: expert skipping differs from the oracle on the timed batch")
+    gbps = alg / (us_acc * 1e-6) / 1e9
+    line = {
+        "metric": f"acceptance + resampling us/step ({B} sequences, draft length {gamma}, vocabulary {V})",
+        "value": round(us_acc, 2), "unit": "us/step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(us_acc * 1e-3, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "rules_mtp4_vocab129k", "B": B, "gamma": gamma, "V": V, "launch": "stream"},
+        "roofline": {"bound": "hbm", "kernel": "accept_kernel", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": alg, "avg_launch_us": round(us_acc, 3)},
+        "cpu_baseline": {"value": round(wall * 1e6, 1), "unit": "us/step",
+                         "cores": max(1, int(round(cpu_t / max(wall, 1e-9)))), "kind": "oracle",
+                         "sample": f"oracle acceptance + resampling of the same {B} sequences ({rejected} rejected); "
+                                   f"accepted counts identical, {same_r}/{B} resampled tokens identical"},
+        "extra": {"moe_skip_us": round(us_skip, 2), "moe_skip_tokens": T, "moe_skip_k": k, "moe_skip_m": m,
+                  "moe_skip_mean_skipped": round(float(n_skip_ref.mean()), 3),
+                  "moe_skip_oracle_us": round(t_skip_cpu * 1e6, 1), "moe_skip_tokens_differing": differ,
+                  "moe_calibrate_us": round(us_cal, 2), "moe_calibrate_tokens": 65536,
+                  "mean_accepted": round(float(n_ref.mean()), 3)},
+    }
+    print(json.dumps(line))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -405,6 +492,9 @@ def main():
         return
     if args.sffn:
         sffn(args)
+        return
+    if args.rules:
+        rules(args)
         return
     S.lib()                      # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)

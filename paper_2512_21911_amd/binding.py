@@ -64,7 +64,8 @@ EXPORTS = ["svf_version", "svf_strerror", "svf_budget_blocks", "svf_workspace_by
            "svf_block_reps", "svf_score_select", "svf_verify_attn", "svf_verify_step", "svf_set_exchange_polls",
            "svf_mask_words", "svf_analytics_workspace_bytes", "svf_select_per_draft", "svf_masks_from_selection",
            "svf_overlap_by_distance", "svf_jaccard_adjacent", "svf_topk_anchors",
-           "svf_block_summaries", "svf_retrieve", "svf_ffn_workspace_bytes", "svf_sparse_ffn"]
+           "svf_block_summaries", "svf_retrieve", "svf_ffn_workspace_bytes", "svf_sparse_ffn",
+           "svf_moe_skip", "svf_moe_calibrate_workspace_bytes", "svf_moe_calibrate", "svf_accept_resample"]
 
 
 def lib() -> ctypes.CDLL:
@@ -104,6 +105,14 @@ def lib() -> ctypes.CDLL:
         L.svf_ffn_workspace_bytes.argtypes = [fsp]
         L.svf_sparse_ffn.restype = ctypes.c_int
         L.svf_sparse_ffn.argtypes = [fsp] + [vp] * 10 + [ctypes.c_size_t, vp]
+        L.svf_moe_skip.restype = ctypes.c_int
+        L.svf_moe_skip.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp]
+        L.svf_moe_calibrate_workspace_bytes.restype = ctypes.c_size_t
+        L.svf_moe_calibrate_workspace_bytes.argtypes = [i32, i32]
+        L.svf_moe_calibrate.restype = ctypes.c_int
+        L.svf_moe_calibrate.argtypes = [vp, i32, i32, vp, vp, ctypes.c_size_t, vp]
+        L.svf_accept_resample.restype = ctypes.c_int
+        L.svf_accept_resample.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp]
         L.svf_version.argtypes = []
         L.svf_strerror.restype = ctypes.c_char_p
         L.svf_strerror.argtypes = [ctypes.c_int]
@@ -298,4 +307,24 @@ def svf_sparse_ffn(shape, x, w_gate, w_up, w_down_t, y, ws, b_gate=None, b_up=No
     _check(lib().svf_sparse_ffn(ctypes.byref(shape), _ptr(x), _ptr(w_gate), _ptr(w_up), _ptr(w_down_t), _ptr(b_gate),
                                 _ptr(b_up), _ptr(b_down), _ptr(y), _ptr(active), _ptr(ws), ws.numel(), _stream()),
            "svf_sparse_ffn")
+
+
+# ---- expert skipping, acceptance / resampling (argument marshalling only) -----------------------
+
+def svf_moe_skip(w, m, beta, n_skip, keep_mask):
+    T, k = w.shape
+    _check(lib().svf_moe_skip(_ptr(w), T, k, int(m), _ptr(beta), _ptr(n_skip), _ptr(keep_mask), _stream()), "svf_moe_skip")
+
+
+def svf_moe_calibrate(w_cal, beta, ws=None):
+    T, k = w_cal.shape
+    if ws is None:
+        ws = torch.empty(int(lib().svf_moe_calibrate_workspace_bytes(T, k)), dtype=torch.uint8, device=w_cal.device)
+    _check(lib().svf_moe_calibrate(_ptr(w_cal), T, k, _ptr(beta), _ptr(ws), ws.numel(), _stream()), "svf_moe_calibrate")
+
+
+def svf_accept_resample(p_target, p_draft, draft_tokens, u_accept, u_resample, n_accepted, resampled):
+    B, gamma, V = p_target.shape
+    _check(lib().svf_accept_resample(_ptr(p_target), _ptr(p_draft), _ptr(draft_tokens), _ptr(u_accept), _ptr(u_resample),
+                                     B, gamma, V, _ptr(n_accepted), _ptr(resampled), _stream()), "svf_accept_resample")
 

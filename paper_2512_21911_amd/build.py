@@ -11,7 +11,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libsvf.so")
 
 SOURCES = ["svf_api.hip", "block_reps.hip", "score_select.hip", "verify_attn_valu.hip", "verify_attn_mfma.hip",
-           "analytics.hip", "retrieval_variants.hip", "sparse_ffn.hip", "svf_ffn_api.hip"]
+           "analytics.hip", "retrieval_variants.hip", "sparse_ffn.hip", "svf_ffn_api.hip", "spec_rules.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

@@ -204,3 +204,24 @@ def test_sparse_ffn_validates_before_launching():
     assert call(active=ctypes.c_void_p(0x10004)) == -2
     assert call(ws=null) == -6 and call(ws=ctypes.c_void_p(0x10010)) == -6 and call(ws_bytes=need - 1) == -6
 
+
+def test_rules_validate_before_launching():
+    L = S.lib()
+    ok, null = ctypes.c_void_p(0x10000), None
+    assert L.svf_moe_skip(null, 4, 8, 2, ok, ok, ok, None) == -1
+    assert L.svf_moe_skip(ok, 0, 8, 2, ok, ok, ok, None) == -2
+    assert L.svf_moe_skip(ok, 4, 1, 1, ok, ok, ok, None) == -2 and L.svf_moe_skip(ok, 4, 33, 1, ok, ok, ok, None) == -2
+    assert L.svf_moe_skip(ok, 4, 8, 0, ok, ok, ok, None) == -5 and L.svf_moe_skip(ok, 4, 8, 8, ok, ok, ok, None) == -5
+    need = L.svf_moe_calibrate_workspace_bytes(1000, 8)
+    assert need == -(-7 * 1000 * 4 // 256) * 256 and L.svf_moe_calibrate_workspace_bytes(0, 8) == 0
+    assert L.svf_moe_calibrate_workspace_bytes(10, 40) == 0
+    assert L.svf_moe_calibrate(ok, 1000, 8, null, ok, need, None) == -1
+    assert L.svf_moe_calibrate(ok, 1000, 8, ok, ok, need - 1, None) == -6
+    assert L.svf_moe_calibrate(ok, 1000, 8, ok, ctypes.c_void_p(0x10010), need, None) == -6
+    args = [ok] * 5
+    assert L.svf_accept_resample(*args, 2, 4, 100, ok, null, None) == -1
+    assert L.svf_accept_resample(*args, 0, 4, 100, ok, ok, None) == -2
+    assert L.svf_accept_resample(*args, 2, 65, 100, ok, ok, None) == -2
+    assert L.svf_accept_resample(*args, 2, 4, 0, ok, ok, None) == -2
+    assert L.svf_accept_resample(*args, 2, 4, 524289, ok, ok, None) == -2
+
