@@ -29,7 +29,7 @@ def to_gpu(x):
     return {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in x.items()}
 
 
-class GpuRun:
+class DeviceRun:
     """Device buffers of one layer plus the results of the three calls."""
 
     def __init__(self, cfg, x_gpu, shape=None, poison=True):
@@ -145,7 +145,7 @@ def check_attn(cfg, out_gpu, lse_gpu, out_ref, lse_ref):
 def full_parity(cfg, layer=0, x=None):
     """reps -> scores/select -> attention on the GPU against the oracle; returns a small report."""
     x = W.make_layer(cfg, layer) if x is None else x
-    run = GpuRun(cfg, to_gpu(x))
+    run = DeviceRun(cfg, to_gpu(x))
     run.block_reps().score_select().verify_attn().sync()
     reps_ref = check_reps(cfg, x, run.reps)
     scores_ref = O.block_scores(x["q"], reps_ref)

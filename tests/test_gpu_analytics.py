@@ -11,7 +11,7 @@ import paper_2512_21911_amd as S
 import workloads as W
 from oracle import svf_analytics_oracle as A
 from oracle import svf_oracle as O
-from svf_harness import TIE_GAP, GpuRun, shape_for, to_gpu
+from svf_harness import TIE_GAP, DeviceRun, shape_for, to_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -51,7 +51,7 @@ def positions(cfg):
 
 
 def gpu_masks(cfg, x):
-    run = GpuRun(cfg, to_gpu(x))
+    run = DeviceRun(cfg, to_gpu(x))
     run.block_reps()
     W64 = S.svf_mask_words(run.shape)
     assert W64 == -(-cfg.nb_max // 64)
@@ -132,7 +132,7 @@ def test_jaccard_of_adjacent_layers_and_anchor_choice():
     stack = []
     for layer in range(n_layers):
         x = W.make_layer(cfg, layer)
-        run = GpuRun(cfg, to_gpu(x))
+        run = DeviceRun(cfg, to_gpu(x))
         shape = run.shape
         run.block_reps().score_select()
         m = torch.empty((cfg.B, cfg.Hkv, S.svf_mask_words(shape)), dtype=torch.int64, device="cuda")

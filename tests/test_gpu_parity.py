@@ -10,7 +10,7 @@ import torch
 import paper_2512_21911_amd as S
 import workloads as W
 from oracle import svf_oracle as O
-from svf_harness import (GpuRun, check_attn, check_reps, check_selection, full_parity, oracle_attn, shape_for,
+from svf_harness import (DeviceRun, check_attn, check_reps, check_selection, full_parity, oracle_attn, shape_for,
                          to_gpu)
 
 pytestmark = pytest.mark.gpu
@@ -64,10 +64,10 @@ def test_cfg3_reuse_layer_matches_anchor_blocks():
     cfg = W.shrink(W.CONFIGS[3], 4096)
     x0 = W.make_layer(cfg, 0)
     x1 = W.make_layer(cfg, 1)
-    run0 = GpuRun(cfg, to_gpu(x0))
+    run0 = DeviceRun(cfg, to_gpu(x0))
     run0.block_reps().verify_step(True).sync()
     idx0, cnt0 = run0.sel_idx.clone(), run0.sel_cnt.clone()
-    run1 = GpuRun(cfg, to_gpu(x1))
+    run1 = DeviceRun(cfg, to_gpu(x1))
     run1.sel_idx.copy_(idx0)
     run1.sel_cnt.copy_(cnt0)
     run1.verify_step(S.SVF_STEP_REUSE).sync()            # own workspace: nothing of the anchor call in it
@@ -160,7 +160,7 @@ def test_hnd_strides_and_scale():
         xg[key] = hnd.permute(0, 2, 1, 3)                        # logical view, strides carry the layout
     shape = shape_for(cfg, xg, sm_scale=0.05)
     assert shape.kv_stride_head == cfg.page_size * cfg.d and shape.kv_stride_tok == cfg.d
-    run = GpuRun(cfg, xg, shape)
+    run = DeviceRun(cfg, xg, shape)
     run.block_reps().score_select().verify_attn().sync()
     ref = check_reps(cfg, x, run.reps)
     check_selection(cfg, x, O.block_scores(x["q"], ref), run.sel_idx, run.sel_cnt)
@@ -173,11 +173,11 @@ def test_per_batch_masks_and_null_mask():
     x = W.make_layer(cfg)
     xg = to_gpu(x)
     masks = torch.tensor([[1, 3, 5, 9, 19], [1, 3, 7, 15, 31]], dtype=torch.int64)
-    run = GpuRun(cfg, xg, shape_for(cfg, xg, mask_per_batch=1))
+    run = DeviceRun(cfg, xg, shape_for(cfg, xg, mask_per_batch=1))
     run.block_reps().score_select().verify_attn(mask=masks.cuda()).sync()
     ref, lse = oracle_attn(cfg, x, run.sel_idx.cpu(), run.sel_cnt.cpu(), mask=masks)
     check_attn(cfg, run.out, run.lse, ref, lse)
-    run2 = GpuRun(cfg, xg)
+    run2 = DeviceRun(cfg, xg)
     run2.block_reps().score_select().verify_attn(mask=None).sync()     # NULL mask = linear causal
     ref2, lse2 = oracle_attn(cfg, x, run2.sel_idx.cpu(), run2.sel_cnt.cpu(), mask=None)
     check_attn(cfg, run2.out, run2.lse, ref2, lse2)
@@ -187,7 +187,7 @@ def test_incremental_block_reps():
     """Representatives of a block range only: other rows stay untouched."""
     cfg = small()
     x = W.make_layer(cfg)
-    run = GpuRun(cfg, to_gpu(x), poison=False)
+    run = DeviceRun(cfg, to_gpu(x), poison=False)
     run.reps.fill_(123.0)
     run.block_reps(first_block=5, n_blocks=3).sync()
     ref = O.block_reps(x["k_pool"], x["block_table"], x["seq_lens"], cfg.block_size, cfg.nb_max)
@@ -200,7 +200,7 @@ def test_exact_ties_lowest_index_wins():
     """All representatives equal => every score ties => blocks 0..k-1 (after forced ones)."""
     cfg = small(n_sink=0, n_local=1, k_blocks=4)
     x = W.make_layer(cfg)
-    run = GpuRun(cfg, to_gpu(x), poison=False)
+    run = DeviceRun(cfg, to_gpu(x), poison=False)
     run.reps.fill_(0.25)
     run.score_select().sync()
     idx = run.sel_idx.cpu().numpy()
@@ -217,7 +217,7 @@ def test_constant_values_give_constant_output():
     x = W.make_layer(cfg)
     x["v_pool"] = torch.full_like(x["v_pool"], 0.375)
     x["v_draft"] = torch.full_like(x["v_draft"], 0.375)
-    run = GpuRun(cfg, to_gpu(x))
+    run = DeviceRun(cfg, to_gpu(x))
     run.block_reps().score_select().verify_attn().sync()
     out = run.out.float().cpu()
     assert (out - 0.375).abs().max() <= 0.375 * 2 ** -8        # one bf16 ulp
@@ -226,7 +226,7 @@ def test_constant_values_give_constant_output():
 def test_unselected_block_cannot_influence_output():
     cfg = W.shrink(W.CONFIGS[3], 4096)
     x = W.make_layer(cfg)
-    run = GpuRun(cfg, to_gpu(x))
+    run = DeviceRun(cfg, to_gpu(x))
     run.block_reps().score_select().verify_attn().sync()
     out0, idx0 = run.out.clone(), run.sel_idx.clone()
     # overwrite V of one unselected block per (b, h) with large noise
@@ -251,7 +251,7 @@ def test_page_permutation_is_invisible():
     """Same logical cache in two physical page orders: identical representatives, ids and outputs."""
     cfg = W.shrink(W.CONFIGS[3], 4096)
     x = W.make_layer(cfg)
-    run = GpuRun(cfg, to_gpu(x))
+    run = DeviceRun(cfg, to_gpu(x))
     run.block_reps().score_select().verify_attn().sync()
     n_pages = x["k_pool"].shape[0]
     perm = torch.randperm(n_pages, generator=torch.Generator().manual_seed(3))
@@ -261,7 +261,7 @@ def test_page_permutation_is_invisible():
     y["k_pool"] = x["k_pool"][perm]
     y["v_pool"] = x["v_pool"][perm]
     y["block_table"] = inv[x["block_table"].long()].to(torch.int32)
-    run2 = GpuRun(cfg, to_gpu(y))
+    run2 = DeviceRun(cfg, to_gpu(y))
     run2.block_reps().score_select().verify_attn().sync()
     assert torch.equal(run.reps.view(torch.int32), run2.reps.view(torch.int32))
     assert torch.equal(run.sel_idx, run2.sel_idx)
@@ -271,7 +271,7 @@ def test_page_permutation_is_invisible():
 def test_repeated_calls_are_bit_stable():
     cfg = W.CONFIGS[2]
     x = W.make_layer(cfg)
-    run = GpuRun(cfg, to_gpu(x))
+    run = DeviceRun(cfg, to_gpu(x))
     run.block_reps().score_select().verify_attn().sync()
     out0, idx0 = run.out.clone(), run.sel_idx.clone()
     for _ in range(5):
@@ -287,7 +287,7 @@ def test_anchor_retrieval_same_bits_with_and_without_key_exchange(cfg_id, T):
     wait of zero or one poll sends some or all of them down the score-everything path."""
     cfg = W.shrink(W.CONFIGS[cfg_id], T)
     x = W.make_layer(cfg)
-    run = GpuRun(cfg, to_gpu(x))
+    run = DeviceRun(cfg, to_gpu(x))
     run.block_reps().score_select().verify_attn().sync()
     out0, idx0, cnt0 = run.out.clone(), run.sel_idx.clone(), run.sel_cnt.clone()
     try:

@@ -13,7 +13,7 @@ import paper_2512_21911_amd as S
 import workloads as W
 from oracle import svf_oracle as O
 from oracle import svf_variants_oracle as V
-from svf_harness import REPS_TOL, TIE_GAP, GpuRun, check_attn, check_selection, oracle_attn, shape_for, to_gpu
+from svf_harness import REPS_TOL, TIE_GAP, DeviceRun, check_attn, check_selection, oracle_attn, shape_for, to_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -87,7 +87,7 @@ def run_variant(cfg, summary, sdtype, group, budget, n_total=0, stride=None, x=N
     x = W.make_layer(cfg) if x is None else x
     k_row = cfg.k_blocks if stride is None else stride
     shape = shape_for(cfg, x, k_blocks=k_row)
-    run = GpuRun(cfg, to_gpu(x), shape=shape)
+    run = DeviceRun(cfg, to_gpu(x), shape=shape)
     rt = S.SvfRetrieval(summary, sdtype, group, budget, n_total)
     rows = 2 if summary == MINMAX else 1
     tdt = torch.bfloat16 if sdtype == BF16 else torch.float32
@@ -150,7 +150,7 @@ def test_cfg3_shape_shrunk(summary, sdtype, group, budget):
 def test_defaults_are_the_main_path_bit_for_bit():
     cfg = small(dtype="bf16", d=128, Hq=8, Hkv=2)
     x = W.make_layer(cfg)
-    run = GpuRun(cfg, to_gpu(x))
+    run = DeviceRun(cfg, to_gpu(x))
     run.block_reps().score_select().sync()
     rt = S.SvfRetrieval(MEAN, F32, GMEAN, PER_HEAD, 0)
     summ = torch.full_like(run.reps, float("nan"))
@@ -170,7 +170,7 @@ def test_global_with_one_kv_head_is_the_per_head_rule():
     cfg = small(Hq=4, Hkv=1, k_blocks=7)
     x = W.make_layer(cfg)
     run_g, _, _ = run_variant(cfg, MEAN, F32, GMEAN, GLOBAL, 7, stride=7, x=x, attn=False)
-    run_p = GpuRun(cfg, to_gpu(x))
+    run_p = DeviceRun(cfg, to_gpu(x))
     run_p.block_reps().score_select().sync()
     assert torch.equal(run_g.sel_idx, run_p.sel_idx) and torch.equal(run_g.sel_cnt, run_p.sel_cnt)
 
