@@ -107,7 +107,7 @@ __device__ __forceinline__ void walk_tile(const FfnParams& p, const char* w_rows
 #pragma unroll
     for (int n = 0; n < 8; ++n)
       __builtin_amdgcn_global_load_lds(FFN_GLOBAL_PTR(w_rows + src_off[n] + (int64_t)kc * kRowBytes),
-                                       FFN_LDS_PTR(dst + n * 1024), 16, 0, 0);
+                                       FFN_LDS_PTR(dst + n * 1024), 16, 0, 2);
   };
   u32x4 xa[NT][8], xb[NT][8];
   auto load_x = [&](int kc, u32x4 (&xr)[NT][8]) {
@@ -319,7 +319,8 @@ __global__ __launch_bounds__(kDnThreads) void ffn_down_kernel(FfnParams p) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       u32x2 v = {0u, 0u};
-      if ((mine >> e) & 1u) v = *reinterpret_cast<const u32x2*>(wd + (int64_t)(16 * s + 8 * g + e) * row_bytes);
+      if ((mine >> e) & 1u)
+        v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(wd + (int64_t)(16 * s + 8 * g + e) * row_bytes));
       d.w[e] = v;
     }
 #pragma unroll

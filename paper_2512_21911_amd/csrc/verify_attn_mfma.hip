@@ -857,8 +857,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       // rows past the group's last valid row re-read that row
       const uint32_t r = min((uint32_t)lrow, (uint32_t)max(nvn - 1, 0));
       const uint32_t off = r * row_bytes + ((cx ^ (uint32_t)((4 * n) & 15)) << 4);
-      __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(kb + off), SVF_LDS_PTR(dst + n * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(vb + off), SVF_LDS_PTR(vdst + n * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(kb + off), SVF_LDS_PTR(dst + n * 1024), 16, 0, 2);
+      __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(vb + off), SVF_LDS_PTR(vdst + n * 1024), 16, 0, 2);
     }
     return ti;
   };
@@ -1075,8 +1075,8 @@ __device__ __forceinline__ void issue_row_tile(const RowTileIssue& c, int i) {
   const char* vb = kb + (int64_t)(((uint64_t)c.dv_d & fd) | ((uint64_t)c.dv_c & ~fd));
   const uint32_t r = min(c.lrow, (uint32_t)max(nv - 1, 0));
   const uint32_t off = r * row_bytes + ((c.cx ^ (uint32_t)((4 * c.wave) & 15)) << 4);
-  __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(kb + off), SVF_LDS_PTR(dst + c.wave * 1024), 16, 0, 0);
-  __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(vb + off), SVF_LDS_PTR(dst + kTileBytes + c.wave * 1024), 16, 0, 0);
+  __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(kb + off), SVF_LDS_PTR(dst + c.wave * 1024), 16, 0, 2);
+  __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(vb + off), SVF_LDS_PTR(dst + kTileBytes + c.wave * 1024), 16, 0, 2);
   if (c.lane == 0) lds_write4(c.nv_lds + (uint32_t)(st * kWaves + c.wave) * 4u, (uint32_t)nv);
 }
 
