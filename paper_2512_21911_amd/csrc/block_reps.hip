@@ -32,7 +32,8 @@ template <>
 struct Vec16<__hip_bfloat16> {
   static constexpr int N = 8;
   __device__ static void load(const __hip_bfloat16* p, float (&v)[8]) {
-    const uint4 x = *reinterpret_cast<const uint4*>(p);
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));   // read once
     const uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
