@@ -109,15 +109,15 @@ __device__ __forceinline__ void walk_tile(const FfnParams& p, const char* w_rows
       __builtin_amdgcn_global_load_lds(FFN_GLOBAL_PTR(w_rows + src_off[n] + (int64_t)kc * kRowBytes),
                                        FFN_LDS_PTR(dst + n * 1024), 16, 0, 2);
   };
-  u32x4 xa[NT][8], xb[NT][8];
-  auto load_x = [&](int kc, u32x4 (&xr)[NT][8]) {
+  u32x4 xr[NT][8];
+  auto load_x = [&](int kc) {
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks)
         xr[t][ks] = *reinterpret_cast<const u32x4*>(xrow[t] + (int64_t)kc * kRowBytes + ks * 32);
   };
-  auto compute = [&](const unsigned char* src, const u32x4 (&xr)[NT][8]) {
+  auto compute = [&](const unsigned char* src) {
     const uint32_t base = (uint32_t)(uintptr_t)FFN_LDS_PTR(src) + l32 * kRowBytes;
     const uint32_t kx = (uint32_t)((g ^ (l32 & 15)) << 4);
     u32x4 wf[8];
@@ -132,35 +132,28 @@ __device__ __forceinline__ void walk_tile(const FfnParams& p, const char* w_rows
                                                          __builtin_bit_cast(bf16x8, xr[t][ks]), acc[t], 0, 0, 0);
   };
 
-  // chunks wave, wave + 4, ...: two at a time so that the register sets alternate without copies
+  // Chunks wave, wave + 4, ...  The weight chunk after this one is on its way into the other
+  // stage while this one is multiplied; the x pieces of the next chunk are loaded right after
+  // the multiply (one register set), long before that chunk's weights can have arrived.  Loads
+  // retire in order, so "all but the eight just issued" is one fixed wait count.
   int kc = wave;
   if (kc >= n_chunks) return;
   issue(kc, stage);
-  load_x(kc, xa);
-  // (each branch has its own wait and its own copy of the multiply, so that no wait has to
-  // serve both the path with loads in flight and the one without)
+  load_x(kc);
+  int cur = 0;
   while (true) {
     const int kn = kc + kGuWaves;
     if (kn >= n_chunks) {
       wait_vmcnt<0>();
-      compute(stage, xa);
+      compute(stage + cur * kChunkBytes);
       break;
     }
-    issue(kn, stage + kChunkBytes);
-    load_x(kn, xb);
-    wait_vmcnt<8 + 8 * NT>();
-    compute(stage, xa);
-    const int kn2 = kn + kGuWaves;
-    if (kn2 >= n_chunks) {
-      wait_vmcnt<0>();
-      compute(stage + kChunkBytes, xb);
-      break;
-    }
-    issue(kn2, stage);
-    load_x(kn2, xa);
-    wait_vmcnt<8 + 8 * NT>();
-    compute(stage + kChunkBytes, xb);
-    kc = kn2;
+    issue(kn, stage + (cur ^ 1) * kChunkBytes);
+    wait_vmcnt<8>();
+    compute(stage + cur * kChunkBytes);
+    load_x(kn);
+    kc = kn;
+    cur ^= 1;
   }
 }
 
