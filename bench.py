@@ -332,8 +332,9 @@ def sffn(args):
 
     row = cfg.d_model * 2
     table = {}
-    for tau in (0.0, 0.01, 0.05, 0.1):
-        shape = S.make_ffn_shape(M=cfg.M, d_model=cfg.d_model, d_ff=cfg.d_ff, act=cfg.act, tau=tau)
+    for walk, tau in [(S.SVF_FFN_WALK_AUTO, t) for t in (0.0, 0.01, 0.05, 0.1)] + \
+                     [(S.SVF_FFN_WALK_GATE_FIRST, t) for t in (0.0, 0.05, 0.1)]:
+        shape = S.make_ffn_shape(M=cfg.M, d_model=cfg.d_model, d_ff=cfg.d_ff, act=cfg.act, tau=tau, walk=walk)
         ws = S.new_ffn_workspace(shape)
 
         def all_layers():
@@ -349,7 +350,8 @@ def sffn(args):
         rows = float((bits != 0).mean())
         per_tok = float(np.mean([((bits >> np.uint64(m)) & np.uint64(1)).mean() for m in range(cfg.M)]))
         alg = int(cfg.d_ff * row * (1 + 2 * rows) + 2 * cfg.M * row)
-        table[f"tau={tau}"] = {"us_per_layer": round(us, 2), "token_sparsity": round(1 - per_tok, 3),
+        key = f"tau={tau}" if walk == S.SVF_FFN_WALK_AUTO else f"gate_first tau={tau}"
+        table[key] = {"us_per_layer": round(us, 2), "token_sparsity": round(1 - per_tok, 3),
                                "rows_read": round(rows, 3), "algorithmic_bytes": alg,
                                "GBps": round(alg / (us * 1e-6) / 1e9, 1)}
     head = table["tau=0.05"]
@@ -375,7 +377,7 @@ def sffn(args):
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "M": cfg.M, "d_model": cfg.d_model, "d_ff": cfg.d_ff, "act": cfg.act,
                    "tau": 0.05, "launch": "stream"},
-        "roofline": {"bound": "hbm", "kernel": "ffn_gate_up_kernel + ffn_down_kernel + ffn_reduce_kernel",
+        "roofline": {"bound": "hbm", "kernel": "ffn_gate_up_fused_kernel + ffn_down_kernel + ffn_reduce_kernel",
                      "achieved": head["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(head["GBps"] / HBM_PEAK_GBPS, 4), "traffic": None,
                      "algorithmic_bytes_per_launch": head["algorithmic_bytes"], "avg_launch_us": head["us_per_layer"]},

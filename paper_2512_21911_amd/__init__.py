@@ -10,6 +10,6 @@ from .binding import (SVF_BF16, SVF_F32, SVF_STEP_ANCHOR, SVF_STEP_REUSE, SVF_ST
                       svf_overlap_by_distance, svf_select_per_draft, svf_topk_anchors,
                       SVF_BUDGET_GLOBAL, SVF_BUDGET_PER_HEAD, SVF_GROUP_MAX, SVF_GROUP_MEAN, SVF_SUMMARY_MEAN,
                       SVF_SUMMARY_MINMAX, SvfRetrieval, svf_block_summaries, svf_retrieve,
-                      SVF_ACT_GELU, SVF_ACT_SILU, SvfFfnShape, make_ffn_shape, new_ffn_workspace,
+                      SVF_ACT_GELU, SVF_ACT_SILU, SVF_FFN_WALK_AUTO, SVF_FFN_WALK_GATE_FIRST, SVF_FFN_WALK_TOGETHER, SvfFfnShape, make_ffn_shape, new_ffn_workspace,
                       svf_ffn_workspace_bytes, svf_sparse_ffn,
                       svf_accept_resample, svf_moe_calibrate, svf_moe_skip)

@@ -46,10 +46,11 @@ SVF_BUDGET_PER_HEAD, SVF_BUDGET_GLOBAL = 0, 1
 class SvfFfnShape(ctypes.Structure):
     """Mirror of svf_ffn_shape_t (include/svf_ffn.h)."""
     _fields_ = [("M", ctypes.c_int32), ("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32), ("act", ctypes.c_int32),
-                ("tau", ctypes.c_float)]
+                ("tau", ctypes.c_float), ("walk", ctypes.c_int32)]
 
 
 SVF_ACT_SILU, SVF_ACT_GELU = 0, 1
+SVF_FFN_WALK_AUTO, SVF_FFN_WALK_GATE_FIRST, SVF_FFN_WALK_TOGETHER = 0, 1, 2
 
 
 class SvfError(RuntimeError):
@@ -287,9 +288,9 @@ def svf_retrieve(shape, retrieval, q, summaries, seq_lens, sel_idx, sel_cnt, ws,
 
 # ---- sparse feed-forward verification (argument marshalling only) ------------------------------
 
-def make_ffn_shape(*, M, d_model, d_ff, act="silu", tau=0.0) -> SvfFfnShape:
+def make_ffn_shape(*, M, d_model, d_ff, act="silu", tau=0.0, walk=SVF_FFN_WALK_AUTO) -> SvfFfnShape:
     code = {"silu": SVF_ACT_SILU, "gelu": SVF_ACT_GELU}.get(act, act)
-    return SvfFfnShape(M, d_model, d_ff, code, tau)
+    return SvfFfnShape(M, d_model, d_ff, code, tau, walk)
 
 
 def svf_ffn_workspace_bytes(shape: SvfFfnShape) -> int:

@@ -6,15 +6,17 @@
 // in long contiguous runs, and the rows of W_up / W_down of hidden channels that are inactive
 // for all M tokens are not read at all.
 //
-//   gate_up kernel  one workgroup of four wavefronts per tile of 32 hidden channels; the
-//                   wavefronts split the model dimension in chunks of 128.  A chunk of the
-//                   tile (32 rows x 256 bytes) goes straight from global memory to the
-//                   wavefront's own LDS stage (two stages, the next chunk is in flight while
-//                   this one is multiplied), the matching piece of x comes through registers.
-//                   Gate first: h = act(W_gate x + b_gate), the active bits |h| >= tau per
-//                   (channel, token); then the same walk over W_up, where a row that no token
-//                   needs is replaced by a row that is read anyway; h * up, masked per token,
-//                   goes out as bf16 [tokens][d_ff].
+//   gate/up kernels one workgroup of four wavefronts per tile of hidden channels; the wavefronts
+//                   split the model dimension in chunks of 128.  A chunk of the tile (32 rows x
+//                   256 bytes per matrix) goes straight from global memory to the wavefront's
+//                   own LDS stage (two stages, the next chunk is in flight while this one is
+//                   multiplied), the matching piece of x comes through registers.
+//                   Joint walk (default): the gate and the up matrix together, then
+//                   h = act(W_gate x + b_gate), the active bits |h| >= tau per (channel, token),
+//                   and h * up, masked per token, out as bf16 [tokens][d_ff]; x is fetched once
+//                   for both matrices and nothing waits between them, but every row of W_up is
+//                   read.  Gate first: the gate walk, the active bits, then the same walk over
+//                   W_up where a row that no token needs is replaced by a row that is read anyway.
 //   down kernel     y^T = W_down^T-rows times h_up: one workgroup of eight wavefronts per
 //                   (128 output columns, slice of the hidden channels).  The weight rows are
 //                   contiguous along the output dimension while the matrix core wants its
@@ -80,12 +82,16 @@ __device__ __forceinline__ float activate(float z, int act) {
   return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
 }
 
-// One walk of a wavefront over its chunks of a 32-row tile: acc[t] += W_tile(chunk) x^T(chunk).
-//   w_rows: address of row 0 of the tile; row_of(r): which tile row to read for row r (a row
-//   nobody needs is redirected, its products are thrown away); stage: the wavefront's two LDS stages.
-template <int NT, typename RowOf>
-__device__ __forceinline__ void walk_tile(const FfnParams& p, const char* w_rows, RowOf row_of, const char* x,
-                                          unsigned char* stage, int wave, int lane, floatx16 (&acc)[NT]) {
+// One walk of a wavefront over its chunks of a 32-row tile of NMAT matrices at once (the same
+// rows of each): acc[mat][t] += W_mat_tile(chunk) x^T(chunk).
+//   w_rows[mat]: address of row 0 of the tile in matrix mat; row_of(r): which tile row to read
+//   for row r (a row nobody needs is redirected, its products are thrown away); stage: the
+//   wavefront's two LDS stages of NMAT chunks each.
+template <int NT, int NMAT, typename RowOf>
+__device__ __forceinline__ void walk_tile(const FfnParams& p, const char* const (&w_rows)[NMAT], RowOf row_of,
+                                          const char* x, unsigned char* stage, int wave, int lane,
+                                          floatx16 (&acc)[NMAT][NT]) {
+  constexpr int kStageBytes = NMAT * kChunkBytes;
   const int l32 = lane & 31, g = lane >> 5;
   const int n_chunks = p.d_model / kChunkK;
   const int64_t row_bytes = (int64_t)p.d_model * 2;
@@ -105,9 +111,11 @@ __device__ __forceinline__ void walk_tile(const FfnParams& p, const char* w_rows
 
   auto issue = [&](int kc, unsigned char* dst) {
 #pragma unroll
-    for (int n = 0; n < 8; ++n)
-      __builtin_amdgcn_global_load_lds(FFN_GLOBAL_PTR(w_rows + src_off[n] + (int64_t)kc * kRowBytes),
-                                       FFN_LDS_PTR(dst + n * 1024), 16, 0, 2);
+    for (int mat = 0; mat < NMAT; ++mat)
+#pragma unroll
+      for (int n = 0; n < 8; ++n)
+        __builtin_amdgcn_global_load_lds(FFN_GLOBAL_PTR(w_rows[mat] + src_off[n] + (int64_t)kc * kRowBytes),
+                                         FFN_LDS_PTR(dst + mat * kChunkBytes + n * 1024), 16, 0, 2);
   };
   u32x4 xr[NT][8];
   auto load_x = [&](int kc) {
@@ -118,24 +126,28 @@ __device__ __forceinline__ void walk_tile(const FfnParams& p, const char* w_rows
         xr[t][ks] = *reinterpret_cast<const u32x4*>(xrow[t] + (int64_t)kc * kRowBytes + ks * 32);
   };
   auto compute = [&](const unsigned char* src) {
-    const uint32_t base = (uint32_t)(uintptr_t)FFN_LDS_PTR(src) + l32 * kRowBytes;
     const uint32_t kx = (uint32_t)((g ^ (l32 & 15)) << 4);
-    u32x4 wf[8];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) wf[ks] = lds_read16(base + (kx ^ (uint32_t)(ks << 5)));
-    lds_wait(wf);
+    for (int mat = 0; mat < NMAT; ++mat) {
+      const uint32_t base = (uint32_t)(uintptr_t)FFN_LDS_PTR(src + mat * kChunkBytes) + l32 * kRowBytes;
+      u32x4 wf[8];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
+      for (int ks = 0; ks < 8; ++ks) wf[ks] = lds_read16(base + (kx ^ (uint32_t)(ks << 5)));
+      lds_wait(wf);
 #pragma unroll
-      for (int t = 0; t < NT; ++t)
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[ks]),
-                                                         __builtin_bit_cast(bf16x8, xr[t][ks]), acc[t], 0, 0, 0);
+      for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          acc[mat][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[ks]),
+                                                                __builtin_bit_cast(bf16x8, xr[t][ks]), acc[mat][t], 0,
+                                                                0, 0);
+    }
   };
 
   // Chunks wave, wave + 4, ...  The weight chunk after this one is on its way into the other
   // stage while this one is multiplied; the x pieces of the next chunk are loaded right after
   // the multiply (one register set), long before that chunk's weights can have arrived.  Loads
-  // retire in order, so "all but the eight just issued" is one fixed wait count.
+  // retire in order, so "all but the 8 NMAT just issued" is one fixed wait count.
   int kc = wave;
   if (kc >= n_chunks) return;
   issue(kc, stage);
@@ -145,12 +157,12 @@ __device__ __forceinline__ void walk_tile(const FfnParams& p, const char* w_rows
     const int kn = kc + kGuWaves;
     if (kn >= n_chunks) {
       wait_vmcnt<0>();
-      compute(stage + cur * kChunkBytes);
+      compute(stage + cur * kStageBytes);
       break;
     }
-    issue(kn, stage + (cur ^ 1) * kChunkBytes);
-    wait_vmcnt<8>();
-    compute(stage + cur * kChunkBytes);
+    issue(kn, stage + (cur ^ 1) * kStageBytes);
+    wait_vmcnt<8 * NMAT>();
+    compute(stage + cur * kStageBytes);
     load_x(kn);
     kc = kn;
     cur ^= 1;
@@ -192,14 +204,16 @@ __global__ __launch_bounds__(kGuThreads) void ffn_gate_up_kernel(FfnParams p) {
   };
 
   // ---- gate: h = act(W_gate x + b_gate), active bits (Eq. 10, 12) ----
-  floatx16 acc[NT];
+  floatx16 acc[1][NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
-  walk_tile<NT>(p, static_cast<const char*>(p.w_gate) + (int64_t)c0 * row_bytes, [](int r) { return r; }, x, stage,
-                wave, lane, acc);
-  put_partial(acc);
+    for (int v = 0; v < 16; ++v) acc[0][t][v] = 0.f;
+  {
+    const char* const rows[1] = {static_cast<const char*>(p.w_gate) + (int64_t)c0 * row_bytes};
+    walk_tile<NT, 1>(p, rows, [](int r) { return r; }, x, stage, wave, lane, acc);
+  }
+  put_partial(acc[0]);
   __syncthreads();
   {
     // thread: channel tid / 8, tokens (tid % 8) * 4 NT ... + 4 NT
@@ -221,6 +235,7 @@ __global__ __launch_bounds__(kGuThreads) void ffn_gate_up_kernel(FfnParams p) {
     }
     if ((tid & 7) == 0) {
       s_act[c] = bits;
+      p.rowany[c0 + c] = bits != 0 ? 1 : 0;
       if (p.active) p.active[c0 + c] = bits;
     }
   }
@@ -229,7 +244,6 @@ __global__ __launch_bounds__(kGuThreads) void ffn_gate_up_kernel(FfnParams p) {
   // ---- up: only rows some token needs are read; h * up per token (Eq. 13) ----
   const uint64_t my_bits = s_act[l32];
   const uint32_t rowmask = (uint32_t)__ballot(my_bits != 0 && lane < 32);
-  if (tid == 0) p.rowmask[blockIdx.x] = rowmask;
   bf16x8 zero8;
 #pragma unroll
   for (int i = 0; i < 8; ++i) zero8[i] = 0;
@@ -244,10 +258,12 @@ __global__ __launch_bounds__(kGuThreads) void ffn_gate_up_kernel(FfnParams p) {
 #pragma unroll
   for (int t = 0; t < NT; ++t)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
-  walk_tile<NT>(p, static_cast<const char*>(p.w_up) + (int64_t)c0 * row_bytes,
-                [=](int r) { return ((rowmask >> r) & 1u) ? r : first; }, x, stage, wave, lane, acc);
-  put_partial(acc);
+    for (int v = 0; v < 16; ++v) acc[0][t][v] = 0.f;
+  {
+    const char* const rows[1] = {static_cast<const char*>(p.w_up) + (int64_t)c0 * row_bytes};
+    walk_tile<NT, 1>(p, rows, [=](int r) { return ((rowmask >> r) & 1u) ? r : first; }, x, stage, wave, lane, acc);
+  }
+  put_partial(acc[0]);
   __syncthreads();
   if (om < 32 * NT) {
     u32x4 w;
@@ -263,6 +279,85 @@ __global__ __launch_bounds__(kGuThreads) void ffn_gate_up_kernel(FfnParams p) {
       w[j] = pack_bf16(hu[0], hu[1]);
     }
     *reinterpret_cast<u32x4*>(out) = w;
+  }
+}
+
+// The same result with the gate and the up matrix walked together: x is fetched once per chunk for
+// both, and the workgroup's memory pipeline does not run dry between a gate and an up walk; the
+// price is that every row of W_up is read, needed or not.  One workgroup per compute unit (128 KB
+// of stages), so the tiles are cut to p.tile_rows <= 32 channels such that the tile count fills
+// whole rounds of workgroups; the rows of the 32-row matrix-core tile past that repeat the last one.
+// grid: (ceil(d_ff / tile_rows)); block: 256
+template <int NT>
+__global__ __launch_bounds__(kGuThreads) void ffn_gate_up_fused_kernel(FfnParams p) {
+  constexpr int RS = 32 * NT + 1;
+  constexpr int kWaveBytes = kStages * 2 * kChunkBytes;  // a wavefront's two stages of two chunks
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[kGuWaves * kWaveBytes];
+  static_assert(2 * kTileRows * RS * 4 <= kWaveBytes, "a wavefront's two partial tiles fit its own stages");
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int c0 = blockIdx.x * p.tile_rows;
+  const int rows_here = min(p.tile_rows, p.d_ff - c0);
+  unsigned char* stage = smem + wave * kWaveBytes;
+  const int64_t row_bytes = (int64_t)p.d_model * 2;
+
+  floatx16 acc[2][NT];
+#pragma unroll
+  for (int mat = 0; mat < 2; ++mat)
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[mat][t][v] = 0.f;
+  {
+    const char* const rows[2] = {static_cast<const char*>(p.w_gate) + (int64_t)c0 * row_bytes,
+                                 static_cast<const char*>(p.w_up) + (int64_t)c0 * row_bytes};
+    walk_tile<NT, 2>(p, rows, [=](int r) { return min(r, rows_here - 1); }, static_cast<const char*>(p.x), stage, wave,
+                     lane, acc);
+  }
+  // partial tiles [matrix][channel][token] into this wavefront's own stages
+  float* red = reinterpret_cast<float*>(stage);
+#pragma unroll
+  for (int mat = 0; mat < 2; ++mat)
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        red[(mat * kTileRows + 8 * (v >> 2) + 4 * g + (v & 3)) * RS + l32 + 32 * t] = acc[mat][t][v];
+  __syncthreads();
+  // thread: channel tid / 8, tokens (tid % 8) * 4 NT ... + 4 NT
+  const int c = tid >> 3, m0 = (tid & 7) * 4 * NT;
+  if (c >= rows_here) return;
+  const float bg = p.b_gate ? p.b_gate[c0 + c] : 0.f;
+  const float bu = p.b_up ? p.b_up[c0 + c] : 0.f;
+  uint64_t bits = 0;
+#pragma unroll
+  for (int i = 0; i < 4 * NT; ++i) {
+    const int m = m0 + i;
+    float zg = 0.f, zu = 0.f;
+#pragma unroll
+    for (int w = 0; w < kGuWaves; ++w) {
+      const float* r = reinterpret_cast<const float*>(smem + w * kWaveBytes);
+      zg += r[c * RS + m];
+      zu += r[(kTileRows + c) * RS + m];
+    }
+    const float h = activate(zg + bg, p.act);
+    const bool on = m < p.M && !(fabsf(h) < p.tau);
+    if (on) bits |= 1ull << m;
+    const float hu = on ? h * (zu + bu) : 0.f;
+    reinterpret_cast<__hip_bfloat16*>(p.h_up)[(int64_t)m * p.d_ff + c0 + c] = __float2bfloat16(hu);
+  }
+  // the eight threads of a channel are neighbours in a wavefront (and leave together)
+#pragma unroll
+  for (int o = 1; o < 8; o <<= 1) {
+    const uint32_t lo = __shfl_xor((uint32_t)bits, o, 64), hi = __shfl_xor((uint32_t)(bits >> 32), o, 64);
+    bits |= (uint64_t)lo | ((uint64_t)hi << 32);
+  }
+  if ((tid & 7) == 0) {
+    p.rowany[c0 + c] = bits != 0 ? 1 : 0;
+    if (p.active) p.active[c0 + c] = bits;
   }
 }
 
@@ -307,7 +402,11 @@ __global__ __launch_bounds__(kDnThreads) void ffn_down_kernel(FfnParams p) {
   // k-slot e of lane half g in step s is channel 16 s + 8 g + e
   auto load_step = [&](int s, DownLoads<NT>& d) {
     d.bits = 0;
-    if (s < n_steps) d.bits = (p.rowmask[s >> 1] >> ((s & 1) * 16)) & 0xffffu;   // uniform
+    if (s < n_steps) {                                                            // uniform
+      const u32x4 any = *reinterpret_cast<const u32x4*>(p.rowany + 16 * s);     // one byte per channel
+#pragma unroll
+      for (int i = 0; i < 16; ++i) d.bits |= ((any[i >> 2] >> (8 * (i & 3))) & 0xffu) ? (1u << i) : 0u;
+    }
     const uint32_t mine = (d.bits >> (8 * g)) & 0xffu;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -414,6 +513,20 @@ __global__ __launch_bounds__(256) void ffn_reduce_kernel(FfnParams p) {
 
 }  // namespace
 
+// Channels per tile of the fused walk: one workgroup per compute unit runs at a time, so the
+// cost is (rounds of 256 workgroups) x (rows per tile); the largest multiple of four that
+// minimises it.
+int ffn_fused_tile_rows(int d_ff) {
+  int best = kTileRows;
+  int64_t best_cost = -1;
+  for (int r = kTileRows; r >= 16; r -= 4) {
+    const int64_t tiles = (d_ff + r - 1) / r;
+    const int64_t cost = ((tiles + 255) / 256) * r;
+    if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = r; }
+  }
+  return best;
+}
+
 int ffn_k_splits(int d_model, int d_ff) {
   const int n_tiles = d_model / kDnCols;
   int ks = 256 / (n_tiles > 0 ? n_tiles : 1);                                     // one workgroup per compute unit
@@ -423,8 +536,15 @@ int ffn_k_splits(int d_model, int d_ff) {
 }
 
 hipError_t launch_sparse_ffn(const FfnParams& p, hipStream_t st) {
-  if (p.M <= 32) hipLaunchKernelGGL(ffn_gate_up_kernel<1>, dim3(p.d_ff / kTileRows), dim3(kGuThreads), 0, st, p);
-  else hipLaunchKernelGGL(ffn_gate_up_kernel<2>, dim3(p.d_ff / kTileRows), dim3(kGuThreads), 0, st, p);
+  const dim3 gu(p.d_ff / kTileRows);
+  if (p.fused_walk) {
+    const dim3 gf((p.d_ff + p.tile_rows - 1) / p.tile_rows);
+    if (p.M <= 32) hipLaunchKernelGGL(ffn_gate_up_fused_kernel<1>, gf, dim3(kGuThreads), 0, st, p);
+    else hipLaunchKernelGGL(ffn_gate_up_fused_kernel<2>, gf, dim3(kGuThreads), 0, st, p);
+  } else {
+    if (p.M <= 32) hipLaunchKernelGGL(ffn_gate_up_kernel<1>, gu, dim3(kGuThreads), 0, st, p);
+    else hipLaunchKernelGGL(ffn_gate_up_kernel<2>, gu, dim3(kGuThreads), 0, st, p);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   dim3 gd(p.d_model / kDnCols, p.k_splits);

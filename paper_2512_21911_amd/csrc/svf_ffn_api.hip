@@ -16,6 +16,8 @@ int check_ffn_shape(const svf_ffn_shape_t* s) {
   if (s->d_ff < 32 || s->d_ff % 32 != 0 || s->d_ff > (1 << 24)) return SVF_ERR_SHAPE;
   if (s->act != SVF_ACT_SILU && s->act != SVF_ACT_GELU) return SVF_ERR_SHAPE;
   if (!(s->tau >= 0.0f) || std::isinf(s->tau)) return SVF_ERR_SHAPE;
+  if (s->walk != SVF_FFN_WALK_AUTO && s->walk != SVF_FFN_WALK_GATE_FIRST && s->walk != SVF_FFN_WALK_TOGETHER)
+    return SVF_ERR_SHAPE;
   return SVF_OK;
 }
 
@@ -31,7 +33,7 @@ FfnPlan plan_ffn(const svf_ffn_shape_t& s) {
   pl.off_h_up = off;
   off += align_up((size_t)64 * s.d_ff * 2);
   pl.off_rowmask = off;
-  off += align_up((size_t)(s.d_ff / 32) * 4);
+  off += align_up((size_t)s.d_ff);
   pl.off_partial = off;
   off += align_up((size_t)pl.k_splits * s.M * s.d_model * 4);
   pl.bytes = off;
@@ -72,7 +74,7 @@ int svf_sparse_ffn(const svf_ffn_shape_t* shape, const void* x, const void* w_ga
   p.active = active_or_null;
   char* w = static_cast<char*>(ws);
   p.h_up = w + pl.off_h_up;
-  p.rowmask = reinterpret_cast<uint32_t*>(w + pl.off_rowmask);
+  p.rowany = reinterpret_cast<uint8_t*>(w + pl.off_rowmask);
   p.partial = reinterpret_cast<float*>(w + pl.off_partial);
   p.M = shape->M;
   p.d_model = shape->d_model;
@@ -80,6 +82,8 @@ int svf_sparse_ffn(const svf_ffn_shape_t* shape, const void* x, const void* w_ga
   p.act = shape->act;
   p.k_splits = pl.k_splits;
   p.tau = shape->tau;
+  p.fused_walk = shape->walk != SVF_FFN_WALK_GATE_FIRST;
+  p.tile_rows = svf::ffn_fused_tile_rows(shape->d_ff);
   return svf::launch_sparse_ffn(p, static_cast<hipStream_t>(stream)) == hipSuccess ? SVF_OK : SVF_ERR_HIP;
 }
 

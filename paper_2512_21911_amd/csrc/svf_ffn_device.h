@@ -20,14 +20,17 @@ struct FfnParams {
   void* y;                  // bf16 [M][d_model]
   uint64_t* active;         // [d_ff] or NULL
   void* h_up;               // bf16 [64][d_ff]: h * up per token, zero where the token does not use the channel
-  uint32_t* rowmask;        // [d_ff / 32]: bit r = channel 32 tile + r is used by some token
+  uint8_t* rowany;          // [d_ff]: nonzero = the channel is used by some token
   float* partial;           // fp32 [k_splits][M][d_model]
   int32_t M, d_model, d_ff, act, k_splits;
+  int32_t fused_walk;       // gate and up matrices walked together (every row of W_up is read)
+  int32_t tile_rows;        // channels per tile of the fused walk (<= 32)
   float tau;
 };
 
 // Slices of the hidden dimension the down projection is cut into (partial sums in the workspace).
 int ffn_k_splits(int d_model, int d_ff);
+int ffn_fused_tile_rows(int d_ff);
 hipError_t launch_sparse_ffn(const FfnParams& p, hipStream_t st);
 
 }  // namespace svf

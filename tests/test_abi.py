@@ -193,7 +193,7 @@ def test_sparse_ffn_validates_before_launching():
     def call(shape=sh, x=ok, y=ok, ws=ok, ws_bytes=need, b=null, active=null):
         return L.svf_sparse_ffn(ctypes.byref(shape), x, ok, ok, ok, b, null, null, y, active, ws, ws_bytes, None)
 
-    for bad in (dict(M=0), dict(M=65), dict(d_model=192), dict(d_model=0), dict(d_ff=48), dict(d_ff=0), dict(act=2),
+    for bad in (dict(M=0), dict(M=65), dict(d_model=192), dict(d_model=0), dict(d_ff=48), dict(d_ff=0), dict(act=2), dict(walk=3), dict(walk=-1),
                 dict(tau=-0.1), dict(tau=float("nan")), dict(tau=float("inf"))):
         kw = dict(M=8, d_model=256, d_ff=64, act="silu", tau=0.05)
         kw.update(bad)

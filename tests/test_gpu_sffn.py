@@ -18,9 +18,12 @@ from workloads import ffn as WF
 pytestmark = pytest.mark.gpu
 
 
-def run_gpu(cfg, w, tau=None):
+WALKS = {"together": S.SVF_FFN_WALK_TOGETHER, "gate_first": S.SVF_FFN_WALK_GATE_FIRST}
+
+
+def run_gpu(cfg, w, tau=None, walk=S.SVF_FFN_WALK_AUTO):
     tau = cfg.tau if tau is None else tau
-    shape = S.make_ffn_shape(M=cfg.M, d_model=cfg.d_model, d_ff=cfg.d_ff, act=cfg.act, tau=tau)
+    shape = S.make_ffn_shape(M=cfg.M, d_model=cfg.d_model, d_ff=cfg.d_ff, act=cfg.act, tau=tau, walk=walk)
     g = {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in w.items()}
     y = torch.full((cfg.M, cfg.d_model), float("nan"), device="cuda", dtype=torch.bfloat16)
     active = torch.full((cfg.d_ff,), -1, device="cuda", dtype=torch.int64)
@@ -35,9 +38,9 @@ def run_gpu(cfg, w, tau=None):
     return y.double().cpu().numpy(), act
 
 
-def check(cfg, w, tau=None, tokens=None):
+def check(cfg, w, tau=None, tokens=None, walk=S.SVF_FFN_WALK_AUTO):
     tau = cfg.tau if tau is None else tau
-    y, act = run_gpu(cfg, w, tau)
+    y, act = run_gpu(cfg, w, tau, walk)
     toks = list(range(cfg.M)) if tokens is None else tokens
     sub = dict(w)
     sub["x"] = w["x"][toks]
@@ -54,66 +57,75 @@ def check(cfg, w, tau=None, tokens=None):
     assert np.isfinite(y).all()
     worst = float((err / (2.0 ** -7 * 1.05 * A + 1e-6)).max())
     assert worst <= 1.0, f"output error {worst:.2f} x the derived bound"
-    print(f"[sffn] {cfg.name} M={cfg.M} tau={tau}: active {act[toks].mean():.3f}, rows read "
+    print(f"[sffn] {cfg.name} walk={walk} M={cfg.M} tau={tau}: active {act[toks].mean():.3f}, rows read "
           f"{act.any(axis=0).mean():.3f}, flips {int(flips.sum())}, error {worst:.2f} of the bound", flush=True)
     return y, act
 
 
+@pytest.mark.parametrize("walk", sorted(WALKS))
 @pytest.mark.parametrize("act", ["silu", "gelu"])
-def test_tiny_with_biases(act):
+def test_tiny_with_biases(act, walk):
     cfg = WF.FFN_CONFIGS[1].scaled(act=act)
-    check(cfg, WF.make_ffn(cfg))
+    check(cfg, WF.make_ffn(cfg), walk=WALKS[walk])
 
 
+@pytest.mark.parametrize("walk", sorted(WALKS))
 @pytest.mark.parametrize("tau", [0.0, 0.01, 0.05, 0.1])
-def test_expert_shape_at_the_papers_thresholds(tau):
+def test_expert_shape_at_the_papers_thresholds(tau, walk):
     cfg = WF.FFN_CONFIGS[2]
     w = WF.make_ffn(cfg)
-    y, act = check(cfg, w, tau)
+    y, act = check(cfg, w, tau, walk=WALKS[walk])
     if tau == 0.0:                                        # Eq. 10-11: the dense layer
         assert act.all()
         dense = FO.dense_ffn(w["x"], w["w_gate"], w["w_up"], w["w_down_t"], act=cfg.act)
         assert np.abs(y - dense).max() <= 2e-2 * max(1.0, np.abs(dense).max())
 
 
+@pytest.mark.parametrize("walk", sorted(WALKS))
 @pytest.mark.parametrize("M", [1, 31, 32, 33, 60, 64])
-def test_token_counts(M):
+def test_token_counts(M, walk):
     cfg = WF.FFN_CONFIGS[2].scaled(M=M, d_model=512, d_ff=352, bias=True)
-    check(cfg, WF.make_ffn(cfg))
+    check(cfg, WF.make_ffn(cfg), walk=WALKS[walk])
 
 
-@pytest.mark.parametrize("d_model,d_ff", [(128, 32), (384, 96), (640, 2080), (1024, 32)])
-def test_ragged_splits(d_model, d_ff):
+@pytest.mark.parametrize("walk", sorted(WALKS))
+@pytest.mark.parametrize("d_model,d_ff", [(128, 32), (384, 96), (640, 2080), (1024, 32), (256, 7200)])
+def test_ragged_splits(d_model, d_ff, walk):
     """Fewer chunks than wavefronts, chunk counts that do not divide by four, one tile, hidden sizes that
-    leave wavefronts of the down projection without a step."""
+    leave wavefronts of the down projection without a step, a hidden size whose tiles of the joint walk
+    are cut below 32 channels with a shorter last tile."""
     cfg = WF.FFN_CONFIGS[1].scaled(M=5, d_model=d_model, d_ff=d_ff)
-    check(cfg, WF.make_ffn(cfg))
+    check(cfg, WF.make_ffn(cfg), walk=WALKS[walk])
 
 
-def test_everything_inactive_leaves_the_bias():
+@pytest.mark.parametrize("walk", sorted(WALKS))
+def test_everything_inactive_leaves_the_bias(walk):
     cfg = WF.FFN_CONFIGS[1].scaled(M=4, d_model=256, d_ff=128)
     w = WF.make_ffn(cfg)
-    y, act = check(cfg, w, tau=1e6)
+    y, act = check(cfg, w, tau=1e6, walk=WALKS[walk])
     assert not act.any()
     want = w["b_down"].to(torch.bfloat16).double().numpy()
     assert np.array_equal(y, np.broadcast_to(want, y.shape))
 
 
-def test_dense_8b_full_size():
+@pytest.mark.parametrize("walk", sorted(WALKS))
+def test_dense_8b_full_size(walk):
     """The benchmark's shape; the oracle checks every token."""
     cfg = WF.FFN_CONFIGS[3]
-    check(cfg, WF.make_ffn(cfg))
+    check(cfg, WF.make_ffn(cfg), walk=WALKS[walk])
 
 
-def test_dense_8b_tree_full_size_sampled_tokens():
+@pytest.mark.parametrize("walk", sorted(WALKS))
+def test_dense_8b_tree_full_size_sampled_tokens(walk):
     cfg = WF.FFN_CONFIGS[4]
-    check(cfg, WF.make_ffn(cfg), tokens=[0, 31, 32, 59])
+    check(cfg, WF.make_ffn(cfg), tokens=[0, 31, 32, 59], walk=WALKS[walk])
 
 
-def test_same_bits_on_repeated_calls():
+@pytest.mark.parametrize("walk", sorted(WALKS))
+def test_same_bits_on_repeated_calls(walk):
     cfg = WF.FFN_CONFIGS[2]
     w = WF.make_ffn(cfg)
-    y0, a0 = run_gpu(cfg, w)
+    y0, a0 = run_gpu(cfg, w, walk=WALKS[walk])
     for _ in range(3):
-        y1, a1 = run_gpu(cfg, w)
+        y1, a1 = run_gpu(cfg, w, walk=WALKS[walk])
         assert np.array_equal(y0, y1) and np.array_equal(a0, a1)
