@@ -330,6 +330,24 @@ def sffn(args):
         torch.cuda.synchronize()
         return a.elapsed_time(b) / iters * 1e3 / n_rep    # us per layer
 
+    if args.profile_only:
+        # for the profiler's byte counters: a few calls at tau = 0.05 (default walk), then plain copies of
+        # known size to scale the counters with
+        shape = S.make_ffn_shape(M=cfg.M, d_model=cfg.d_model, d_ff=cfg.d_ff, act=cfg.act, tau=0.05)
+        ws = S.new_ffn_workspace(shape)
+        for _ in range(int(args.profile_only)):
+            for w in layers:
+                S.svf_sparse_ffn(shape, w["x"], w["w_gate"], w["w_up"], w["w_down_t"], y, ws)
+        torch.cuda.synchronize()
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"profile_only_steps": int(args.profile_only), "workload": cfg.name,
+                          "calibration_copy_bytes": 256 << 20}))
+        return
+
     row = cfg.d_model * 2
     table = {}
     for walk, tau in [(S.SVF_FFN_WALK_AUTO, t) for t in (0.0, 0.01, 0.05, 0.1)] + \
@@ -379,7 +397,9 @@ def sffn(args):
                    "tau": 0.05, "launch": "stream"},
         "roofline": {"bound": "hbm", "kernel": "ffn_gate_up_fused_kernel + ffn_down_kernel + ffn_reduce_kernel",
                      "achieved": head["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(head["GBps"] / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(head["GBps"] / HBM_PEAK_GBPS, 4),
+                     # FETCH_SIZE + WRITE_SIZE of the three kernels, scaled (profiles/sparse_ffn_dense8b_hbm_traffic.md)
+                     "traffic": 339.5e6 if cfg.name == "ffn3_dense_8b" else None,
                      "algorithmic_bytes_per_launch": head["algorithmic_bytes"], "avg_launch_us": head["us_per_layer"]},
         "cpu_baseline": {"value": round(wall * 1e6 * cfg.M / len(toks), 1), "unit": "us/layer",
                          "cores": max(1, int(round(cpu_t / max(wall, 1e-9)))), "kind": "oracle",
