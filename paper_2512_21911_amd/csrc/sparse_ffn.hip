@@ -87,9 +87,10 @@ __device__ __forceinline__ float activate(float z, int act) {
 //   w_rows[mat]: address of row 0 of the tile in matrix mat; row_of(r): which tile row to read
 //   for row r (a row nobody needs is redirected, its products are thrown away); stage: the
 //   wavefront's two LDS stages of NMAT chunks each.
+//   The workgroup's n_waves wavefronts take the chunks wave, wave + n_waves, ...
 template <int NT, int NMAT, typename RowOf>
 __device__ __forceinline__ void walk_tile(const FfnParams& p, const char* const (&w_rows)[NMAT], RowOf row_of,
-                                          const char* x, unsigned char* stage, int wave, int lane,
+                                          const char* x, unsigned char* stage, int wave, int n_waves, int lane,
                                           floatx16 (&acc)[NMAT][NT]) {
   constexpr int kStageBytes = NMAT * kChunkBytes;
   const int l32 = lane & 31, g = lane >> 5;
@@ -144,7 +145,7 @@ __device__ __forceinline__ void walk_tile(const FfnParams& p, const char* const 
     }
   };
 
-  // Chunks wave, wave + 4, ...  The weight chunk after this one is on its way into the other
+  // The weight chunk after this one is on its way into the other
   // stage while this one is multiplied; the x pieces of the next chunk are loaded right after
   // the multiply (one register set), long before that chunk's weights can have arrived.  Loads
   // retire in order, so "all but the 8 NMAT just issued" is one fixed wait count.
@@ -154,7 +155,7 @@ __device__ __forceinline__ void walk_tile(const FfnParams& p, const char* const 
   load_x(kc);
   int cur = 0;
   while (true) {
-    const int kn = kc + kGuWaves;
+    const int kn = kc + n_waves;
     if (kn >= n_chunks) {
       wait_vmcnt<0>();
       compute(stage + cur * kStageBytes);
@@ -211,7 +212,7 @@ __global__ __launch_bounds__(kGuThreads) void ffn_gate_up_kernel(FfnParams p) {
     for (int v = 0; v < 16; ++v) acc[0][t][v] = 0.f;
   {
     const char* const rows[1] = {static_cast<const char*>(p.w_gate) + (int64_t)c0 * row_bytes};
-    walk_tile<NT, 1>(p, rows, [](int r) { return r; }, x, stage, wave, lane, acc);
+    walk_tile<NT, 1>(p, rows, [](int r) { return r; }, x, stage, wave, kGuWaves, lane, acc);
   }
   put_partial(acc[0]);
   __syncthreads();
@@ -261,7 +262,8 @@ __global__ __launch_bounds__(kGuThreads) void ffn_gate_up_kernel(FfnParams p) {
     for (int v = 0; v < 16; ++v) acc[0][t][v] = 0.f;
   {
     const char* const rows[1] = {static_cast<const char*>(p.w_up) + (int64_t)c0 * row_bytes};
-    walk_tile<NT, 1>(p, rows, [=](int r) { return ((rowmask >> r) & 1u) ? r : first; }, x, stage, wave, lane, acc);
+    walk_tile<NT, 1>(p, rows, [=](int r) { return ((rowmask >> r) & 1u) ? r : first; }, x, stage, wave, kGuWaves, lane,
+                     acc);
   }
   put_partial(acc[0]);
   __syncthreads();
@@ -284,80 +286,97 @@ __global__ __launch_bounds__(kGuThreads) void ffn_gate_up_kernel(FfnParams p) {
 
 // The same result with the gate and the up matrix walked together: x is fetched once per chunk for
 // both, and the workgroup's memory pipeline does not run dry between a gate and an up walk; the
-// price is that every row of W_up is read, needed or not.  One workgroup per compute unit (128 KB
-// of stages), so the tiles are cut to p.tile_rows <= 32 channels such that the tile count fills
-// whole rounds of workgroups; the rows of the 32-row matrix-core tile past that repeat the last one.
-// grid: (ceil(d_ff / tile_rows)); block: 256
-template <int NT>
-__global__ __launch_bounds__(kGuThreads) void ffn_gate_up_fused_kernel(FfnParams p) {
+// price is that every row of W_up is read, needed or not.
+//   TILES channel tiles per workgroup share the x pieces as well (TILES = 2 for more than 32
+//   tokens, where fetching x costs as much as fetching the weights), WAVES wavefronts split the
+//   model dimension; TILES * WAVES = 4, 128 KB of stages, one workgroup per compute unit.  So
+//   the tile height p.tile_rows <= 32 is chosen such that the workgroups fill whole rounds; the
+//   rows of the 32-row matrix-core tile past it repeat its last row, and a tile that would
+//   reach past d_ff is moved back to end there (the channels it shares with its neighbour are
+//   computed twice, to the same bits).
+// grid: (ceil(ceil(d_ff / tile_rows) / TILES)); block: 64 WAVES
+template <int NT, int TILES, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void ffn_gate_up_fused_kernel(FfnParams p) {
   constexpr int RS = 32 * NT + 1;
-  constexpr int kWaveBytes = kStages * 2 * kChunkBytes;  // a wavefront's two stages of two chunks
-  __shared__ __attribute__((aligned(1024))) unsigned char smem[kGuWaves * kWaveBytes];
-  static_assert(2 * kTileRows * RS * 4 <= kWaveBytes, "a wavefront's two partial tiles fit its own stages");
+  constexpr int NMAT = 2 * TILES;                        // gate tiles, then up tiles
+  constexpr int kWaveBytes = kStages * NMAT * kChunkBytes;
+  constexpr int kThreads = WAVES * 64;
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[WAVES * kWaveBytes];
+  static_assert(NMAT * kTileRows * RS * 4 <= kWaveBytes, "a wavefront's partial tiles fit its own stages");
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
   const int l32 = lane & 31, g = lane >> 5;
-  const int c0 = blockIdx.x * p.tile_rows;
-  const int rows_here = min(p.tile_rows, p.d_ff - c0);
+  const int R = p.tile_rows;
+  int c0[TILES];
+#pragma unroll
+  for (int s = 0; s < TILES; ++s) c0[s] = min((blockIdx.x * TILES + s) * R, p.d_ff - R);
   unsigned char* stage = smem + wave * kWaveBytes;
   const int64_t row_bytes = (int64_t)p.d_model * 2;
 
-  floatx16 acc[2][NT];
+  floatx16 acc[NMAT][NT];
 #pragma unroll
-  for (int mat = 0; mat < 2; ++mat)
+  for (int mat = 0; mat < NMAT; ++mat)
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mat][t][v] = 0.f;
   {
-    const char* const rows[2] = {static_cast<const char*>(p.w_gate) + (int64_t)c0 * row_bytes,
-                                 static_cast<const char*>(p.w_up) + (int64_t)c0 * row_bytes};
-    walk_tile<NT, 2>(p, rows, [=](int r) { return min(r, rows_here - 1); }, static_cast<const char*>(p.x), stage, wave,
-                     lane, acc);
+    const char* rows[NMAT];
+#pragma unroll
+    for (int s = 0; s < TILES; ++s) {
+      rows[s] = static_cast<const char*>(p.w_gate) + (int64_t)c0[s] * row_bytes;
+      rows[TILES + s] = static_cast<const char*>(p.w_up) + (int64_t)c0[s] * row_bytes;
+    }
+    const char* const(&crows)[NMAT] = rows;
+    walk_tile<NT, NMAT>(p, crows, [=](int r) { return min(r, R - 1); }, static_cast<const char*>(p.x), stage, wave,
+                        WAVES, lane, acc);
   }
   // partial tiles [matrix][channel][token] into this wavefront's own stages
   float* red = reinterpret_cast<float*>(stage);
 #pragma unroll
-  for (int mat = 0; mat < 2; ++mat)
+  for (int mat = 0; mat < NMAT; ++mat)
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v)
         red[(mat * kTileRows + 8 * (v >> 2) + 4 * g + (v & 3)) * RS + l32 + 32 * t] = acc[mat][t][v];
   __syncthreads();
-  // thread: channel tid / 8, tokens (tid % 8) * 4 NT ... + 4 NT
-  const int c = tid >> 3, m0 = (tid & 7) * 4 * NT;
-  if (c >= rows_here) return;
-  const float bg = p.b_gate ? p.b_gate[c0 + c] : 0.f;
-  const float bu = p.b_up ? p.b_up[c0 + c] : 0.f;
-  uint64_t bits = 0;
+  // thread: tile row tid / 8 (+ 8 WAVES per round), tokens (tid % 8) * 4 NT ... + 4 NT
+  const int m0 = (tid & 7) * 4 * NT;
+  for (int cc = tid >> 3; cc < TILES * kTileRows; cc += kThreads / 8) {
+    const int s = cc / kTileRows, c = cc - s * kTileRows;
+    if (c >= R) continue;                                 // (the eight threads of a row go together)
+    const int ch = c0[s] + c;
+    const float bg = p.b_gate ? p.b_gate[ch] : 0.f;
+    const float bu = p.b_up ? p.b_up[ch] : 0.f;
+    uint64_t bits = 0;
 #pragma unroll
-  for (int i = 0; i < 4 * NT; ++i) {
-    const int m = m0 + i;
-    float zg = 0.f, zu = 0.f;
+    for (int i = 0; i < 4 * NT; ++i) {
+      const int m = m0 + i;
+      float zg = 0.f, zu = 0.f;
 #pragma unroll
-    for (int w = 0; w < kGuWaves; ++w) {
-      const float* r = reinterpret_cast<const float*>(smem + w * kWaveBytes);
-      zg += r[c * RS + m];
-      zu += r[(kTileRows + c) * RS + m];
+      for (int w = 0; w < WAVES; ++w) {
+        const float* r = reinterpret_cast<const float*>(smem + w * kWaveBytes);
+        zg += r[(s * kTileRows + c) * RS + m];
+        zu += r[((TILES + s) * kTileRows + c) * RS + m];
+      }
+      const float h = activate(zg + bg, p.act);
+      const bool on = m < p.M && !(fabsf(h) < p.tau);
+      if (on) bits |= 1ull << m;
+      const float hu = on ? h * (zu + bu) : 0.f;
+      reinterpret_cast<__hip_bfloat16*>(p.h_up)[(int64_t)m * p.d_ff + ch] = __float2bfloat16(hu);
     }
-    const float h = activate(zg + bg, p.act);
-    const bool on = m < p.M && !(fabsf(h) < p.tau);
-    if (on) bits |= 1ull << m;
-    const float hu = on ? h * (zu + bu) : 0.f;
-    reinterpret_cast<__hip_bfloat16*>(p.h_up)[(int64_t)m * p.d_ff + c0 + c] = __float2bfloat16(hu);
-  }
-  // the eight threads of a channel are neighbours in a wavefront (and leave together)
 #pragma unroll
-  for (int o = 1; o < 8; o <<= 1) {
-    const uint32_t lo = __shfl_xor((uint32_t)bits, o, 64), hi = __shfl_xor((uint32_t)(bits >> 32), o, 64);
-    bits |= (uint64_t)lo | ((uint64_t)hi << 32);
-  }
-  if ((tid & 7) == 0) {
-    p.rowany[c0 + c] = bits != 0 ? 1 : 0;
-    if (p.active) p.active[c0 + c] = bits;
+    for (int o = 1; o < 8; o <<= 1) {
+      const uint32_t lo = __shfl_xor((uint32_t)bits, o, 64), hi = __shfl_xor((uint32_t)(bits >> 32), o, 64);
+      bits |= (uint64_t)lo | ((uint64_t)hi << 32);
+    }
+    if ((tid & 7) == 0) {
+      p.rowany[ch] = bits != 0 ? 1 : 0;
+      if (p.active) p.active[ch] = bits;
+    }
   }
 }
 
@@ -516,12 +535,13 @@ __global__ __launch_bounds__(256) void ffn_reduce_kernel(FfnParams p) {
 // Channels per tile of the fused walk: one workgroup per compute unit runs at a time, so the
 // cost is (rounds of 256 workgroups) x (rows per tile); the largest multiple of four that
 // minimises it.
-int ffn_fused_tile_rows(int d_ff) {
+int ffn_fused_tile_rows(int d_ff, int M) {
+  const int per_wg = M <= 32 ? 1 : 2;                     // channel tiles per workgroup
   int best = kTileRows;
   int64_t best_cost = -1;
   for (int r = kTileRows; r >= 16; r -= 4) {
-    const int64_t tiles = (d_ff + r - 1) / r;
-    const int64_t cost = ((tiles + 255) / 256) * r;
+    const int64_t wgs = ((d_ff + r - 1) / r + per_wg - 1) / per_wg;
+    const int64_t cost = ((wgs + 255) / 256) * r;
     if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = r; }
   }
   return best;
@@ -538,9 +558,9 @@ int ffn_k_splits(int d_model, int d_ff) {
 hipError_t launch_sparse_ffn(const FfnParams& p, hipStream_t st) {
   const dim3 gu(p.d_ff / kTileRows);
   if (p.fused_walk) {
-    const dim3 gf((p.d_ff + p.tile_rows - 1) / p.tile_rows);
-    if (p.M <= 32) hipLaunchKernelGGL(ffn_gate_up_fused_kernel<1>, gf, dim3(kGuThreads), 0, st, p);
-    else hipLaunchKernelGGL(ffn_gate_up_fused_kernel<2>, gf, dim3(kGuThreads), 0, st, p);
+    const int tiles = (p.d_ff + p.tile_rows - 1) / p.tile_rows;
+    if (p.M <= 32) hipLaunchKernelGGL((ffn_gate_up_fused_kernel<1, 1, 4>), dim3(tiles), dim3(256), 0, st, p);
+    else hipLaunchKernelGGL((ffn_gate_up_fused_kernel<2, 2, 2>), dim3((tiles + 1) / 2), dim3(128), 0, st, p);
   } else {
     if (p.M <= 32) hipLaunchKernelGGL(ffn_gate_up_kernel<1>, gu, dim3(kGuThreads), 0, st, p);
     else hipLaunchKernelGGL(ffn_gate_up_kernel<2>, gu, dim3(kGuThreads), 0, st, p);

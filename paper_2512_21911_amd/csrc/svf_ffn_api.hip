@@ -83,7 +83,7 @@ int svf_sparse_ffn(const svf_ffn_shape_t* shape, const void* x, const void* w_ga
   p.k_splits = pl.k_splits;
   p.tau = shape->tau;
   p.fused_walk = shape->walk != SVF_FFN_WALK_GATE_FIRST;
-  p.tile_rows = svf::ffn_fused_tile_rows(shape->d_ff);
+  p.tile_rows = svf::ffn_fused_tile_rows(shape->d_ff, shape->M);
   return svf::launch_sparse_ffn(p, static_cast<hipStream_t>(stream)) == hipSuccess ? SVF_OK : SVF_ERR_HIP;
 }
 

@@ -30,7 +30,7 @@ struct FfnParams {
 
 // Slices of the hidden dimension the down projection is cut into (partial sums in the workspace).
 int ffn_k_splits(int d_model, int d_ff);
-int ffn_fused_tile_rows(int d_ff);
+int ffn_fused_tile_rows(int d_ff, int M);
 hipError_t launch_sparse_ffn(const FfnParams& p, hipStream_t st);
 
 }  // namespace svf
