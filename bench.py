@@ -592,7 +592,7 @@ def main():
                 one_layer(l, S.SVF_STEP_ANCHOR)
 
     def select_only():
-        """Stand-alone block scores + selection (the two-kernel path svf_score_select exposes)."""
+        """Stand-alone block selection (svf_score_select without the scores output: one launch)."""
         for l, x in enumerate(layers):
             if cfg.is_anchor(l):
                 S.svf_score_select(shape, x["q"], reps[l], x["seq_lens"], sel_idx, sel_cnt, ws)

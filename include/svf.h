@@ -125,6 +125,7 @@ int svf_block_reps(const svf_shape_t* shape, const void* K, const int32_t* block
  *   kept blocks  = first n_sink and last n_local blocks, then the highest scores until
  *                  min(k_blocks, nb_b) blocks are kept; equal scores: lowest block id first.
  * Writes sel_idx (ascending, -1 padded), sel_cnt and, if scores_or_null is given, s.
+ * (Without the scores, shapes with a gather list take a single launch; the blocks are the same.)
  */
 int svf_score_select(const svf_shape_t* shape, const void* q, const float* reps,
                      const int32_t* seq_lens, int32_t* sel_idx, int32_t* sel_cnt,

@@ -12,6 +12,7 @@ namespace svf {
 
 hipError_t launch_verify_attn_valu(const AttnParams& p, int dtype, hipStream_t st);
 hipError_t launch_verify_attn_mfma(const AttnParams& p, hipStream_t st);
+hipError_t launch_retrieve_only(const AttnParams& p, hipStream_t st);
 bool mfma_supported(const svf_shape_t& s);
 int mfma_splits(const svf_shape_t& s);
 bool mfma_rows_mode(const svf_shape_t& s);
@@ -248,6 +249,45 @@ static int score_select_impl(const svf_shape_t* shape, const void* q, const floa
   if (misaligned(q) || misaligned(reps)) return SVF_ERR_SHAPE;
   rc = check_ws(shape, ws, ws_bytes);
   if (rc) return rc;
+  {
+    // Shapes the retrieving attention kernel handles, when neither the scores nor a gather list
+    // are asked for: its retrieval alone, one launch (the workgroups of a (sequence, KV head)
+    // share the scoring), the same blocks bit for bit.
+    const AttnPlan pl = plan_attn(*shape);
+    if (pl.fused_select && !scores_or_null && !with_gather) {
+      char* w = static_cast<char*>(ws);
+      AttnParams a{};
+      a.kv = layout_of(*shape);
+      a.kv.page_size = 0;                                 // no page table in this call
+      a.q = q;
+      a.seq_lens = seq_lens;
+      a.reps = reps;
+      a.sel_idx_out = sel_idx;
+      a.sel_cnt_out = sel_cnt;
+      a.tickets = reinterpret_cast<uint64_t*>(w + pl.off_tickets);
+      a.xkeys = reinterpret_cast<uint64_t*>(w + pl.off_xkeys);
+      a.epochs = reinterpret_cast<uint32_t*>(w + pl.off_epochs);
+      a.poll_budget = g_exchange_polls.load(std::memory_order_relaxed);
+      a.nb_max = nb_max_of(*shape);
+      a.n_sink = shape->n_sink;
+      a.n_local = shape->n_local;
+      a.B = shape->B;
+      a.gamma = shape->gamma;
+      a.Hq = shape->Hq;
+      a.Hkv = shape->Hkv;
+      a.G = shape->Hq / shape->Hkv;
+      a.d = shape->d;
+      a.M = pl.M;
+      a.Mpad = pl.Mpad;
+      a.block_size = shape->block_size;
+      a.k_blocks = shape->k_blocks;
+      a.n_splits = pl.n_splits;
+      a.max_seq_len = shape->max_seq_len;
+      a.g_magic = (1ull << 32) / (uint64_t)a.G + 1ull;
+      a.hkv_magic = (1ull << 32) / (uint64_t)a.Hkv + 1ull;
+      return hip_code(launch_retrieve_only(a, static_cast<hipStream_t>(stream)));
+    }
+  }
   SelectParams p;
   p.q = q;
   p.reps = reps;

@@ -1377,6 +1377,53 @@ int mfma_rows_splits(const svf_shape_t& s) {
   return (int)want;
 }
 
+// The retrieval of kSelect without the attention behind it (the stand-alone block selection of a
+// shape the retrieving attention kernel handles): the workgroups of a (sequence, KV head) share
+// the scoring through the key exchange, the last split publishes the kept blocks, and the
+// workgroup that finishes last moves the group's tag on.  No page table is touched (p.kv.page_size
+// must be 0 here) and no gather list is written.
+// grid: x = kXcds * n_splits, y = ceil(pairs / kXcds)
+__global__ __launch_bounds__(kThreads) void retrieve_only_kernel(AttnParams p, int pairs) {
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[kStageBytes];
+  __shared__ int32_t s_sel[kMaxSelectBlocks];
+  __shared__ int s_exchange_failed;
+  {
+    const __attribute__((address_space(4))) uint32_t* ka =
+        (const __attribute__((address_space(4))) uint32_t*)__builtin_amdgcn_kernarg_segment_ptr();
+    const uint32_t w0 = ka[0], w1 = ka[16], w2 = ka[32], w3 = ka[48], w4 = ka[64], w5 = ka[80];
+    asm volatile("" : : "s"(w0), "s"(w1), "s"(w2), "s"(w3), "s"(w4), "s"(w5));
+  }
+  int vzero;
+  asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
+  const int split = blockIdx.x / kXcds;
+  const int pair = blockIdx.y * kXcds + blockIdx.x % kXcds;
+  if (pair >= pairs) return;
+  const int b = (int)(((uint64_t)(uint32_t)pair * p.hkv_magic) >> 32), h = pair - b * p.Hkv;
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
+  RetrievalLoads rl = issue_retrieval_loads(p, b, h, pair, split, pair, split % kScoreBatch, tid, vzero);
+  const int L = clamped_len(p.seq_lens, b + vzero, p.max_seq_len);
+  issue_first_score_batch(p, rl, pair, split, tid);
+  const Retrieved rt = retrieve_blocks(p, rl, smem, s_sel, &s_exchange_failed, L, pair, split, pair, tid, lane, wave);
+  if (split == p.n_splits - 1) publish_selection(p, s_sel, rt.cnt, pair, tid);
+  if (rl.share_scores && tid == 0) {
+    // every workgroup that takes a ticket has read all the keys it needed
+    const uint64_t prev = __hip_atomic_fetch_add(&p.tickets[pair], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (prev == (uint64_t)(p.n_splits - 1)) {
+      __hip_atomic_store(&p.tickets[pair], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      p.epochs[pair] = rt.tag;
+    }
+  }
+}
+
+hipError_t launch_retrieve_only(const AttnParams& p, hipStream_t st) {
+  const int pairs = p.B * p.Hkv;
+  const dim3 grid((unsigned)(kXcds * p.n_splits), (unsigned)((pairs + kXcds - 1) / kXcds));
+  hipLaunchKernelGGL(retrieve_only_kernel, grid, dim3(kThreads), 0, st, p, pairs);
+  return hipGetLastError();
+}
+
 hipError_t launch_verify_attn_mfma(const AttnParams& p, hipStream_t st) {
   const int row_groups = (p.M + 31) / 32;
   const int pairs = p.B * p.Hkv;

@@ -315,3 +315,31 @@ def test_anchor_retrieval_same_bits_with_and_without_key_exchange(cfg_id, T):
 def test_budget_helper_matches_oracle():
     for L, L0, rho, bs in [(32768, 4096, 0.1, 64), (4096, 4096, 0.1, 64), (131072, 1024, 0.1, 128), (777, 100, 0.5, 7)]:
         assert S.svf_budget_blocks(L, L0, rho, bs) == O.budget_blocks(L, L0, rho, bs)
+
+
+@pytest.mark.parametrize("cfg_id,T", [(3, 4096), (3, 32768), (5, 8192), (2, 8192)])
+def test_selection_without_scores_takes_one_launch_and_the_same_blocks(cfg_id, T):
+    """svf_score_select without the scores output runs the retrieving attention kernel's retrieval alone
+    (one launch, key exchange between the workgroups of a pair): same blocks as the two-kernel path, call
+    after call, also interleaved with anchor steps on the same workspace (they share the exchange tags)."""
+    cfg = W.shrink(W.CONFIGS[cfg_id], T) if T < W.CONFIGS[cfg_id].T else W.CONFIGS[cfg_id]
+    x = W.make_layer(cfg)
+    run = DeviceRun(cfg, to_gpu(x), poison=False)
+    run.block_reps().score_select(with_scores=True).sync()
+    idx0, cnt0 = run.sel_idx.clone(), run.sel_cnt.clone()
+    check_selection(cfg, x, O.block_scores(x["q"], O.block_reps(x["k_pool"], x["block_table"], x["seq_lens"],
+                                                                 cfg.block_size, cfg.nb_max)),
+                    idx0, cnt0, cfg.n_sink, cfg.n_local)
+    try:
+        for polls in (64, 0, 1):
+            S.svf_set_exchange_polls(polls)
+            for i in range(12):
+                run.sel_idx.fill_(-7)
+                run.sel_cnt.fill_(-7)
+                run.score_select(with_scores=False)
+                if i % 4 == 3:
+                    run.verify_step(S.SVF_STEP_ANCHOR)
+                run.sync()
+                assert torch.equal(run.sel_idx, idx0) and torch.equal(run.sel_cnt, cnt0), f"polls={polls} call {i}"
+    finally:
+        S.svf_set_exchange_polls(64)
