@@ -23,8 +23,8 @@
 //                   operand contiguous along the reduction; each lane therefore loads four
 //                   output columns of eight channels and byte-permutes them into operands
 //                   (row i of sub-product nt = output column 4 i + nt).  Rows of channels
-//                   nobody needs are skipped.  Wavefront results are added in a fixed order
-//                   through LDS; the slices' partial sums are added, with b_down, by a third
+//                   nobody needs are skipped.  Wavefront results are added in wavefront order
+//                   through LDS (one barrier); the slices' partial sums are added, with b_down, by a third
 //                   small kernel (fixed order: the result does not depend on scheduling).
 #include <hip/hip_bf16.h>
 #include <hip/hip_runtime.h>
@@ -396,7 +396,8 @@ struct DownLoads {
 // grid: (d_model / 128, k_splits); block: 512
 template <int NT>
 __global__ __launch_bounds__(kDnThreads) void ffn_down_kernel(FfnParams p) {
-  __shared__ __attribute__((aligned(16))) float s_red[kDnWaves / 2][NT * 4 * 16 * 64];   // [slot][t][nt][v][lane]
+  constexpr int kRedStride = kDnCols + 4;                // floats per token row: keeps rows off each other's banks
+  __shared__ __attribute__((aligned(16))) float s_red[kDnWaves][32 * kRedStride];        // [wavefront][token][column]
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -471,42 +472,31 @@ __global__ __launch_bounds__(kDnThreads) void ffn_down_kernel(FfnParams p) {
     }
   }
 
-  // wavefronts 4..7 -> 0..3, 2..3 -> 0..1, 1 -> 0: a fixed order of additions
-  auto put = [&](int slot) {
+  // Every wavefront parks the rows of the real tokens (32 token columns at a time) in LDS; after
+  // one barrier the 512 threads add the eight wavefronts' values in wavefront order and write
+  // the slice's partial sums as whole rows.
+  // value v of a lane: output column n0 + 4 (8 (v / 4) + 4 g + v % 4) + nt, token l32 (+ 32 t)
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+  for (int t = 0; t < NT; ++t) {
+    if (t > 0) __syncthreads();                           // the round before has been read
+    if (l32 + 32 * t < p.M) {
+      float* row = &s_red[wave][l32 * kRedStride];
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s_red[slot][((t * 4 + nt) * 16 + v) * 64 + lane] = acc[t][nt][v];
-  };
-  auto take = [&](int slot) {
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-      for (int nt = 0; nt < 4; ++nt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[t][nt][v] += s_red[slot][((t * 4 + nt) * 16 + v) * 64 + lane];
-  };
-#pragma unroll
-  for (int half = kDnWaves / 2; half >= 1; half >>= 1) {
-    if (wave >= half && wave < 2 * half) put(wave - half);
+      for (int v = 0; v < 16; ++v)
+        *reinterpret_cast<float4*>(row + 4 * (8 * (v >> 2) + 4 * g + (v & 3))) =
+            make_float4(acc[t][0][v], acc[t][1][v], acc[t][2][v], acc[t][3][v]);
+    }
     __syncthreads();
-    if (wave < half) take(wave);
-    __syncthreads();
-  }
-  if (wave == 0) {
-    // value v of a lane: output column n0 + 4 (8 (v / 4) + 4 g + v % 4) + nt, token l32 (+ 32 t)
+    const int rows = min(p.M - 32 * t, 32);
+    for (int i = tid; i < rows * (kDnCols / 4); i += kDnThreads) {
+      const int m = i / (kDnCols / 4), c4 = i - m * (kDnCols / 4);
+      float4 sum = *reinterpret_cast<const float4*>(&s_red[0][m * kRedStride + 4 * c4]);
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      const int m = l32 + 32 * t;
-      if (m < p.M) {
-        float* dst = p.partial + ((int64_t)blockIdx.y * p.M + m) * p.d_model + n0;
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          *reinterpret_cast<float4*>(dst + 4 * (8 * (v >> 2) + 4 * g + (v & 3))) =
-              make_float4(acc[t][0][v], acc[t][1][v], acc[t][2][v], acc[t][3][v]);
+      for (int w = 1; w < kDnWaves; ++w) {
+        const float4 o = *reinterpret_cast<const float4*>(&s_red[w][m * kRedStride + 4 * c4]);
+        sum.x += o.x; sum.y += o.y; sum.z += o.z; sum.w += o.w;
       }
+      *reinterpret_cast<float4*>(p.partial + ((int64_t)blockIdx.y * p.M + 32 * t + m) * p.d_model + n0 + 4 * c4) = sum;
     }
   }
 }
