@@ -88,13 +88,15 @@ def test_token_counts(M, walk):
     check(cfg, WF.make_ffn(cfg), walk=WALKS[walk])
 
 
+@pytest.mark.parametrize("M", [5, 40])
 @pytest.mark.parametrize("walk", sorted(WALKS))
 @pytest.mark.parametrize("d_model,d_ff", [(128, 32), (384, 96), (640, 2080), (1024, 32), (256, 7200)])
-def test_ragged_splits(d_model, d_ff, walk):
+def test_ragged_splits(d_model, d_ff, walk, M):
     """Fewer chunks than wavefronts, chunk counts that do not divide by four, one tile, hidden sizes that
     leave wavefronts of the down projection without a step, a hidden size whose tiles of the joint walk
-    are cut below 32 channels with a shorter last tile."""
-    cfg = WF.FFN_CONFIGS[1].scaled(M=5, d_model=d_model, d_ff=d_ff)
+    are cut below 32 channels with a last tile moved back; with 40 tokens the joint walk takes two tiles
+    per workgroup (an odd tile count leaves the last workgroup a repeated tile)."""
+    cfg = WF.FFN_CONFIGS[1].scaled(M=M, d_model=d_model, d_ff=d_ff)
     check(cfg, WF.make_ffn(cfg), walk=WALKS[walk])
 
 
