@@ -8,8 +8,9 @@
 //   median        one workgroup per skip size: 4-pass radix select over the tokens' ratios
 //                 (positive floats order like their bit patterns), twice when T is even.
 //   accept        one workgroup per sequence: the gamma acceptance tests in one wavefront, then,
-//                 if a position was rejected, the residual mass per thread segment, a scan of the
-//                 segment sums, and a sequential walk of the one segment the target falls in.
+//                 if a position was rejected, the residual mass of every chunk of 256 consecutive
+//                 tokens (a wavefront reads a chunk as one contiguous kilobyte per distribution),
+//                 a scan of the chunk sums, and a walk of the one chunk the target falls in.
 #include <hip/hip_runtime.h>
 
 #include "svf.h"
