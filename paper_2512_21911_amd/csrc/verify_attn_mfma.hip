@@ -728,6 +728,17 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   if (MODE == kSelect)
     rl = issue_retrieval_loads(p, b, h, pair, split, group, (split + rg * p.n_splits) % kScoreBatch, tid, vzero);
   const int32_t* const table_row = p.table + (int64_t)b * p.kv.max_pages;
+  // With a gather list the tile loads wait for nothing but their gather entries: those (and the
+  // draft mask) go out ahead of the query fragments, which may then arrive while the tiles are
+  // on their way.  Lane 8u + n holds the entry of group n of the wavefront's u-th tile.
+  uint64_t rmask = 0;
+  if (MODE == kGather && p.draft_mask) rmask = p.draft_mask[p.mask_per_batch ? (int64_t)b * p.gamma + qi : qi];
+  uint64_t gent = 0;
+  if (MODE == kGather) {
+    const int tc = gw + (lane >> 3) * NW - tiles_d;          // cache tile index
+    const int e = tc * 8 + (lane & 7);
+    if (lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups) gent = p.gather[(int64_t)pair * p.gather_groups + e];
+  }
   bf16x8 qf[8];
   {
     const __hip_bfloat16* qrow = static_cast<const __hip_bfloat16*>(p.q) +
@@ -735,16 +746,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
   }
-  uint64_t rmask = 0;
-  if (p.draft_mask) rmask = p.draft_mask[p.mask_per_batch ? (int64_t)b * p.gamma + qi : qi];
+  if (MODE != kGather && p.draft_mask) rmask = p.draft_mask[p.mask_per_batch ? (int64_t)b * p.gamma + qi : qi];
 
-  // gather entries of this wavefront's tiles: lane 8u + n holds group n of its u-th tile
-  uint64_t gent = 0;
-  if (MODE == kGather) {
-    const int tc = gw + (lane >> 3) * NW - tiles_d;          // cache tile index
-    const int e = tc * 8 + (lane & 7);
-    if (lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups) gent = p.gather[(int64_t)pair * p.gather_groups + e];
-  }
   int L = 0;
   if (MODE != kGather) L = clamped_len(p.seq_lens, b + vzero, p.max_seq_len);
   if (MODE == kSelect) issue_first_score_batch(p, rl, pair, split, tid);
@@ -874,9 +877,10 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   unsigned char* const my_stage = smem + wave * kStageBytes;
   unsigned char* const x_stage = smem + kWaves * kStageBytes;
   const bool own_x = gw == 0;            // owner of draft tile 0
-  // Everything loaded so far is needed before the stream starts anyway; draining the counter
-  // here keeps later register reuse from being mistaken for a hazard against the stream.
-  wait_vmcnt<0>();
+  // Without a gather list everything loaded so far is needed before the stream starts anyway
+  // (draining the counter here keeps later register reuse from being mistaken for a hazard
+  // against the stream); with one, only what was issued ahead of the eight query fragments.
+  if (MODE == kGather) wait_vmcnt<8>(); else wait_vmcnt<0>();
   if (!p.draft_mask) rmask = qi >= 63 ? ~0ull : ((2ull << qi) - 1ull);     // linear causal drafts
   if (!row_valid) rmask = 0;
 
