@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--cfg", type=int, default=3, help="workload configuration (3 = the headline metric)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the config's)")
+    ap.add_argument("--tree", type=int, default=0,
+                    help="verify a draft tree of this many nodes (depth 6; 60 = the paper's EAGLE-3 runs, Sec. 4.1) "
+                         "instead of the configuration's drafts, over the same cache")
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=8, help="layers the CPU oracle is timed on")
@@ -521,6 +524,9 @@ def main():
     S.lib()                      # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
     cfg = W.CONFIGS[args.cfg]
+    if args.tree:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, name=f"{cfg.name}_tree{args.tree}", gamma=args.tree, tree_depth=6)
     # single-layer configurations are replicated (independent seeds, every replica an anchor layer) so
     # that no launch re-reads a KV pool that is still in cache and the launch overhead is amortised
     n_layers = args.layers or (cfg.n_layers if cfg.n_layers > 1 else 16)
@@ -709,8 +715,15 @@ def main():
                                   f"({wall:.2f} s wall), scaled to {n_layers} layers; max-abs vs GPU {worst:.2e}"}
 
     value_us = ms_step * 1e3
+    if cfg.dtype != "bf16" or cfg.d != 128:
+        kernel_name = "verify_attn_valu_kernel"
+    elif cfg.gamma * (cfg.Hq // cfg.Hkv) > 64:     # more than two groups of 32 query rows per KV head
+        kernel_name = "verify_attn_mfma_rows_kernel + merge_rows_kernel (reuse layer)"
+    else:
+        kernel_name = "verify_attn_mfma_kernel (reuse layer)"
     line = {
-        "metric": "verify-attn us/step (32k ctx, gamma=8, 2k budget)" if args.cfg == 3 else f"verify-attn us/step ({cfg.name})",
+        "metric": "verify-attn us/step (32k ctx, gamma=8, 2k budget)" if cfg.name == W.CONFIGS[3].name
+                  else f"verify-attn us/step ({cfg.name})",
         "value": round(value_us, 2),
         "unit": "us/step",
         "n_gpus": 1,
@@ -726,8 +739,7 @@ def main():
                    "block_size": cfg.block_size, "gamma": cfg.gamma, "budget_tokens": cfg.k_blocks * cfg.block_size,
                    "page_size": cfg.page_size, "layers": n_layers, "anchor_layers": n_anchor,
                    "launch": "stream" if args.no_graph else "hipgraph"},
-        "roofline": {"bound": "hbm", "kernel": "verify_attn_mfma_kernel (reuse layer)" if cfg.dtype == "bf16" and cfg.d == 128
-                     else "verify_attn_valu_kernel", "achieved": round(attn_gbps, 1),
+        "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if n_layers == cfg.n_layers else None,
                      "algorithmic_bytes_per_launch": bytes_["verify_attn"],

@@ -173,12 +173,21 @@ __device__ __forceinline__ u32x2 load8_bypass_l1(const void* p) {
   asm volatile("global_load_dwordx2 %0, %1, off sc0" : "=v"(v) : "v"(p) : "memory");
   return v;
 }
-__device__ __forceinline__ void merge_loads_wait(u32x4 (&o)[8], u32x2 (&ml)[8]) {
+__device__ __forceinline__ void merge_loads_wait(u32x4 (&o)[8], u32x2& ml) {
   asm volatile("s_waitcnt vmcnt(0)"
-               : "+v"(o[0]), "+v"(o[1]), "+v"(o[2]), "+v"(o[3]), "+v"(o[4]), "+v"(o[5]), "+v"(o[6]), "+v"(o[7]),
-                 "+v"(ml[0]), "+v"(ml[1]), "+v"(ml[2]), "+v"(ml[3]), "+v"(ml[4]), "+v"(ml[5]), "+v"(ml[6]), "+v"(ml[7])
+               : "+v"(o[0]), "+v"(o[1]), "+v"(o[2]), "+v"(o[3]), "+v"(o[4]), "+v"(o[5]), "+v"(o[6]), "+v"(o[7]), "+v"(ml)
                :
                : "memory");
+}
+// Lane N of every row of sixteen lanes, to all lanes of that row.
+template <int N>
+__device__ __forceinline__ uint32_t row_lane(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x150 + N, 0xf, 0xf, false);   // row_newbcast:N
+}
+template <int N>
+__device__ __forceinline__ void row_lanes_upto(uint32_t x, uint32_t (&out)[8]) {
+  out[N] = row_lane<N>(x);
+  if constexpr (N > 0) row_lanes_upto<N - 1>(x, out);
 }
 
 // One 32-token tile against the workgroup's 32 query rows.  stage: LDS address of the stage;
@@ -295,7 +304,8 @@ __device__ __forceinline__ void process_tile(uint32_t stage, const bf16x8 (&qf)[
 // Final merge of a group's split partials by its last workgroup (512 threads): sixteen threads
 // per row, 8 channels each.  All splits, the workgroup's own included, are read back in split
 // order, so the result does not depend on which workgroup happened to arrive last; the loads of
-// kMergeBatch splits are in flight before the first is used.
+// kMergeBatch splits are in flight before the first is used.  A split's (m, l) is loaded by one
+// of the row's sixteen threads and handed round inside the row.
 template <bool LOCAL>
 __device__ __forceinline__ void merge_splits(const AttnParams& p, int64_t g_row, int64_t orow, bool row_ok, int cg) {
   constexpr int kMergeBatch = 8;
@@ -306,27 +316,30 @@ __device__ __forceinline__ void merge_splits(const AttnParams& p, int64_t g_row,
   float m_acc = -INFINITY, l_acc = 0.f;
   for (int s0 = 0; s0 < p.n_splits; s0 += kMergeBatch) {
     u32x4 t[kMergeBatch];
-    u32x2 ml[kMergeBatch];
+    u32x2 ml;                        // of split s0 + cg mod 8
     // (straight-line code between the hand-issued loads and their wait)
+    {
+      const int64_t pr = g_row + (int64_t)min(s0 + (cg & (kMergeBatch - 1)), p.n_splits - 1) * p.Mpad;
+      if (LOCAL) ml = load8_bypass_l1(p.part_ml + 2 * pr);
+      else ml = *reinterpret_cast<const u32x2*>(p.part_ml + 2 * pr);
+    }
 #pragma unroll
     for (int u = 0; u < kMergeBatch; ++u) {
       // entries past the last split (index clamped) get weight 0 below
       const int64_t pr = g_row + (int64_t)min(s0 + u, p.n_splits - 1) * p.Mpad;
-      if (LOCAL) {
-        ml[u] = load8_bypass_l1(p.part_ml + 2 * pr);
-        t[u] = load16_bypass_l1(part_o + pr * kD + cg * 8);
-      } else {
-        ml[u] = *reinterpret_cast<const u32x2*>(p.part_ml + 2 * pr);
-        t[u] = *reinterpret_cast<const u32x4*>(part_o + pr * kD + cg * 8);
-      }
+      if (LOCAL) t[u] = load16_bypass_l1(part_o + pr * kD + cg * 8);
+      else t[u] = *reinterpret_cast<const u32x4*>(part_o + pr * kD + cg * 8);
     }
     if (LOCAL) merge_loads_wait(t, ml);
+    uint32_t mbits[kMergeBatch], lbits[kMergeBatch];
+    row_lanes_upto<kMergeBatch - 1>(ml[0], mbits);
+    row_lanes_upto<kMergeBatch - 1>(ml[1], lbits);
     float pm[kMergeBatch], pl[kMergeBatch];
     float mb = m_acc;
 #pragma unroll
     for (int u = 0; u < kMergeBatch; ++u) {
-      pm[u] = s0 + u >= p.n_splits ? -INFINITY : __uint_as_float(ml[u][0]);
-      pl[u] = __uint_as_float(ml[u][1]);
+      pm[u] = s0 + u >= p.n_splits ? -INFINITY : __uint_as_float(mbits[u]);
+      pl[u] = __uint_as_float(lbits[u]);
       mb = fmaxf(mb, pm[u]);
     }
     const float fa = m_acc == -INFINITY ? 0.f : fast_exp2(m_acc - mb);
@@ -468,6 +481,7 @@ struct RetrievalLoads {
   const int32_t* table_row;             // the sequence's page-table row ...
   int32_t tbl[kTableLoads];             // ... and this thread's entries of it, on their way to LDS
   bool table_in_lds;
+  bool table_wide;                      // entries 4 tid .. 4 tid + 3 (16-byte loads) instead of tid, tid + 512, ...
   bool share_scores;
   uint32_t tag;                         // the group's counter as loaded; retrieve_blocks() adds one
   int rot;                              // first pass of a workgroup that scores alone
@@ -497,7 +511,10 @@ __device__ __forceinline__ RetrievalLoads issue_retrieval_loads(const AttnParams
   RetrievalLoads R;
   // first in the queue, so that nothing slower has to come back before it
   R.q0ch = static_cast<const __hip_bfloat16*>(p.q) + ((int64_t)b * p.gamma * p.Hq + (int64_t)h * p.G) * kD + (tid & (kD - 1));
-  R.q0h = load_query_heads<__hip_bfloat16>(R.q0ch, p.G, kD);
+  // (only the first kD threads use theirs.  A workgroup can hand the memory pipeline one load
+  // instruction per ~20 cycles, whatever its size, so the instructions issued up front, not their
+  // bytes, set how soon the retrieval starts.)
+  if (tid < kD) R.q0h = load_query_heads<__hip_bfloat16>(R.q0ch, p.G, kD);
   // the page-table row goes to LDS while the scores are computed, so that turning kept blocks
   // into addresses afterwards costs no further trip to memory
   R.table_row = p.table + (int64_t)b * p.kv.max_pages;
@@ -505,10 +522,23 @@ __device__ __forceinline__ RetrievalLoads issue_retrieval_loads(const AttnParams
   R.share_scores = p.n_splits >= 2 && p.poll_budget > 0;
   R.tag = p.epochs[xgroup + vzero];
   R.rot = rot;
+  R.table_wide = (p.kv.max_pages & 3) == 0 && (reinterpret_cast<uintptr_t>(p.table) & 15) == 0;
   if (R.table_in_lds) {
+    if (R.table_wide) {
 #pragma unroll
-    for (int u = 0; u < kTableLoads; ++u)
-      if (u * kThreads < p.kv.max_pages) R.tbl[u] = R.table_row[min(tid + u * kThreads, p.kv.max_pages - 1)];
+      for (int u = 0; u < kTableLoads / 4; ++u)
+        if (4 * u * kThreads < p.kv.max_pages) {
+          const int4 t = *reinterpret_cast<const int4*>(R.table_row + min(4 * (tid + u * kThreads), p.kv.max_pages - 4));
+          R.tbl[4 * u] = t.x;
+          R.tbl[4 * u + 1] = t.y;
+          R.tbl[4 * u + 2] = t.z;
+          R.tbl[4 * u + 3] = t.w;
+        }
+    } else {
+#pragma unroll
+      for (int u = 0; u < kTableLoads; ++u)
+        if (u * kThreads < p.kv.max_pages) R.tbl[u] = R.table_row[min(tid + u * kThreads, p.kv.max_pages - 1)];
+    }
   }
   return R;
 }
@@ -529,11 +559,15 @@ struct Retrieved {
 
 // Scores, exchange, selection.  On return s_sel[0 .. cnt) holds the kept blocks (ascending) and
 // every thread has passed the barrier behind the selection.  The scratch arrays live in stage 0
-// and the page-table row in the stages after it; the caller must not stream into them before
-// its own next barrier.  L_raw: the sequence length as loaded (per lane, not yet uniform).
+// and the page-table row in stage 1 (stages 2 and up are the caller's); the caller must not stream
+// into them before its own next barrier.  L_raw: the sequence length as loaded (per lane, not yet uniform).
+// meanwhile(): work of the caller's that may run behind the first barrier (what the caller wrote
+// to its stages before the call is visible there) while the other workgroups' keys are on their way.
+template <typename Meanwhile>
 __device__ __forceinline__ Retrieved retrieve_blocks(const AttnParams& p, RetrievalLoads& R, unsigned char* smem,
                                                      int32_t* s_sel, int* s_exchange_failed, int L_raw, int pair,
-                                                     int split, int xgroup, int tid, int lane, int wave) {
+                                                     int split, int xgroup, int tid, int lane, int wave,
+                                                     Meanwhile&& meanwhile) {
   int32_t* s_table = reinterpret_cast<int32_t*>(smem + kStageBytes);
   float* s_q0 = reinterpret_cast<float*>(smem);
   uint32_t* s_keys = reinterpret_cast<uint32_t*>(smem + kD * 4);
@@ -546,9 +580,17 @@ __device__ __forceinline__ Retrieved retrieve_blocks(const AttnParams& p, Retrie
   for (int i = tid; i < 4 * 256; i += kThreads) (&s_sc->hist[0][0])[i] = 0;
   if (tid == 0) *s_exchange_failed = 0;
   if (R.table_in_lds) {
+    if (R.table_wide) {
 #pragma unroll
-    for (int u = 0; u < kTableLoads; ++u)
-      if (tid + u * kThreads < p.kv.max_pages) s_table[tid + u * kThreads] = R.tbl[u];
+      for (int u = 0; u < kTableLoads / 4; ++u)
+        if (4 * (tid + u * kThreads) < p.kv.max_pages)
+          *reinterpret_cast<int4*>(s_table + 4 * (tid + u * kThreads)) =
+              make_int4(R.tbl[4 * u], R.tbl[4 * u + 1], R.tbl[4 * u + 2], R.tbl[4 * u + 3]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < kTableLoads; ++u)
+        if (tid + u * kThreads < p.kv.max_pages) s_table[tid + u * kThreads] = R.tbl[u];
+    }
   }
   __syncthreads();
   Retrieved out;
@@ -585,6 +627,7 @@ __device__ __forceinline__ Retrieved retrieve_blocks(const AttnParams& p, Retrie
     // the others' keys: a key is valid once its word carries this call's tag.  The wait is
     // bounded; a workgroup that runs out of patience scores everything itself.
     score_batch(split, p.n_splits, false, true);
+    meanwhile();
     const int j0 = tid, j1 = tid + kThreads;
     bool need0 = j0 < nb && ((j0 >> 6) % p.n_splits) != split;
     bool need1 = j1 < nb && ((j1 >> 6) % p.n_splits) != split;
@@ -607,6 +650,7 @@ __device__ __forceinline__ Retrieved retrieve_blocks(const AttnParams& p, Retrie
     __syncthreads();
     score_alone = *s_exchange_failed != 0;
   }
+  if (!R.share_scores) meanwhile();
   if (score_alone) {
     const bool loaded = !R.share_scores;               // the up-front batch was this one
     for (int f = 0; f * 64 < nb; f += kScoreBatch) {
@@ -740,7 +784,21 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     if (lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups) gent = p.gather[(int64_t)pair * p.gather_groups + e];
   }
   bf16x8 qf[8];
-  {
+  // A retrieving workgroup has barriers ahead anyway: its 32 query rows come in once (16 bytes
+  // per thread) and reach the wavefronts' registers through LDS (chunk c of row r at position
+  // c ^ (r & 15)), instead of eight loads per lane in each of the eight wavefronts.
+  unsigned char* const q_stage = smem + 2 * kStageBytes;
+  u32x4 qpiece = {0u, 0u, 0u, 0u};
+  if (MODE == kSelect) {
+    const int r = tid >> 4, rrow = row0 + r;
+    int ri = 0, rj = 0;
+    if (rrow < p.M) {
+      ri = (int)(((uint64_t)(uint32_t)rrow * p.g_magic) >> 32);
+      rj = rrow - ri * p.G;
+    }
+    qpiece = *reinterpret_cast<const u32x4*>(static_cast<const __hip_bfloat16*>(p.q) +
+                                             (((int64_t)b * p.gamma + ri) * p.Hq + h * p.G + rj) * kD + (tid & 15) * 8);
+  } else {
     const __hip_bfloat16* qrow = static_cast<const __hip_bfloat16*>(p.q) +
                                  (((int64_t)b * p.gamma + qi) * p.Hq + h * p.G + qj) * kD + g * 8;
 #pragma unroll
@@ -751,26 +809,31 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   int L = 0;
   if (MODE != kGather) L = clamped_len(p.seq_lens, b + vzero, p.max_seq_len);
   if (MODE == kSelect) issue_first_score_batch(p, rl, pair, split, tid);
+  if (MODE == kSelect) {
+    const int r = tid >> 4;
+    *reinterpret_cast<u32x4*>(q_stage + r * kRowBytes + (((tid & 15) ^ (r & 15)) << 4)) = qpiece;
+  }
   int cnt;
   uint32_t tag = 0;                  // (retrieval only) this call's tag of the key exchange
   if (MODE == kSelect) {
-    const Retrieved rt = retrieve_blocks(p, rl, smem, s_sel, &s_exchange_failed, L, pair, split, group, tid, lane, wave);
+    const Retrieved rt = retrieve_blocks(p, rl, smem, s_sel, &s_exchange_failed, L, pair, split, group, tid, lane, wave, [&]() {
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+        qf[ks] = *reinterpret_cast<const bf16x8*>(q_stage + l32 * kRowBytes + (((2 * ks + g) ^ (l32 & 15)) << 4));
+    });
     L = rt.L;
     cnt = rt.cnt;
     tag = rt.tag;
-    // the workgroup with the least other work publishes the selection
-    if (split == p.n_splits - 1 && rg == 0) publish_selection(p, s_sel, cnt, pair, tid);
     // gather entries of this wavefront's tiles (lane 8u + n: group n of its u-th tile), kept for
-    // the loads below and written out for the layers that reuse the selection
+    // the loads below; they are written out for the layers that reuse the selection, and the
+    // selection itself, behind the main loop: a store in front of the stream would be one more
+    // thing the stream's first wait has to see acknowledged
     {
       const int tc = gw + (lane >> 3) * NW - tiles_d;                          // cache tile index
       const int e = tc * 8 + (lane & 7);
-      if (lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups) {
-        gent = gather_entry_of(p, s_sel, rt, rl, e, b, h);
-        if (rg == 0) p.gather_out[(int64_t)pair * p.gather_groups + e] = gent;
-      }
+      if (lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups) gent = gather_entry_of(p, s_sel, rt, rl, e, b, h);
     }
-    __syncthreads();                 // the last reads of the staged page table are done
+    __syncthreads();                 // the last reads of the staged page table and the query rows are done
   } else {
     cnt = __builtin_amdgcn_readfirstlane(min(max(p.sel_cnt[pair + vzero], 0), p.k_blocks));
   }
@@ -909,11 +972,21 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     cur = nxt;
   }
 
+  if (MODE == kSelect) {
+    // the workgroup with the least other work publishes the selection (s_sel is not a stage)
+    if (split == p.n_splits - 1 && rg == 0) publish_selection(p, s_sel, cnt, pair, tid);
+    const int tc = gw + (lane >> 3) * NW - tiles_d;
+    const int e = tc * 8 + (lane & 7);
+    if (rg == 0 && lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups)
+      p.gather_out[(int64_t)pair * p.gather_groups + e] = gent;
+  }
+
   // ---- combine the eight wavefronts through LDS ------------------------------------------------
   // Wavefront w parks its fp32 output, as it stands (relative to its own running maximum), in
   // its own stage as [32 rows][32 float4], as soon as it is done; float4 chunk c4 of row r sits
-  // at position c4 ^ r, which keeps both the row-per-lane writes and the chunk-per-lane reads
-  // off each other's banks.  After the one barrier the readers bring the eight slices to the
+  // at position (c4 / 2 + 16 (c4 mod 2)) ^ r (even chunks in one half of the row, odd ones in the
+  // other), which keeps both the row-per-lane writes and the reads (sixteen lanes take the even,
+  // then the odd chunks of a row) off each other's banks.  After the one barrier the readers bring the eight slices to the
   // common maximum while they add them.
   l_run += __shfl_xor(l_run, 32, 64);
   if (g == 0) {
@@ -925,7 +998,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int i = 8 * (v >> 2) + 4 * g + (v & 3);        // dims 4*i .. 4*i+3
-      mine[l32 * 32 + (i ^ l32)] = make_float4(oacc[0][v], oacc[1][v], oacc[2][v], oacc[3][v]);
+      mine[l32 * 32 + (((i >> 1) | ((i & 1) << 4)) ^ l32)] = make_float4(oacc[0][v], oacc[1][v], oacc[2][v], oacc[3][v]);
     }
   }
   __syncthreads();
@@ -952,7 +1025,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   for (int w = 0; w < kWaves; ++w)
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
-      const float4 t = reinterpret_cast<const float4*>(smem + w * kStageBytes)[r * 32 + ((cg * 2 + c) ^ r)];
+      const float4 t = reinterpret_cast<const float4*>(smem + w * kStageBytes)[r * 32 + ((cg | (c << 4)) ^ r)];
       racc[4 * c] = __builtin_fmaf(t.x, fw[w], racc[4 * c]);
       racc[4 * c + 1] = __builtin_fmaf(t.y, fw[w], racc[4 * c + 1]);
       racc[4 * c + 2] = __builtin_fmaf(t.z, fw[w], racc[4 * c + 2]);
@@ -1154,7 +1227,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   int cnt;
   uint32_t tag = 0;
   if (MODE == kSelect) {
-    const Retrieved rt = retrieve_blocks(p, rl, smem, s_sel, &s_exchange_failed, L, pair, split, xgroup, tid, lane, wave);
+    const Retrieved rt = retrieve_blocks(p, rl, smem, s_sel, &s_exchange_failed, L, pair, split, xgroup, tid, lane, wave, []() {});
     L = rt.L;
     cnt = rt.cnt;
     tag = rt.tag;
@@ -1409,7 +1482,7 @@ __global__ __launch_bounds__(kThreads) void retrieve_only_kernel(AttnParams p, i
   RetrievalLoads rl = issue_retrieval_loads(p, b, h, pair, split, pair, split % kScoreBatch, tid, vzero);
   const int L = clamped_len(p.seq_lens, b + vzero, p.max_seq_len);
   issue_first_score_batch(p, rl, pair, split, tid);
-  const Retrieved rt = retrieve_blocks(p, rl, smem, s_sel, &s_exchange_failed, L, pair, split, pair, tid, lane, wave);
+  const Retrieved rt = retrieve_blocks(p, rl, smem, s_sel, &s_exchange_failed, L, pair, split, pair, tid, lane, wave, []() {});
   if (split == p.n_splits - 1) publish_selection(p, s_sel, rt.cnt, pair, tid);
   if (rl.share_scores && tid == 0) {
     // every workgroup that takes a ticket has read all the keys it needed
