@@ -190,6 +190,34 @@ __device__ __forceinline__ void row_lanes_upto(uint32_t x, uint32_t (&out)[8]) {
   if constexpr (N > 0) row_lanes_upto<N - 1>(x, out);
 }
 
+// The eight 16-byte fragments of a lane's query row, loaded by hand: not valid before a wait of
+// the caller's own has covered them and query_fragments_arrived() has been given the registers.
+__device__ __forceinline__ void load_query_fragments(bf16x8 (&qf)[8], const void* row) {
+#define SVF_QFRAG(i)                                                                                   \
+  asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(qf[i]) : "v"(row), "n"((i) * 32) : "memory")
+  SVF_QFRAG(0); SVF_QFRAG(1); SVF_QFRAG(2); SVF_QFRAG(3);
+  SVF_QFRAG(4); SVF_QFRAG(5); SVF_QFRAG(6); SVF_QFRAG(7);
+#undef SVF_QFRAG
+}
+__device__ __forceinline__ u32x2 load8_plain(const void* p) {
+  u32x2 v;
+  asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+  return v;
+}
+__device__ __forceinline__ uint32_t load4_plain(const void* p) {
+  uint32_t v;
+  asm volatile("global_load_dword %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+  return v;
+}
+__device__ __forceinline__ void front_loads_arrived(u32x2& a, u32x2& b, uint32_t& c) {
+  asm volatile("" : "+v"(a), "+v"(b), "+v"(c) : : "memory");
+}
+__device__ __forceinline__ void query_fragments_arrived(bf16x8 (&qf)[8]) {
+  asm volatile("" : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[4]), "+v"(qf[5]), "+v"(qf[6]), "+v"(qf[7])
+               :
+               : "memory");
+}
+
 // One 32-token tile against the workgroup's 32 query rows.  stage: LDS address of the stage;
 // allowed: bit t set = token t of the tile is visible to this lane's row.  Register use is kept
 // low (two wavefronts share a SIMD): fragment addresses are recomputed, K fragments come in two
@@ -710,7 +738,8 @@ struct TileInfo {
 // LDS; the workgroups of a pair repeat this work (they share an XCD, so the representatives
 // come out of its L2 after the first), which costs less than two more launches.  The result is
 // written to sel_idx / sel_cnt and, tile by tile, to the gather list for the layers that reuse it.
-template <int MODE>
+// kEntriesFirst (MODE kGather): which of the up-front loads go out first, see below.
+template <int MODE, bool kEntriesFirst = true>
 __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p, int pairs) {
   // one stage per wavefront, plus one for draft tile 0 (its owner then streams its cache tile
   // at the same time); after the main loop stage w becomes wavefront w's fp32 output buffer
@@ -772,17 +801,33 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   if (MODE == kSelect)
     rl = issue_retrieval_loads(p, b, h, pair, split, group, (split + rg * p.n_splits) % kScoreBatch, tid, vzero);
   const int32_t* const table_row = p.table + (int64_t)b * p.kv.max_pages;
-  // With a gather list the tile loads wait for nothing but their gather entries: those (and the
-  // draft mask) go out ahead of the query fragments, which may then arrive while the tiles are
-  // on their way.  Lane 8u + n holds the entry of group n of the wavefront's u-th tile.
+  // With a gather list the tile loads wait for nothing but their gather entries.  Where a
+  // wavefront has one tile (kEntriesFirst) the entries (with the draft mask and the pair's block
+  // count) go out ahead of the query fragments, which may then arrive while the tile is on its
+  // way: 0.4 us per launch.  Where wavefronts walk several tiles one after the other the
+  // fragments go first and everything is waited for: the earlier start loses there (measured:
+  // 15.2 against 15.7 us per launch with two to three tiles per wavefront) - the compute units
+  // then alternate between fetching and computing in step with each other.
+  // Lane 8u + n holds the entry of group n of the wavefront's u-th tile.  All of these loads are
+  // issued by hand (the compiler, which cannot see hand-issued loads, would make the wait for a
+  // load of its own a wait for the fragments as well), unconditionally, from addresses that are
+  // valid either way; nothing of them is used before front_loads_arrived().
   uint64_t rmask = 0;
-  if (MODE == kGather && p.draft_mask) rmask = p.draft_mask[p.mask_per_batch ? (int64_t)b * p.gamma + qi : qi];
   uint64_t gent = 0;
-  if (MODE == kGather) {
+  u32x2 rmask_raw = {0u, 0u}, gent_raw = {0u, 0u};
+  uint32_t cnt_raw = 0;
+  bool gent_wanted = false;
+  auto request_entries = [&]() {
     const int tc = gw + (lane >> 3) * NW - tiles_d;          // cache tile index
     const int e = tc * 8 + (lane & 7);
-    if (lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups) gent = p.gather[(int64_t)pair * p.gather_groups + e];
-  }
+    gent_wanted = lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups;
+    const uint64_t* gsrc = p.gather + (int64_t)pair * p.gather_groups + (gent_wanted ? e : 0);
+    const uint64_t* msrc = p.draft_mask ? p.draft_mask + (p.mask_per_batch ? (int64_t)b * p.gamma + qi : qi) : gsrc;
+    gent_raw = load8_plain(gsrc);
+    rmask_raw = load8_plain(msrc);
+    cnt_raw = load4_plain(p.sel_cnt + pair + vzero);
+  };
+  if (MODE == kGather && kEntriesFirst) request_entries();
   bf16x8 qf[8];
   // A retrieving workgroup has barriers ahead anyway: its 32 query rows come in once (16 bytes
   // per thread) and reach the wavefronts' registers through LDS (chunk c of row r at position
@@ -801,9 +846,16 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   } else {
     const __hip_bfloat16* qrow = static_cast<const __hip_bfloat16*>(p.q) +
                                  (((int64_t)b * p.gamma + qi) * p.Hq + h * p.G + qj) * kD + g * 8;
+    if (MODE == kGather) {
+      // issued by hand: the fragments are in once at most one tile's loads are outstanding (see
+      // below), which the compiler's own bookkeeping would turn into a full wait inside the loop
+      load_query_fragments(qf, qrow);
+    } else {
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
+      for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
+    }
   }
+  if (MODE == kGather && !kEntriesFirst) request_entries();
   if (MODE != kGather && p.draft_mask) rmask = p.draft_mask[p.mask_per_batch ? (int64_t)b * p.gamma + qi : qi];
 
   int L = 0;
@@ -834,6 +886,13 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       if (lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups) gent = gather_entry_of(p, s_sel, rt, rl, e, b, h);
     }
     __syncthreads();                 // the last reads of the staged page table and the query rows are done
+  } else if (MODE == kGather) {
+    // everything requested ahead of the eight query fragments, or everything
+    if (kEntriesFirst) wait_vmcnt<8>(); else wait_vmcnt<0>();
+    front_loads_arrived(gent_raw, rmask_raw, cnt_raw);
+    if (gent_wanted) gent = (uint64_t)gent_raw[0] | ((uint64_t)gent_raw[1] << 32);
+    if (p.draft_mask) rmask = (uint64_t)rmask_raw[0] | ((uint64_t)rmask_raw[1] << 32);
+    cnt = __builtin_amdgcn_readfirstlane(min(max((int)cnt_raw, 0), p.k_blocks));
   } else {
     cnt = __builtin_amdgcn_readfirstlane(min(max(p.sel_cnt[pair + vzero], 0), p.k_blocks));
   }
@@ -942,8 +1001,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   const bool own_x = gw == 0;            // owner of draft tile 0
   // Without a gather list everything loaded so far is needed before the stream starts anyway
   // (draining the counter here keeps later register reuse from being mistaken for a hazard
-  // against the stream); with one, only what was issued ahead of the eight query fragments.
-  if (MODE == kGather) wait_vmcnt<8>(); else wait_vmcnt<0>();
+  // against the stream); with one, the query fragments may still be on their way.
+  if (MODE != kGather) wait_vmcnt<0>();
   if (!p.draft_mask) rmask = qi >= 63 ? ~0ull : ((2ull << qi) - 1ull);     // linear causal drafts
   if (!row_valid) rmask = 0;
 
@@ -956,7 +1015,13 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       nxt = issue_tile(gw + NW, 1, my_stage);
       issued = 2;
     }
+    // The query fragments were requested before the tiles and loads complete in order: with at
+    // most one tile's loads outstanding they are in (a second tile may still be in flight).
+    if (MODE == kGather) wait_vmcnt<16>();
+  } else if (MODE == kGather) {
+    wait_vmcnt<0>();
   }
+  if (MODE == kGather) query_fragments_arrived(qf);
   for (int u = 0; u < n_my; ++u) {
     if (u >= issued) {                   // the single stage is free again: fetch the next tile
       cur = issue_tile(gw + u * NW, u, my_stage);
@@ -1519,8 +1584,14 @@ hipError_t launch_verify_attn_mfma(const AttnParams& p, hipStream_t st) {
   }
   const dim3 grid((unsigned)(kXcds * p.n_splits), (unsigned)((pairs + kXcds - 1) / kXcds), (unsigned)row_groups);
   if (p.reps) hipLaunchKernelGGL(verify_attn_mfma_kernel<kSelect>, grid, dim3(kThreads), 0, st, p, pairs);
-  else if (p.gather) hipLaunchKernelGGL(verify_attn_mfma_kernel<kGather>, grid, dim3(kThreads), 0, st, p, pairs);
-  else hipLaunchKernelGGL(verify_attn_mfma_kernel<kResolve>, grid, dim3(kThreads), 0, st, p, pairs);
+  else if (p.gather) {
+    // one tile per wavefront (the owner of draft tile 0 streams a second one beside it)?
+    const int64_t tiles = ((int64_t)p.k_blocks * p.block_size + kTile - 1) / kTile + (p.gamma + kTile - 1) / kTile;
+    if (tiles - 1 <= (int64_t)kWaves * p.n_splits)
+      hipLaunchKernelGGL((verify_attn_mfma_kernel<kGather, true>), grid, dim3(kThreads), 0, st, p, pairs);
+    else
+      hipLaunchKernelGGL((verify_attn_mfma_kernel<kGather, false>), grid, dim3(kThreads), 0, st, p, pairs);
+  } else hipLaunchKernelGGL(verify_attn_mfma_kernel<kResolve>, grid, dim3(kThreads), 0, st, p, pairs);
   return hipGetLastError();
 }
 

@@ -120,6 +120,8 @@ EDGE = {
     "blocks_768": small(B=1, Hq=4, Hkv=1, T=49152, k_blocks=24, planted=5, min_len=40000),
     "long_page_table": small(B=1, Hq=4, Hkv=1, T=20480, page_size=4, k_blocks=8, planted=3),
     "two_row_groups": small(Hq=16, Hkv=2, gamma=7, n_sink=1, n_local=1),
+    # a page-table row whose length is no multiple of four entries (staged entry by entry)
+    "page_table_63_entries": small(T=1000, min_len=600, k_blocks=5),
     # more than two row groups of 32 query rows: one workgroup walks the tiles for up to eight row groups
     "rows_gamma24_tree": small(gamma=24, tree_depth=5),
     "rows_ring_of_stages": small(B=8, Hq=32, Hkv=8, gamma=24, T=4096, k_blocks=32, tree_depth=4, min_len=3000),
