@@ -27,7 +27,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 # HBM bytes per reuse-layer attention launch from rocprofv3 (FETCH_SIZE x 1.9997 + WRITE_SIZE, KiB
 # per dispatch, scaled by a 256 MiB copy kernel): profiles/verify_attn_cfg3_hbm_traffic.md
-MEASURED_TRAFFIC_BYTES = {"cfg3_long_batch_32k": 38.7e6}
+MEASURED_TRAFFIC_BYTES = {"cfg3_long_batch_32k": 38.8e6}
 
 
 def step_mode(cfg, layer):
