@@ -1171,6 +1171,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
 // LDS at the end: every wavefront writes its rows itself: the output if there is one split, else
 // a partial that merge_rows_kernel combines.
 constexpr int kRowStages = kWaves + 1;
+constexpr int kRowWindow = 3;                // tiles between two barriers; divides kRowStages
+static_assert(kRowStages % kRowWindow == 0, "a window must map onto whole stages of the ring");
 constexpr int kMaxRowTiles = 64;             // tiles per workgroup: one gather entry per lane
 
 // What a wavefront of the rows kernel needs to fetch its part of a tile.
@@ -1368,47 +1370,63 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   if (!p.draft_mask) rmask = qi >= 63 ? ~0ull : ((2ull << qi) - 1ull);
   if (!row_valid) rmask = 0;
 
-  // ---- main loop: up to nine tiles in flight ----------------------------------------------------
+  // ---- main loop: nine stages, tiles taken three at a time -----------------------------------------
+  // One barrier per window of kRowWindow tiles rather than per tile: behind a barrier all eight
+  // wavefronts are in the same phase (all reading LDS, then all on the matrix cores, then all in
+  // the softmax); over three tiles they drift apart and one wavefront's MFMA runs under the other's
+  // vector work.  The stages of the window before take the next tiles.
   int issued = 0;
   for (; issued < min(n_my, kRowStages); ++issued) issue_row_tile(ic, issued);
-  for (int i = 0; i < n_my; ++i) {
-    // this wavefront's loads of tile i have landed (two loads per tile, issued in order); the
-    // count of the group it fetched is on its way to LDS
-    wait_vmcnt_upto16(2 * (issued - i - 1));
+  for (int i0 = 0; i0 < n_my; i0 += kRowWindow) {
+    const int nw = min(kRowWindow, n_my - i0);
+    // this wavefront's loads of the window's tiles have landed (two loads per tile, issued in
+    // order); the counts of the groups it fetched are on their way to LDS
+    wait_vmcnt_upto16(2 * (issued - (i0 + nw)));
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    // everybody is done with tile i - 1: its stage takes tile i + 8
-    if (i >= 1 && issued < n_my) {
-      issue_row_tile(ic, issued);
-      ++issued;
-    }
-    const int t = split + i * S;
-    const int st = i % kRowStages;
-    u32x4 nvq[2];
-    nvq[0] = lds_read16<0>(nv_lds + (uint32_t)st * (kWaves * 4));
-    nvq[1] = lds_read16<16>(nv_lds + (uint32_t)st * (kWaves * 4));
-    lds_wait2(nvq);
-    uint32_t valid = 0;
+    // everybody is done with the window before
+    if (i0 >= kRowWindow) {
 #pragma unroll
-    for (int n = 0; n < 8; ++n) valid |= ((1u << nvq[n >> 2][n & 3]) - 1u) << (4 * n);
-    valid = (uint32_t)__builtin_amdgcn_readfirstlane((int)valid);
-    if (has_rows) {
-      const int draft_base = t < tiles_d ? t * kTile : -1;
-      uint32_t allowed = valid;
-      if (draft_base >= 0) allowed &= (uint32_t)(rmask >> (draft_base & 63));
-      const bool all_visible = draft_base < 0 && valid == 0xffffffffu;
-      const uint32_t stage = (uint32_t)(uintptr_t)SVF_LDS_PTR(smem + st * kStageBytes);
-      process_tile(stage, qf, allowed, all_visible, p.scale_log2, l32, g, m_run, l_run, oacc);
+      for (int k = 0; k < kRowWindow; ++k)
+        if (issued < n_my) {
+          issue_row_tile(ic, issued);
+          ++issued;
+        }
+    }
+    for (int k = 0; k < nw; ++k) {
+      const int i = i0 + k;
+      const int t = split + i * S;
+      const int st = i % kRowStages;
+      u32x4 nvq[2];
+      nvq[0] = lds_read16<0>(nv_lds + (uint32_t)st * (kWaves * 4));
+      nvq[1] = lds_read16<16>(nv_lds + (uint32_t)st * (kWaves * 4));
+      lds_wait2(nvq);
+      uint32_t valid = 0;
+#pragma unroll
+      for (int n = 0; n < 8; ++n) valid |= ((1u << nvq[n >> 2][n & 3]) - 1u) << (4 * n);
+      valid = (uint32_t)__builtin_amdgcn_readfirstlane((int)valid);
+      if (has_rows) {
+        const int draft_base = t < tiles_d ? t * kTile : -1;
+        uint32_t allowed = valid;
+        if (draft_base >= 0) allowed &= (uint32_t)(rmask >> (draft_base & 63));
+        const bool all_visible = draft_base < 0 && valid == 0xffffffffu;
+        const uint32_t stage = (uint32_t)(uintptr_t)SVF_LDS_PTR(smem + st * kStageBytes);
+        process_tile(stage, qf, allowed, all_visible, p.scale_log2, l32, g, m_run, l_run, oacc);
+      }
     }
   }
+  // the other wavefronts may still be reading the last window's stages
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
   if (!has_rows) return;             // no barrier from here on
 
   // ---- this wavefront's 32 rows: output or partial ------------------------------------------------
   // The normalised rows go through LDS once (bf16, [row][128 channels], 16-byte chunk c of row r
   // at position c ^ (r & 15)) so that they leave in whole 256-byte rows: a lane's registers hold
-  // 8-byte pieces of 32 different rows.  The stage used is one nobody reads any more: no load
-  // is in flight after the last barrier, and only the last tile's stage may still be read.
+  // 8-byte pieces of 32 different rows.  Behind the barrier above nobody reads a stage any more
+  // and no load is in flight.
   l_run += __shfl_xor(l_run, 32, 64);
   const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
   {
