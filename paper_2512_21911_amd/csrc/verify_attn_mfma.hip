@@ -679,14 +679,14 @@ __device__ __forceinline__ Retrieved retrieve_blocks(const AttnParams& p, Retrie
     score_alone = *s_exchange_failed != 0;
   }
   if (!R.share_scores) meanwhile();
-  if (score_alone) {
+  if (score_alone) {                                   // (the same for the whole workgroup)
     const bool loaded = !R.share_scores;               // the up-front batch was this one
     for (int f = 0; f * 64 < nb; f += kScoreBatch) {
       if (!(loaded && f == 0)) load_score_batch(p, rp, jrow, f, 1, true, R.rot, R.r);
       score_batch(f, 1, true, false);
     }
+    __syncthreads();                                   // (after an exchange the barrier above has done this)
   }
-  __syncthreads();
   if (out.cnt > 0) workgroup_select(s_keys, s_sc, nb, out.cnt, s_sel, tid, lane, wave);
   __syncthreads();
   return out;
