@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--cfg", type=int, default=3, help="workload configuration (3 = the headline metric)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the config's)")
+    ap.add_argument("--hnd", action="store_true",
+                    help="store the cache pages head-major ([page][Hkv][slot][d]) instead of token-major "
+                         "([page][slot][Hkv][d], the configurations' layout); same interface, through the strides")
     ap.add_argument("--tree", type=int, default=0,
                     help="verify a draft tree of this many nodes (depth 6; 60 = the paper's EAGLE-3 runs, Sec. 4.1) "
                          "instead of the configuration's drafts, over the same cache")
@@ -536,6 +539,10 @@ def main():
     layers = []
     for l in range(n_layers):
         x = W.make_layer(cfg, l, device="cuda")
+        if args.hnd and x["block_table"] is not None:
+            for key in ("k_pool", "v_pool"):
+                store = x[key].permute(0, 2, 1, 3).contiguous()     # storage [page][Hkv][slot][d]
+                x[key] = store.permute(0, 2, 1, 3)                  # logical view: the strides carry the layout
         layers.append(x)
     x0 = layers[0]
     shape = S.make_shape(B=cfg.B, gamma=cfg.gamma, Hq=cfg.Hq, Hkv=cfg.Hkv, d=cfg.d, dtype=cfg.dtype,
@@ -694,6 +701,9 @@ def main():
             wall += time.perf_counter() - w0
             cpu_t += time.process_time() - c0
             xg = {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in x.items()}
+            if args.hnd and xg["block_table"] is not None:
+                for key in ("k_pool", "v_pool"):
+                    xg[key] = xg[key].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
             r = torch.empty_like(reps[0])
             o = torch.empty_like(outs[0])
             S.svf_block_reps(shape, xg["k_pool"], xg["block_table"], xg["seq_lens"], r)
@@ -737,11 +747,12 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "d": cfg.d, "T": cfg.T,
                    "block_size": cfg.block_size, "gamma": cfg.gamma, "budget_tokens": cfg.k_blocks * cfg.block_size,
-                   "page_size": cfg.page_size, "layers": n_layers, "anchor_layers": n_anchor,
+                   "page_size": cfg.page_size, "page_layout": "head-major" if args.hnd else "token-major",
+                   "layers": n_layers, "anchor_layers": n_anchor,
                    "launch": "stream" if args.no_graph else "hipgraph"},
         "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if n_layers == cfg.n_layers else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if n_layers == cfg.n_layers and not args.hnd else None,
                      "algorithmic_bytes_per_launch": bytes_["verify_attn"],
                      "avg_launch_us": round(attn_us, 3)},
         "cpu_baseline": cpu_baseline,
