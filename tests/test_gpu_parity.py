@@ -59,6 +59,14 @@ def test_full_size_configs(cfg_id):
             assert set(idx[0, h].tolist()) <= set(r["x"]["planted"][0][h].tolist())
 
 
+def test_tree60_over_the_full_size_cache():
+    """A 60-node draft tree (Sec. 4.1's EAGLE-3 runs) over cfg 3's cache: the many-rows kernel at the
+    shape `bench.py --tree 60` times."""
+    cfg = dataclasses.replace(W.CONFIGS[3], name="cfg3_tree60", gamma=60, tree_depth=6, n_layers=1)
+    r = full_parity(cfg)
+    report("cfg3 cache, 60-node tree", r)
+
+
 def test_cfg3_reuse_layer_matches_anchor_blocks():
     """Eq. 9: the non-anchor layer attends with the anchor's block set."""
     cfg = W.shrink(W.CONFIGS[3], 4096)
