@@ -508,9 +508,16 @@ __global__ __launch_bounds__(256) void ffn_reduce_kernel(FfnParams p) {
   if (i4 >= total) return;
   const int n = (int)(i4 % p.d_model);
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int k = 0; k < p.k_splits; ++k) {
-    const float4 v = *reinterpret_cast<const float4*>(p.partial + (int64_t)k * total + i4);
-    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  // eight slices requested before the first is added (one after the other, every slice costs a
+  // trip to memory); added in slice order
+  for (int k0 = 0; k0 < p.k_splits; k0 += 8) {
+    float4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      v[u] = *reinterpret_cast<const float4*>(p.partial + (int64_t)min(k0 + u, p.k_splits - 1) * total + i4);
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (k0 + u < p.k_splits) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
   }
   if (p.b_down) {
     const float4 b = *reinterpret_cast<const float4*>(p.b_down + n);
