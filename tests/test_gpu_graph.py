@@ -3,6 +3,8 @@ captured sequence of anchor and reuse layers must give, on every replay, the bit
 made eagerly - with other work and synchronisations between the replays (the anchor kernel's key
 exchange advances its tags inside the graph, the workspaces reset themselves) - and those bits are
 checked against the oracle."""
+import dataclasses
+
 import pytest
 import torch
 
@@ -44,9 +46,11 @@ def poison_outputs(runs, cfg):
             r.sel_cnt.fill_(-7)
 
 
-@pytest.mark.parametrize("T,n_layers", [(4096, 4), (32768, 2)])
-def test_step_graph_replays_match_eager_calls(T, n_layers):
+@pytest.mark.parametrize("T,n_layers,tree", [(4096, 4, 0), (32768, 2, 0), (4096, 4, 24)])
+def test_step_graph_replays_match_eager_calls(T, n_layers, tree):
     cfg = W.shrink(W.CONFIGS[3], T) if T < W.CONFIGS[3].T else W.CONFIGS[3]
+    if tree:        # a draft tree: the many-rows kernel, whose splits are merged by a second launch
+        cfg = dataclasses.replace(cfg, name=cfg.name + "_tree", gamma=tree, tree_depth=4)
     runs = build_layers(cfg, n_layers)
     step(cfg, runs)
     torch.cuda.synchronize()
