@@ -738,14 +738,22 @@ struct TileInfo {
 // LDS; the workgroups of a pair repeat this work (they share an XCD, so the representatives
 // come out of its L2 after the first), which costs less than two more launches.  The result is
 // written to sel_idx / sel_cnt and, tile by tile, to the gather list for the layers that reuse it.
-// kEntriesFirst (MODE kGather): which of the up-front loads go out first, see below.
-template <int MODE, bool kEntriesFirst = true>
+// kOneTile: no wavefront has more than one tile of the cache (the launcher knows).  Then only
+// wavefronts 0 .. 3 compute: wavefront w takes its own tile and, after a barrier, the tile that
+// wavefront w + 4 (same SIMD) has fetched into its stage - the second wavefront of a SIMD gets its
+// loads out last anyway.  Four slices instead of eight go through the combination below (whose
+// cost is its instruction count: 0.5 instead of 1.0 us), four wavefronts instead of eight load
+// query fragments, and the tiles that arrive last are computed by wavefronts that have the SIMD
+// to themselves.  Also (MODE kGather): which of the up-front loads go out first, see below.
+template <int MODE, bool kOneTile>
 __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p, int pairs) {
   // one stage per wavefront, plus one for draft tile 0 (its owner then streams its cache tile
   // at the same time); after the main loop stage w becomes wavefront w's fp32 output buffer
   __shared__ __attribute__((aligned(1024))) unsigned char smem[(kWaves + 1) * kStageBytes];
   __shared__ float sm_m[kWaves][32];
   __shared__ float sm_l[kWaves][32];
+  __shared__ uint32_t sm_pair_valid[kWaves / 2];   // (kOneTile) what wavefront w + 4 fetched: valid slots,
+  __shared__ int sm_pair_draft[kWaves / 2];        // draft base (-1: cache tile, -2: nothing)
   __shared__ int sm_last;
   __shared__ int32_t s_sel[MODE == kSelect ? kMaxSelectBlocks : 1];   // kept blocks, ascending
   __shared__ int s_exchange_failed;
@@ -779,6 +787,20 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   const int row0 = rg * 32;
   const int NW = kWaves * p.n_splits;
   const int gw = split * kWaves + wave;
+  constexpr int kSlices = kOneTile ? kWaves / 2 : kWaves;      // wavefronts that compute
+  const bool computes = wave < kSlices;                         // (wave-uniform)
+  // Draft tile 0 has a stage of its own, of which only the four-token groups that hold a draft
+  // are fetched (two of eight for eight drafts: 4 load instructions instead of 32).  The V rows
+  // of the other groups must still be finite (their weights are zero, and 0 x NaN is not): the
+  // wavefront that owns the tile clears them now, before it has any load in flight.  What the K
+  // rows hold does not matter: the scores of slots without a token are replaced.
+  if (gw == 0) {
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int k = 0; k < kTileBytes / 1024; ++k)
+      *reinterpret_cast<u32x4*>(smem + kWaves * kStageBytes + kTileBytes + k * 1024 + lane * 16) = zero;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  }
   const int tiles_d = (p.gamma + kTile - 1) / kTile;           // draft tiles come first
 
   const char* Kc = static_cast<const char*>(p.K);
@@ -802,7 +824,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     rl = issue_retrieval_loads(p, b, h, pair, split, group, (split + rg * p.n_splits) % kScoreBatch, tid, vzero);
   const int32_t* const table_row = p.table + (int64_t)b * p.kv.max_pages;
   // With a gather list the tile loads wait for nothing but their gather entries.  Where a
-  // wavefront has one tile (kEntriesFirst) the entries (with the draft mask and the pair's block
+  // wavefront has one tile (kOneTile) the entries (with the draft mask and the pair's block
   // count) go out ahead of the query fragments, which may then arrive while the tile is on its
   // way: 0.4 us per launch.  Where wavefronts walk several tiles one after the other the
   // fragments go first and everything is waited for: the earlier start loses there (measured:
@@ -827,7 +849,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     rmask_raw = load8_plain(msrc);
     cnt_raw = load4_plain(p.sel_cnt + pair + vzero);
   };
-  if (MODE == kGather && kEntriesFirst) request_entries();
+  if (MODE == kGather && kOneTile) request_entries();
   bf16x8 qf[8];
   // A retrieving workgroup has barriers ahead anyway: its 32 query rows come in once (16 bytes
   // per thread) and reach the wavefronts' registers through LDS (chunk c of row r at position
@@ -849,13 +871,13 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     if (MODE == kGather) {
       // issued by hand: the fragments are in once at most one tile's loads are outstanding (see
       // below), which the compiler's own bookkeeping would turn into a full wait inside the loop
-      load_query_fragments(qf, qrow);
-    } else {
+      if (computes) load_query_fragments(qf, qrow);
+    } else if (computes) {
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
     }
   }
-  if (MODE == kGather && !kEntriesFirst) request_entries();
+  if (MODE == kGather && !kOneTile) request_entries();
   if (MODE != kGather && p.draft_mask) rmask = p.draft_mask[p.mask_per_batch ? (int64_t)b * p.gamma + qi : qi];
 
   int L = 0;
@@ -869,17 +891,19 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   uint32_t tag = 0;                  // (retrieval only) this call's tag of the key exchange
   if (MODE == kSelect) {
     const Retrieved rt = retrieve_blocks(p, rl, smem, s_sel, &s_exchange_failed, L, pair, split, group, tid, lane, wave, [&]() {
+      if (computes) {
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks)
-        qf[ks] = *reinterpret_cast<const bf16x8*>(q_stage + l32 * kRowBytes + (((2 * ks + g) ^ (l32 & 15)) << 4));
+        for (int ks = 0; ks < 8; ++ks)
+          qf[ks] = *reinterpret_cast<const bf16x8*>(q_stage + l32 * kRowBytes + (((2 * ks + g) ^ (l32 & 15)) << 4));
+      }
     });
     L = rt.L;
     cnt = rt.cnt;
     tag = rt.tag;
     // gather entries of this wavefront's tiles (lane 8u + n: group n of its u-th tile), kept for
     // the loads below; they are written out for the layers that reuse the selection, and the
-    // selection itself, behind the main loop: a store in front of the stream would be one more
-    // thing the stream's first wait has to see acknowledged
+    // selection itself, behind the combination of the wavefronts: a store in front of the stream
+    // would be one more thing the stream's first wait has to see acknowledged
     {
       const int tc = gw + (lane >> 3) * NW - tiles_d;                          // cache tile index
       const int e = tc * 8 + (lane & 7);
@@ -888,7 +912,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     __syncthreads();                 // the last reads of the staged page table and the query rows are done
   } else if (MODE == kGather) {
     // everything requested ahead of the eight query fragments, or everything
-    if (kEntriesFirst) wait_vmcnt<8>(); else wait_vmcnt<0>();
+    if (kOneTile && computes) wait_vmcnt<8>(); else wait_vmcnt<0>();
     front_loads_arrived(gent_raw, rmask_raw, cnt_raw);
     if (gent_wanted) gent = (uint64_t)gent_raw[0] | ((uint64_t)gent_raw[1] << 32);
     if (p.draft_mask) rmask = (uint64_t)rmask_raw[0] | ((uint64_t)rmask_raw[1] << 32);
@@ -921,7 +945,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   // sequence's end) are redirected to the nearest valid row of their group, or, if the whole
   // group is void, to the first draft row (finite, always mapped); they are masked out of the
   // softmax through `valid`.
-  auto issue_tile = [&](int t, int u, unsigned char* dst) -> TileInfo {
+  auto issue_tile = [&](int t, int u, unsigned char* dst, bool skip_void_groups) -> TileInfo {
     TileInfo ti;
     const int n8 = lane & 7;
     const int src0 = __builtin_amdgcn_readfirstlane(8 * u);
@@ -982,6 +1006,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       // rows past the group's last valid row re-read that row
       const uint32_t r = min((uint32_t)lrow, (uint32_t)max(nvn - 1, 0));
       const uint32_t off = r * row_bytes + ((cx ^ (uint32_t)((4 * n) & 15)) << 4);
+      if (skip_void_groups && nvn == 0) continue;        // (wave-uniform)
       __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(kb + off), SVF_LDS_PTR(dst + n * 1024), 16, 0, 2);
       __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(vb + off), SVF_LDS_PTR(vdst + n * 1024), 16, 0, 2);
     }
@@ -1009,22 +1034,23 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   TileInfo cur = {0u, -1}, nxt = {0u, -1};
   int issued = 0;
   if (n_my > 0) {
-    cur = issue_tile(gw, 0, own_x ? x_stage : my_stage);
+    // (draft tile 0 in its own stage: only the groups that hold a draft are fetched)
+    cur = issue_tile(gw, 0, own_x ? x_stage : my_stage, own_x);
     issued = 1;
     if (own_x && n_my > 1) {
-      nxt = issue_tile(gw + NW, 1, my_stage);
+      nxt = issue_tile(gw + NW, 1, my_stage, false);
       issued = 2;
     }
     // The query fragments were requested before the tiles and loads complete in order: with at
     // most one tile's loads outstanding they are in (a second tile may still be in flight).
-    if (MODE == kGather) wait_vmcnt<16>();
+    if (MODE == kGather && computes) wait_vmcnt<16>();
   } else if (MODE == kGather) {
     wait_vmcnt<0>();
   }
-  if (MODE == kGather) query_fragments_arrived(qf);
-  for (int u = 0; u < n_my; ++u) {
+  if (MODE == kGather && computes) query_fragments_arrived(qf);
+  for (int u = 0; computes && u < n_my; ++u) {
     if (u >= issued) {                   // the single stage is free again: fetch the next tile
-      cur = issue_tile(gw + u * NW, u, my_stage);
+      cur = issue_tile(gw + u * NW, u, my_stage, false);
       issued = u + 1;
     }
     // tiles are issued in order, 16 loads each
@@ -1036,17 +1062,31 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     process_tile(stage, qf, allowed, all_visible, p.scale_log2, l32, g, m_run, l_run, oacc);
     cur = nxt;
   }
-
-  if (MODE == kSelect) {
-    // the workgroup with the least other work publishes the selection (s_sel is not a stage)
-    if (split == p.n_splits - 1 && rg == 0) publish_selection(p, s_sel, cnt, pair, tid);
-    const int tc = gw + (lane >> 3) * NW - tiles_d;
-    const int e = tc * 8 + (lane & 7);
-    if (rg == 0 && lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups)
-      p.gather_out[(int64_t)pair * p.gather_groups + e] = gent;
+  if (kOneTile) {
+    // wavefronts 4 .. 7 hand their tile over: once its loads have landed, what the tile holds
+    // goes to LDS, and behind the barrier wavefront w continues with the stage of wavefront w + 4
+    if (!computes) {
+      wait_vmcnt<0>();
+      if (lane == 0) {
+        sm_pair_valid[wave - kSlices] = cur.valid;
+        sm_pair_draft[wave - kSlices] = n_my > 0 ? cur.draft_base : -2;
+      }
+    }
+    __syncthreads();
+    if (computes) {
+      const uint32_t pvalid = sm_pair_valid[wave];
+      const int pdraft = sm_pair_draft[wave];
+      if (pdraft != -2) {
+        uint32_t allowed = pvalid;
+        if (pdraft >= 0) allowed &= (uint32_t)(rmask >> (pdraft & 63));
+        const bool all_visible = pdraft < 0 && pvalid == 0xffffffffu;
+        const uint32_t stage = (uint32_t)(uintptr_t)SVF_LDS_PTR(smem + (wave + kSlices) * kStageBytes);
+        process_tile(stage, qf, allowed, all_visible, p.scale_log2, l32, g, m_run, l_run, oacc);
+      }
+    }
   }
 
-  // ---- combine the eight wavefronts through LDS ------------------------------------------------
+  // ---- combine the computing wavefronts through LDS ---------------------------------------------
   // Wavefront w parks its fp32 output, as it stands (relative to its own running maximum), in
   // its own stage as [32 rows][32 float4], as soon as it is done; float4 chunk c4 of row r sits
   // at position (c4 / 2 + 16 (c4 mod 2)) ^ r (even chunks in one half of the row, odd ones in the
@@ -1054,11 +1094,11 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   // then the odd chunks of a row) off each other's banks.  After the one barrier the readers bring the eight slices to the
   // common maximum while they add them.
   l_run += __shfl_xor(l_run, 32, 64);
-  if (g == 0) {
-    sm_m[wave][l32] = m_run;
-    sm_l[wave][l32] = l_run;
-  }
-  {
+  if (computes) {
+    if (g == 0) {
+      sm_m[wave][l32] = m_run;
+      sm_l[wave][l32] = l_run;
+    }
     float4* mine = reinterpret_cast<float4*>(my_stage);
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -1068,18 +1108,30 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   }
   __syncthreads();
 
+  if (MODE == kSelect) {
+    // The selection and the gather list for the layers that reuse them go out here: a barrier
+    // waits for the acknowledgement of every store issued before it, and the next wait of that
+    // kind is the one the partial's own stores need anyway.  The workgroup with the least other
+    // work publishes the selection (s_sel is not a stage).
+    if (split == p.n_splits - 1 && rg == 0) publish_selection(p, s_sel, cnt, pair, tid);
+    const int tc = gw + (lane >> 3) * NW - tiles_d;
+    const int e = tc * 8 + (lane & 7);
+    if (rg == 0 && lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups)
+      p.gather_out[(int64_t)pair * p.gather_groups + e] = gent;
+  }
+
   // 512 threads: sixteen per row, 8 channels (two float4 chunks) each
   const bool single = p.n_splits == 1;
   const int r = tid >> 4, cg = tid & 15;
   float mw = -INFINITY, lw = 0.f;
-  float fw[kWaves];
+  float fw[kSlices];
 #pragma unroll
-  for (int w = 0; w < kWaves; ++w) {
+  for (int w = 0; w < kSlices; ++w) {
     fw[w] = sm_m[w][r];
     mw = fmaxf(mw, fw[w]);
   }
 #pragma unroll
-  for (int w = 0; w < kWaves; ++w) {
+  for (int w = 0; w < kSlices; ++w) {
     fw[w] = fw[w] == -INFINITY ? 0.f : fast_exp2(fw[w] - mw);      // a slice that saw no token counts nothing
     lw = __builtin_fmaf(sm_l[w][r], fw[w], lw);
   }
@@ -1087,7 +1139,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
 #pragma unroll
   for (int c = 0; c < 8; ++c) racc[c] = 0.f;
 #pragma unroll
-  for (int w = 0; w < kWaves; ++w)
+  for (int w = 0; w < kSlices; ++w)
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
       const float4 t = reinterpret_cast<const float4*>(smem + w * kStageBytes)[r * 32 + ((cg | (c << 4)) ^ r)];
@@ -1601,15 +1653,19 @@ hipError_t launch_verify_attn_mfma(const AttnParams& p, hipStream_t st) {
     return hipGetLastError();
   }
   const dim3 grid((unsigned)(kXcds * p.n_splits), (unsigned)((pairs + kXcds - 1) / kXcds), (unsigned)row_groups);
-  if (p.reps) hipLaunchKernelGGL(verify_attn_mfma_kernel<kSelect>, grid, dim3(kThreads), 0, st, p, pairs);
-  else if (p.gather) {
-    // one tile per wavefront (the owner of draft tile 0 streams a second one beside it)?
-    const int64_t tiles = ((int64_t)p.k_blocks * p.block_size + kTile - 1) / kTile + (p.gamma + kTile - 1) / kTile;
-    if (tiles - 1 <= (int64_t)kWaves * p.n_splits)
-      hipLaunchKernelGGL((verify_attn_mfma_kernel<kGather, true>), grid, dim3(kThreads), 0, st, p, pairs);
-    else
-      hipLaunchKernelGGL((verify_attn_mfma_kernel<kGather, false>), grid, dim3(kThreads), 0, st, p, pairs);
-  } else hipLaunchKernelGGL(verify_attn_mfma_kernel<kResolve>, grid, dim3(kThreads), 0, st, p, pairs);
+  // one tile per wavefront (the owner of draft tile 0 streams a second one beside it)?  The same
+  // answer for the three modes: they have to add up in the same order (same bits).
+  const int64_t tiles = ((int64_t)p.k_blocks * p.block_size + kTile - 1) / kTile + (p.gamma + kTile - 1) / kTile;
+  const bool one_tile = tiles - 1 <= (int64_t)kWaves * p.n_splits;
+#define SVF_LAUNCH_ATTN(MODE)                                                                              \
+  do {                                                                                                     \
+    if (one_tile) hipLaunchKernelGGL((verify_attn_mfma_kernel<MODE, true>), grid, dim3(kThreads), 0, st, p, pairs);  \
+    else hipLaunchKernelGGL((verify_attn_mfma_kernel<MODE, false>), grid, dim3(kThreads), 0, st, p, pairs);          \
+  } while (0)
+  if (p.reps) SVF_LAUNCH_ATTN(kSelect);
+  else if (p.gather) SVF_LAUNCH_ATTN(kGather);
+  else SVF_LAUNCH_ATTN(kResolve);
+#undef SVF_LAUNCH_ATTN
   return hipGetLastError();
 }
 
