@@ -10,7 +10,9 @@
 // common case, and as few instructions as possible in front of the K/V loads: the addresses of
 // a tile are resolved by eight lanes in parallel (one per group of four consecutive tokens,
 // which share a block and a page), moved to scalar registers, and every load is "scalar base +
-// per-lane 32-bit offset" with the per-lane offsets computed once.
+// per-lane 32-bit offset" with the per-lane offsets computed once.  Load instructions count as
+// well as bytes: a compute unit hands the memory pipeline one per ~20 cycles, so what a
+// workgroup requests before its tiles is kept to few instructions.
 //
 // Shape of the work.  For one (sequence, KV head) the gamma x G query rows that share the KV
 // head are packed into M = gamma * G rows (row = draft * G + head-in-group), 32 rows per
@@ -22,7 +24,9 @@
 // Data path.  K and V rows go straight into LDS with 16-byte direct-to-LDS loads (no registers
 // in between), one 16 KB stage per wavefront, private to it: no workgroup barrier in the main
 // loop.  The wavefront that owns draft tile 0 keeps it in a ninth stage, so that its prefix
-// tile streams at the same time.  The 16-byte chunks of a row sit at an XOR-swizzled position
+// tile streams at the same time.  In launches where no wavefront has a second cache tile every
+// wavefront still fetches a tile, but wavefronts 4 .. 7 leave theirs to wavefronts 0 .. 3 (one
+// barrier), which halves what has to be combined afterwards.  The 16-byte chunks of a row sit at an XOR-swizzled position
 // (chosen on the global-address side; the LDS side of such a load is fixed by the lane id),
 // which keeps the fragment reads off each other's banks.  The LDS reads of the main loop are
 // issued by hand (inline ds_read + explicit waits): the compiler would otherwise wait for every
@@ -37,7 +41,7 @@
 // the rescale of O is a per-lane scalar, applied only when the maximum moved by more than
 // kRescaleGap.  P is rounded to bf16 (hardware RNE) for the second product; accumulators fp32.
 //
-// Merge.  The eight wavefronts combine through LDS (log-sum-exp rule).  With one split the
+// Merge.  The computing wavefronts combine through LDS (log-sum-exp rule).  With one split the
 // workgroup writes out / lse itself.  Otherwise it writes a partial (normalised output in bf16,
 // (m, l) in fp32) through to device-coherent memory, and the last workgroup to arrive for that
 // group (atomic ticket) merges all splits in split order.  The ticket also counts arrivals per
