@@ -128,12 +128,20 @@ constexpr int kAccWaves = kAccThreads / 64;
 constexpr int kChunk = 256;                               // tokens per chunk: four per lane
 constexpr int kMaxChunks = 2 * kAccThreads;               // two chunk sums per thread in the scan
 
-__device__ __forceinline__ float wave_inclusive_sum_f(float v, int lane) {
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const float up = __shfl_up(v, o, 64);
-    if (lane >= o) v += up;
-  }
+// Inclusive prefix sum over the 64 lanes with cross-lane operand moves only (no trip through LDS
+// per step): shifts by 1, 2, 4, 8 inside each row of 16 lanes (lanes without a source add zero),
+// then the last lane of row 0 / row 2 into rows 1 / 3, then the last lane of row 1 into rows 2, 3.
+template <int CTRL, int ROW_MASK, bool BOUND>
+__device__ __forceinline__ float lane_move(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xf, BOUND));
+}
+__device__ __forceinline__ float wave_inclusive_sum_f(float v, int /*lane*/) {
+  v += lane_move<0x111, 0xf, true>(v);    // row_shr:1
+  v += lane_move<0x112, 0xf, true>(v);    // row_shr:2
+  v += lane_move<0x114, 0xf, true>(v);    // row_shr:4
+  v += lane_move<0x118, 0xf, true>(v);    // row_shr:8
+  v += lane_move<0x142, 0xa, false>(v);   // row_bcast:15 -> rows 1, 3
+  v += lane_move<0x143, 0xc, false>(v);   // row_bcast:31 -> rows 2, 3
   return v;
 }
 
@@ -200,14 +208,14 @@ __global__ __launch_bounds__(kAccThreads) void accept_kernel(const float* __rest
     if (tid == 0) { sh_chunk = n_chunks - 1; sh_base = 0.f; sh_pick = V - 1; }
     for (int i = tid; i < kMaxChunks; i += kAccThreads) csum[i] = 0.f;
     __syncthreads();
-    // chunk sums, four chunks' loads in flight per wavefront
-    for (int c0 = c_begin; c0 < c_end; c0 += 4) {
-      float4 r[4];
+    // chunk sums, eight chunks' loads in flight per wavefront
+    for (int c0 = c_begin; c0 < c_end; c0 += 8) {
+      float4 r[8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < 8; ++u)
         r[u] = residual4(pt, pd, min(c0 + u, c_end - 1) * kChunk + 4 * lane, V, aligned, from_target);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < 8; ++u) {
         const float incl = wave_inclusive_sum_f(((r[u].x + r[u].y) + r[u].z) + r[u].w, lane);
         if (lane == 63 && c0 + u < c_end) csum[c0 + u] = incl;
       }
