@@ -131,6 +131,19 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w 
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Maximum / sum of the values that lanes l and l ^ 32 hold (a query row's two half-rows): the
+// halves of the wavefront are exchanged by one cross-lane instruction, v_permlane32_swap, which
+// hands back (lower half twice, upper half twice); a shuffle would go through LDS and, with its
+// wait, drain the LDS reads in flight around it.
+__device__ __forceinline__ float halves_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float halves_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // Stores of data exchanged between workgroups: device-scope write-through stores, so making
 // them visible across the chip's L2 slices needs no bulk write-back, only a wait for the
 // stores' acknowledgement.
@@ -272,7 +285,7 @@ __device__ __forceinline__ void process_tile(uint32_t stage, const bf16x8 (&qf)[
   float mx = sacc[0];
 #pragma unroll
   for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sacc[v]);
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
+  mx = halves_max(mx) * scale_log2;
   // keep the old reference while the maximum has not run away from it
   float m_ref = m_run;
   const bool move = mx > m_ref + kRescaleGap;            // always true on a row's first visible tile
@@ -1097,7 +1110,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   // other), which keeps both the row-per-lane writes and the reads (sixteen lanes take the even,
   // then the odd chunks of a row) off each other's banks.  After the one barrier the readers bring the eight slices to the
   // common maximum while they add them.
-  l_run += __shfl_xor(l_run, 32, 64);
+  l_run = halves_sum(l_run);
   if (computes) {
     if (g == 0) {
       sm_m[wave][l32] = m_run;
@@ -1483,7 +1496,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   // at position c ^ (r & 15)) so that they leave in whole 256-byte rows: a lane's registers hold
   // 8-byte pieces of 32 different rows.  Behind the barrier above nobody reads a stage any more
   // and no load is in flight.
-  l_run += __shfl_xor(l_run, 32, 64);
+  l_run = halves_sum(l_run);
   const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
   {
     const int last_st = n_my > 0 ? (n_my - 1) % kRowStages : 0;
