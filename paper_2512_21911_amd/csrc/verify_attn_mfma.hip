@@ -1008,15 +1008,16 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       row_bytes = tok_bytes;
       ti.draft_base = -1;
     }
-    // slot validity: slot s is valid iff (s mod 4) < nv of group s / 4
-    const int nv_s = __shfl(nv, src0 + (l32 >> 2), 64);
-    ti.valid = (uint32_t)__ballot((l32 & 3) < nv_s);
+    // slot validity: slot s is valid iff (s mod 4) < nv of group s / 4 (collected below from the
+    // groups' counts as they pass through scalar registers)
+    uint32_t valid = 0;
     unsigned char* vdst = dst + kTileBytes;
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
       const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)base, src0 + n);
       const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)((uint64_t)base >> 32), src0 + n);
       const int nvn = __builtin_amdgcn_readlane(nv, src0 + n);
+      valid |= ((1u << nvn) - 1u) << (4 * n);
       const bool fd = __builtin_amdgcn_readlane((int)from_draft, src0 + n) != 0;
       const char* kb = reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
       const char* vb = kb + (fd ? dv_d : dv_c);
@@ -1027,6 +1028,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(kb + off), SVF_LDS_PTR(dst + n * 1024), 16, 0, 2);
       __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(vb + off), SVF_LDS_PTR(vdst + n * 1024), 16, 0, 2);
     }
+    ti.valid = valid;
     return ti;
   };
 
