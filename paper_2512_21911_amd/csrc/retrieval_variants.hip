@@ -177,12 +177,7 @@ __global__ __launch_bounds__(kGThreads) void select_global_kernel(VariantParams 
     uint32_t hcount = 0, incl = 0;
     if (tid < 256) {                                     // whole wavefronts
       hcount = hist[255 - tid];
-      incl = hcount;
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t up = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += up;
-      }
+      incl = wave_inclusive_sum(hcount);
       if (lane == 63) wave_eq[wave] = incl;
     }
     __syncthreads();

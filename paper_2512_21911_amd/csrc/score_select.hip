@@ -177,12 +177,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectParams p) {
     {
       const uint32_t need = sh_need;
       const uint32_t hcount = hist[255 - tid];
-      uint32_t incl = hcount;
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t up = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += up;
-      }
+      uint32_t incl = wave_inclusive_sum(hcount);
       if (lane == 63) wave_eq[wave] = incl;
       __syncthreads();
       for (int w = 0; w < wave; ++w) incl += wave_eq[w];

@@ -423,19 +423,6 @@ constexpr int kTableLoads = 8;   // page-table entries a thread stages in LDS (r
 
 constexpr int kMaxSelectBlocks = 1024;   // blocks per sequence the in-kernel retrieval handles
 
-// Inclusive prefix sum over the 64 lanes with cross-lane operand modifiers only: shifts by
-// 1, 2, 4, 8 inside each row of 16 lanes (lanes without a source add zero), then the last lane
-// of row 0 / row 2 into rows 1 / 3, then the last lane of row 1 into rows 2 and 3.
-__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x) {
-  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, true);   // row_shr:1
-  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, true);   // row_shr:2
-  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, true);   // row_shr:4
-  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, true);   // row_shr:8
-  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);  // row_bcast:15 -> rows 1, 3
-  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);  // row_bcast:31 -> rows 2, 3
-  return x;
-}
-
 // Top-cnt of keys[0 .. nb) by the whole workgroup (Sec. 3.1 top-N rule; equal keys: lowest index
 // first).  nb <= kMaxSelectBlocks = 2 * kThreads, so a thread holds keys tid and tid + kThreads.
 // Four 8-bit radix passes find the key of the weakest kept block: LDS histogram (one per pass,
