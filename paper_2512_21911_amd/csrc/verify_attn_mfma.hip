@@ -162,7 +162,28 @@ __device__ __forceinline__ void store_coherent8(void* p, u32x2 bits) {
   __hip_atomic_store(reinterpret_cast<uint64_t*>(p), w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// s_waitcnt vmcnt(n) for an even run-time n in 0 .. 16 (the count is an immediate of the instruction).
+// s_waitcnt vmcnt(n) for an even run-time n in 0 .. 24 (the count is an immediate of the instruction).
+__device__ __forceinline__ void wait_vmcnt_upto24(int n) {
+  switch (n) {
+    case 18: wait_vmcnt<18>(); return;
+    case 20: wait_vmcnt<20>(); return;
+    case 22: wait_vmcnt<22>(); return;
+    case 24: wait_vmcnt<24>(); return;
+    default: break;
+  }
+  switch (n) {
+    case 0: wait_vmcnt<0>(); break;
+    case 2: wait_vmcnt<2>(); break;
+    case 4: wait_vmcnt<4>(); break;
+    case 6: wait_vmcnt<6>(); break;
+    case 8: wait_vmcnt<8>(); break;
+    case 10: wait_vmcnt<10>(); break;
+    case 12: wait_vmcnt<12>(); break;
+    case 14: wait_vmcnt<14>(); break;
+    default: wait_vmcnt<16>(); break;
+  }
+}
+// The same for n in 0 .. 16.
 __device__ __forceinline__ void wait_vmcnt_upto16(int n) {
   switch (n) {
     case 0: wait_vmcnt<0>(); break;
@@ -882,6 +903,26 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     }
   }
   if (MODE == kGather && !kOneTile) request_entries();
+  // The owner of draft tile 0 requests it now, without waiting for its gather entries (the draft
+  // rows need none, and they are the slowest to arrive: a small tensor nothing has touched yet).
+  int early_draft_loads = 0;
+  if (MODE == kGather && kOneTile && gw == 0) {
+    const int er = lane >> 4;
+    const uint32_t ecx = (uint32_t)((lane & 15) ^ er);
+    const uint32_t drow = (uint32_t)p.Hkv * kRowBytes;
+    const char* kd = Kd + (((int64_t)b * p.gamma) * p.Hkv + h) * kRowBytes;
+    const int64_t dvd = Vd - Kd;
+    unsigned char* xs = smem + kWaves * kStageBytes;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      const int nvn = min(max(p.gamma - 4 * n, 0), 4);     // drafts in slots 4n .. 4n + 3 (uniform)
+      if (nvn == 0) continue;
+      const uint32_t off = (uint32_t)(4 * n + min(er, nvn - 1)) * drow + ((ecx ^ (uint32_t)((4 * n) & 15)) << 4);
+      __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(kd + off), SVF_LDS_PTR(xs + n * 1024), 16, 0, 2);
+      __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(kd + dvd + off), SVF_LDS_PTR(xs + kTileBytes + n * 1024), 16, 0, 2);
+      early_draft_loads += 2;
+    }
+  }
   if (MODE != kGather && p.draft_mask) rmask = p.draft_mask[p.mask_per_batch ? (int64_t)b * p.gamma + qi : qi];
 
   int L = 0;
@@ -915,8 +956,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     }
     __syncthreads();                 // the last reads of the staged page table and the query rows are done
   } else if (MODE == kGather) {
-    // everything requested ahead of the eight query fragments, or everything
-    if (kOneTile && computes) wait_vmcnt<8>(); else wait_vmcnt<0>();
+    // everything requested ahead of the eight query fragments (and of an early draft tile), or everything
+    if (kOneTile && computes) wait_vmcnt_upto24(8 + early_draft_loads); else wait_vmcnt<0>();
     front_loads_arrived(gent_raw, rmask_raw, cnt_raw);
     if (gent_wanted) gent = (uint64_t)gent_raw[0] | ((uint64_t)gent_raw[1] << 32);
     if (p.draft_mask) rmask = (uint64_t)rmask_raw[0] | ((uint64_t)rmask_raw[1] << 32);
@@ -1041,7 +1082,12 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   int issued = 0;
   if (n_my > 0) {
     // (draft tile 0 in its own stage: only the groups that hold a draft are fetched)
-    cur = issue_tile(gw, 0, own_x ? x_stage : my_stage, own_x);
+    if (early_draft_loads) {
+      cur.valid = p.gamma >= 32 ? 0xffffffffu : ((1u << p.gamma) - 1u);
+      cur.draft_base = 0;
+    } else {
+      cur = issue_tile(gw, 0, own_x ? x_stage : my_stage, own_x);
+    }
     issued = 1;
     if (own_x && n_my > 1) {
       nxt = issue_tile(gw + NW, 1, my_stage, false);
