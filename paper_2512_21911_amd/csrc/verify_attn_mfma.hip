@@ -903,10 +903,12 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     }
   }
   if (MODE == kGather && !kOneTile) request_entries();
-  // The owner of draft tile 0 requests it now, without waiting for its gather entries (the draft
-  // rows need none, and they are the slowest to arrive: a small tensor nothing has touched yet).
+  // Draft tile 0 into its own stage, by its owner, ahead of everything that depends on the kept
+  // blocks (the draft rows need no gather entry, and they are the slowest to arrive: a small
+  // tensor nothing has touched yet).  Not in a retrieving launch: there every barrier of the
+  // retrieval, and every LDS access the compiler issues, would wait for these loads (+0.3 us).
   int early_draft_loads = 0;
-  if (MODE == kGather && kOneTile && gw == 0) {
+  auto request_draft_tile = [&]() {
     const int er = lane >> 4;
     const uint32_t ecx = (uint32_t)((lane & 15) ^ er);
     const uint32_t drow = (uint32_t)p.Hkv * kRowBytes;
@@ -922,7 +924,9 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(kd + dvd + off), SVF_LDS_PTR(xs + kTileBytes + n * 1024), 16, 0, 2);
       early_draft_loads += 2;
     }
-  }
+  };
+  // (with a gather list: now, without waiting for the entries)
+  if (MODE == kGather && kOneTile && gw == 0) request_draft_tile();
   if (MODE != kGather && p.draft_mask) rmask = p.draft_mask[p.mask_per_batch ? (int64_t)b * p.gamma + qi : qi];
 
   int L = 0;
