@@ -926,7 +926,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     }
   };
   // (with a gather list: now, without waiting for the entries)
-  if (MODE == kGather && kOneTile && gw == 0) request_draft_tile();
+  if (MODE == kGather && gw == 0) request_draft_tile();
   if (MODE != kGather && p.draft_mask) rmask = p.draft_mask[p.mask_per_batch ? (int64_t)b * p.gamma + qi : qi];
 
   int L = 0;
@@ -961,7 +961,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     __syncthreads();                 // the last reads of the staged page table and the query rows are done
   } else if (MODE == kGather) {
     // everything requested ahead of the eight query fragments (and of an early draft tile), or everything
-    if (kOneTile && computes) wait_vmcnt_upto24(8 + early_draft_loads); else wait_vmcnt<0>();
+    if (kOneTile && computes) wait_vmcnt_upto24(8 + early_draft_loads); else wait_vmcnt_upto24(early_draft_loads);
     front_loads_arrived(gent_raw, rmask_raw, cnt_raw);
     if (gent_wanted) gent = (uint64_t)gent_raw[0] | ((uint64_t)gent_raw[1] << 32);
     if (p.draft_mask) rmask = (uint64_t)rmask_raw[0] | ((uint64_t)rmask_raw[1] << 32);
