@@ -904,8 +904,9 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   }
   if (MODE == kGather && !kOneTile) request_entries();
   // Draft tile 0 into its own stage, by its owner, ahead of everything that depends on the kept
-  // blocks (the draft rows need no gather entry, and they are measured to arrive last).  Not in a retrieving launch: there every barrier of the
-  // retrieval, and every LDS access the compiler issues, would wait for these loads (+0.3 us).
+  // blocks (the draft rows need no gather entry, and they are measured to arrive last).  Not in
+  // a retrieving launch: there every barrier of the retrieval, and every LDS access the compiler
+  // issues, would wait for these loads (+0.3 us).
   int early_draft_loads = 0;
   auto request_draft_tile = [&]() {
     const int er = lane >> 4;
