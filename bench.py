@@ -52,7 +52,7 @@ def parse():
                          "instead of the configuration's drafts, over the same cache")
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-layers", type=int, default=16, help="layers the CPU oracle is timed on")
+    ap.add_argument("--cpu-layers", type=int, default=32, help="layers the CPU oracle is timed on")
     ap.add_argument("--profile-only", default="", help="run only this many steps of the timed loop (for rocprofv3)")
     ap.add_argument("--analytics", action="store_true",
                     help="time the retrieval analytics (per-draft block sets, overlap, Jaccard) instead of the step")
