@@ -120,6 +120,9 @@ EDGE = {
     "f32_d64_paged": small(dtype="f32", d=64, min_len=64),
     "gqa8": small(Hq=16, Hkv=2, gamma=6),
     "mha": small(Hq=4, Hkv=4, gamma=3),
+    # two draft tiles (more than 32 drafts) in the one-row-group-per-workgroup kernel
+    "mha_gamma40": small(Hq=2, Hkv=2, gamma=40),
+    "mha_gamma33_tree": small(Hq=2, Hkv=2, gamma=33, tree_depth=5, B=3, min_len=300),
     "short_seq": small(T=40, page_size=8, block_size=16, k_blocks=2),
     # the anchor kernel's own retrieval: sixteen query heads per KV head (more than one batch of
     # head loads), a second selection key per thread (more than 512 blocks), a page table too long
