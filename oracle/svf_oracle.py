@@ -14,7 +14,11 @@ What each function follows:
   first_query           Sec. 2.2: the first draft token drives retrieval; with grouped
                         query heads the queries sharing a KV head are averaged.
   block_scores          Eq. 5 with the mean taken first (equal by linearity).
-  block_scores_literal  Eq. 5 as printed: mean over the block of q0 . k.
+  block_scores_literal  Eq. 5 term by term: sum over the block of q0 . k, divided by the
+                        block's token count (the reading taken) or by B (as printed).
+  near_tie_blocks       which blocks a selection may differ in without being wrong
+                        (scores within a relative gap of the weakest block kept for
+                        its score; forced first/last blocks excluded).
   select_blocks         Sec. 3.1: top-N scores, first/last blocks never evicted; one
                         set per (batch, KV head) shared by all draft tokens (Sec. 2.2).
   verify_attn           Sec. 3.1/3.3: the draft tokens attend to the selected blocks
@@ -27,7 +31,8 @@ What each function follows:
 Readings taken where the paper is silent are listed in the design notes of the
 repository (partial last block divides by its real token count; ties go to the
 lowest block index; forced blocks count inside the budget; scores are unscaled;
-softmax scale defaults to 1/sqrt(d)).
+softmax scale defaults to 1/sqrt(d); a query row with no visible key gets a zero
+output and lse = -inf).
 
 Pinned by tests/test_oracle_pins.py against: an independent loop-level brute force,
 torch's scaled_dot_product_attention in fp64, closed forms (Eq. 5 linearity, Eq. 6
@@ -125,8 +130,15 @@ def block_scores(q, reps: np.ndarray) -> np.ndarray:
     return np.einsum("bhd,bhjd->bhj", q0, _f64(reps))
 
 
-def block_scores_literal(q, k_pool, block_table, seq_lens, block_size: int) -> np.ndarray:
-    """Eq. 5 as printed: average over the block's keys of q0bar . k (no cached mean)."""
+def block_scores_literal(q, k_pool, block_table, seq_lens, block_size: int, divisor: str = "count") -> np.ndarray:
+    """Eq. 5 term by term: the sum over the block's keys of q0bar . k, divided (no cached mean).
+
+    divisor = "count": by the number of tokens the block holds (the reading this build takes for
+    a partial last block); divisor = "block_size": by B as Eq. 5 prints it.  The two differ only
+    in a sequence's last block when it is partial, by the factor n_j / B.
+    """
+    if divisor not in ("count", "block_size"):
+        raise ValueError("divisor must be 'count' or 'block_size'")
     cache = PagedCache(k_pool, block_table)
     lens = _ints(seq_lens)
     q0 = first_query(q, cache.Hkv)
@@ -138,7 +150,7 @@ def block_scores_literal(q, k_pool, block_table, seq_lens, block_size: int) -> n
             keys = cache.tokens(b, t0, t1)
             for h in range(cache.Hkv):
                 dots = keys[:, h, :] @ q0[b, h]
-                s[b, h, j] = dots.sum() / (t1 - t0)
+                s[b, h, j] = dots.sum() / ((t1 - t0) if divisor == "count" else block_size)
     return s
 
 
@@ -173,18 +185,23 @@ def select_blocks(scores: np.ndarray, seq_lens, block_size: int, k_blocks: int,
     return sel_idx, sel_cnt
 
 
-def near_tie_blocks(scores_bh: np.ndarray, nb: int, chosen: Sequence[int], rel_gap: float = 1e-3) -> List[int]:
-    """Blocks of one (b, h) whose score lies within rel_gap of the weakest chosen score.
+def near_tie_blocks(scores_bh: np.ndarray, nb: int, chosen: Sequence[int], rel_gap: float = 1e-3,
+                    n_sink: int = 0, n_local: int = 0) -> List[int]:
+    """Blocks of one (b, h) whose score lies within rel_gap of the weakest block kept for its score.
 
-    A selection that differs from the oracle's only inside this set is a near-tie,
-    not an error; tests count and report such cases.
+    The first n_sink and last n_local blocks are kept whatever they score (Sec. 3.1), so they
+    neither set the threshold nor can they be near-ties: the threshold is the lowest score among
+    the chosen blocks outside those two ranges, and only blocks outside them are returned.  A
+    selection that differs from the oracle's only inside this set is a near-tie, not an error;
+    tests count and report such cases.
     """
-    chosen = [int(c) for c in chosen if c >= 0]
-    if not chosen:
+    free = lambda j: n_sink <= j < nb - n_local
+    kept = [int(c) for c in chosen if c >= 0 and free(int(c))]
+    if not kept:
         return []
-    s_k = min(float(scores_bh[j]) for j in chosen)
+    s_k = min(float(scores_bh[j]) for j in kept)
     tol = rel_gap * max(abs(s_k), 1e-30)
-    return [j for j in range(nb) if abs(float(scores_bh[j]) - s_k) <= tol]
+    return [j for j in range(nb) if free(j) and abs(float(scores_bh[j]) - s_k) <= tol]
 
 
 # --------------------------------------------------------------------------- attention
@@ -246,6 +263,14 @@ def _attend(q, k_cache: PagedCache, v_cache: PagedCache, seq_lens, k_draft, v_dr
                     j = h * G + g
                     logit = scale * (keys @ q[b, i, j])
                     logit = np.where(vis, logit, -np.inf)
+                    if not vis.any():
+                        # no key is visible (no kept block and a draft mask without the row's own
+                        # bit): the paper defines nothing here; reading: zero output, lse = -inf
+                        out[b, i, j] = 0.0
+                        lse[b, i, j] = -np.inf
+                        if return_weights:
+                            weights[(b, i, j)] = (list(toks), np.zeros(len(vis)))
+                        continue
                     m = logit.max()
                     p = np.exp(logit - m)
                     z = p.sum()

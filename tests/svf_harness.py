@@ -118,7 +118,7 @@ def check_selection(cfg, x, scores_ref, idx_gpu, cnt_gpu, n_sink=0, n_local=0, k
             assert g.min() >= 0 and g.max() < nb
             if (g == idx_ref[b, h, :c]).all():
                 continue
-            ties = set(O.near_tie_blocks(scores_ref[b, h], nb, idx_ref[b, h, :c], TIE_GAP))
+            ties = set(O.near_tie_blocks(scores_ref[b, h], nb, idx_ref[b, h, :c], TIE_GAP, n_sink, n_local))
             diff = set(g.tolist()) ^ set(idx_ref[b, h, :c].tolist())
             assert diff <= ties, f"selection mismatch at (b={b}, h={h}): {sorted(diff)} not near-ties"
             near += len(diff)

@@ -95,7 +95,7 @@ def test_per_draft_retrieval_overlap_and_similarity(name):
                 diff = set(np.flatnonzero(mg[b, h, i] ^ m_ref[b, h, i]).tolist())
                 if diff:
                     chosen = np.flatnonzero(m_ref[b, h, i]).tolist()
-                    ties = set(O.near_tie_blocks(s_ref[b, i, h], nb, chosen, TIE_GAP))
+                    ties = set(O.near_tie_blocks(s_ref[b, i, h], nb, chosen, TIE_GAP, cfg.n_sink, cfg.n_local))
                     assert diff <= ties, f"mask mismatch at (b={b}, h={h}, draft={i}): {sorted(diff)}"
                     near += len(diff)
     print(f"[{name}] per-draft near-ties excused: {near}")

@@ -253,6 +253,24 @@ def test_eq5_linearity_and_ragged_divisor():
     assert abs(s_mean[0, 1, 2] - hand) < 1e-13
 
 
+def test_eq5_printed_divisor_differs_only_in_a_partial_last_block():
+    # Eq. 5 prints 1/B; the reading taken divides by the block's real token count.  The two agree
+    # on every full block and differ by exactly n_j / B on a partial last block.
+    x = tiny_inputs(13, 2, 4, 2, 8, 24, 4, 2, 0, [24, 22])
+    s_cnt = O.block_scores_literal(x["q"], x["kp"], None, x["lens"], 4, divisor="count")
+    s_B = O.block_scores_literal(x["q"], x["kp"], None, x["lens"], 4, divisor="block_size")
+    np.testing.assert_allclose(s_cnt[0], s_B[0], rtol=0, atol=0)                 # 24 = 6 full blocks
+    np.testing.assert_allclose(s_cnt[1, :, :5], s_B[1, :, :5], rtol=0, atol=0)
+    np.testing.assert_allclose(s_B[1, :, 5], s_cnt[1, :, 5] * (2 / 4), rtol=1e-15)   # 2 tokens of 4
+    assert np.abs(s_B[1, :, 5] - s_cnt[1, :, 5]).min() > 1e-6
+    # by hand, the printed form on the partial block
+    q0 = (x["q"][1, 0, 0] + x["q"][1, 0, 1]) / 2
+    hand = (float(q0 @ x["K"][1, 20, 0]) + float(q0 @ x["K"][1, 21, 0])) / 4
+    assert abs(s_B[1, 0, 5] - hand) < 1e-13
+    with pytest.raises(ValueError):
+        O.block_scores_literal(x["q"], x["kp"], None, x["lens"], 4, divisor="B")
+
+
 def test_selection_invariant_to_query_scale():
     x = tiny_inputs(13, 1, 4, 2, 8, 64, 4, 2)
     reps = O.block_reps(x["kp"], None, x["lens"], 4)
@@ -284,6 +302,54 @@ def test_select_ties_sink_local_and_padding():
     assert list(idx[0, 0]) == [1, 2]
     with pytest.raises(ValueError):
         O.select_blocks(s, [40], 4, 2, n_sink=2, n_local=1)
+
+
+def test_near_tie_blocks_threshold_ignores_forced_blocks():
+    # hand-worked: k = 4 with one sink block.  Block 0 is kept because it is first, not for its
+    # score (-5); the blocks kept for their score are 1, 2, 3 (3, 2, 1), so the cut is at 1.0 and
+    # the only other block within 1e-3 of it is block 4 (0.9995).  Block 5 (-5.003) is within 1e-3
+    # of the sink block's score and must NOT be excused.
+    s = np.array([-5.0, 3.0, 2.0, 1.0, 0.9995, -5.003, 0.5, -1.0])
+    idx, cnt = O.select_blocks(s.reshape(1, 1, -1), [32], 4, 4, n_sink=1)
+    assert list(idx[0, 0]) == [0, 1, 2, 3] and cnt[0, 0] == 4
+    assert O.near_tie_blocks(s, 8, idx[0, 0], 1e-3, n_sink=1) == [3, 4]
+    # the same scores without forced blocks: kept 1, 2, 3, 4; the cut is 0.9995, block 3 ties with it
+    idx, cnt = O.select_blocks(s.reshape(1, 1, -1), [32], 4, 4)
+    assert list(idx[0, 0]) == [1, 2, 3, 4]
+    assert O.near_tie_blocks(s, 8, idx[0, 0], 1e-3) == [3, 4]
+    # a tighter gap excuses nothing but the cut itself
+    assert O.near_tie_blocks(s, 8, idx[0, 0], 1e-5) == [4]
+    # local blocks: the last block is forced and scores far below the cut
+    s2 = np.array([4.0, 1.0, 1.0004, 7.0, 0.2, -9.0])
+    idx, cnt = O.select_blocks(s2.reshape(1, 1, -1), [24], 4, 4, n_local=1)
+    assert list(idx[0, 0]) == [0, 2, 3, 5]
+    assert O.near_tie_blocks(s2, 6, idx[0, 0], 1e-3, n_local=1) == [1, 2]
+    # a forced block never counts as a near-tie, even when its score sits on the cut
+    s3 = np.array([1.0, 3.0, 2.0, 1.0, 0.0])
+    idx, cnt = O.select_blocks(s3.reshape(1, 1, -1), [20], 4, 4, n_sink=1)
+    assert list(idx[0, 0]) == [0, 1, 2, 3]
+    assert O.near_tie_blocks(s3, 5, idx[0, 0], 1e-3, n_sink=1) == [3]
+    # only forced blocks kept: there is no cut, nothing is excused; padding (-1) is ignored
+    assert O.near_tie_blocks(s3, 5, [0, 4, -1], 1e-3, n_sink=1, n_local=1) == []
+    # relative to |s_k|: a cut at -200 excuses a gap of 0.2
+    s4 = np.array([-100.0, -200.0, -200.15, -200.3])
+    assert O.near_tie_blocks(s4, 4, [0, 1], 1e-3) == [1, 2]
+
+
+def test_row_without_a_visible_key_is_zero():
+    # a sequence without prefix tokens and a draft mask that lacks the row's own bit: nothing to
+    # attend to.  Reading: zero output, lse = -inf; the other rows are ordinary softmax rows.
+    x = tiny_inputs(21, 1, 2, 1, 4, 8, 4, 2, 0, [0])
+    mask = np.array([0b00, 0b11], dtype=np.uint64)           # draft 0 sees nothing, draft 1 sees both
+    idx = np.full((1, 1, 2), -1, dtype=np.int32)
+    cnt = np.zeros((1, 1), dtype=np.int32)
+    out, lse, w = O.verify_attn(x["q"], x["kp"], x["vp"], None, x["lens"], x["kd"], x["vd"], mask, idx, cnt, 4,
+                                return_weights=True)
+    assert np.all(out[0, 0] == 0.0) and np.all(np.isneginf(lse[0, 0]))
+    assert np.all(np.isfinite(out[0, 1])) and np.all(np.isfinite(lse[0, 1]))
+    for j in range(2):
+        assert abs(w[(0, 1, j)][1].sum() - 1.0) < 1e-12
+        assert w[(0, 0, j)][1].sum() == 0.0
 
 
 def test_planted_blocks_are_selected():
