@@ -25,9 +25,26 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
-# HBM bytes per reuse-layer attention launch from rocprofv3 (FETCH_SIZE x 1.9997 + WRITE_SIZE, KiB
-# per dispatch, scaled by a 256 MiB copy kernel): profiles/verify_attn_cfg3_hbm_traffic.md
-MEASURED_TRAFFIC_BYTES = {"cfg3_long_batch_32k": 38.8e6}
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "verify_attn_cfg3_hbm_traffic.md")
+KERNEL_SOURCE = os.path.join(ROOT, "paper_2512_21911_amd", "csrc", "verify_attn_mfma.hip")
+
+
+def measured_traffic(workload):
+    """HBM bytes per reuse-layer attention launch from the rocprofv3 counter runs (FETCH_SIZE and
+    WRITE_SIZE, scaled by a copy of known size), as recorded in the profile summary.  The summary
+    carries the SHA-256 of the kernel source it was taken on; for any other source the figure is
+    stale and None is reported."""
+    import hashlib
+    import re
+    try:
+        text = open(TRAFFIC_SUMMARY).read()
+        sha = hashlib.sha256(open(KERNEL_SOURCE, "rb").read()).hexdigest()
+    except OSError:
+        return None
+    m = re.search(r"traffic_bytes_per_launch\[(\w+)\]\s*=\s*(\d+)\s+kernel_source_sha256\s*=\s*([0-9a-f]{64})", text)
+    if not m or m.group(1) != workload or m.group(3) != sha:
+        return None
+    return int(m.group(2))
 
 
 def step_mode(cfg, layer):
@@ -659,6 +676,20 @@ def main():
         return
 
     ms_step = timed(run_step, args.steps, args.warmup)
+
+    def per_replay(run, iters):
+        """Each replay between its own pair of events (all enqueued back to back, one sync at the
+        end): median / min / 90th percentile of a step in us."""
+        evs = [ev() for _ in range(iters + 1)]
+        evs[0].record()
+        for i in range(iters):
+            run()
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        t = sorted(evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(iters))
+        return {"median": round(t[len(t) // 2], 2), "min": round(t[0], 2), "p90": round(t[min(len(t) - 1, (9 * len(t)) // 10)], 2)}
+
+    step_stats = per_replay(run_step, args.steps)
     run_attn = make_runner(attn_only)
     ms_attn = timed(run_attn, args.steps, args.warmup)
     run_anchor = make_runner(anchor_only)
@@ -666,6 +697,23 @@ def main():
     run_sel = make_runner(select_only)
     ms_sel = timed(run_sel, args.steps, args.warmup)
     ms_step_eager = timed(step, max(3, args.steps // 5), 2)
+
+    # What a plain device-to-device copy reaches when one launch moves as many bytes as one attention
+    # launch has to (half read, half written), launches back to back on buffers that are not in cache:
+    # the measured streaming ceiling for a problem of this size, beside the published peak.
+    half = max(1 << 20, bytes_["verify_attn"] // 2 // 256 * 256)
+    n_cp = max(8, min(64, (1 << 30) // (2 * half)))           # >= 1 GiB touched between reuses of a buffer
+    srcs = [torch.empty(half, dtype=torch.uint8, device=dev) for _ in range(n_cp)]
+    dsts = [torch.empty(half, dtype=torch.uint8, device=dev) for _ in range(n_cp)]
+
+    def copies():
+        for a_, b_ in zip(srcs, dsts):
+            b_.copy_(a_)
+
+    ms_copy = timed(make_runner(copies), max(3, args.steps // 2), 2)
+    copy_us = ms_copy * 1e3 / n_cp
+    copy_gbps = 2 * half / (copy_us * 1e-6) / 1e9
+    del srcs, dsts
 
     n_anchor = sum(1 for l in range(n_layers) if cfg.is_anchor(l))
     attn_us = ms_attn * 1e3 / n_layers                        # average duration of one attention launch
@@ -676,6 +724,7 @@ def main():
 
     # ---- sampled check against the oracle + CPU baseline (rank 0, N = 1) ------------------
     cpu_baseline = None
+    near_ties = None
     if not args.no_cpu_baseline:
         from oracle import svf_oracle as O
         import numpy as np
@@ -684,6 +733,7 @@ def main():
         cpu_t = 0.0
         idx = cnt = None
         worst = 0.0
+        near_ties = 0
         gi, gc = torch.empty_like(sel_idx), torch.empty_like(sel_cnt)
         run_step()
         torch.cuda.synchronize()
@@ -712,7 +762,22 @@ def main():
                               xg["seq_lens"], xg["k_draft"], xg["v_draft"], xg["draft_mask"], gi, gc, o, ws)
             torch.cuda.synchronize()
             if cfg.is_anchor(l) and not np.array_equal(gi.cpu().numpy(), idx):
-                raise SystemExit("bench: GPU block selection differs from the oracle on the sampled layer")
+                # blocks may differ only where the oracle's score is within 1e-3 (relative) of the
+                # weakest block kept for its score; such near-ties are counted and reported
+                gi_h, lens_h = gi.cpu().numpy(), x["seq_lens"].tolist()
+                for b in range(cfg.B):
+                    nb_b = -(-int(lens_h[b]) // cfg.block_size)
+                    for h in range(cfg.Hkv):
+                        c = int(cnt[b, h])
+                        diff = set(gi_h[b, h, :c].tolist()) ^ set(idx[b, h, :c].tolist())
+                        if not diff <= set(O.near_tie_blocks(s[b, h], nb_b, idx[b, h, :c], 1e-3, cfg.n_sink, cfg.n_local)):
+                            raise SystemExit("bench: GPU block selection differs from the oracle on the sampled "
+                                             f"layer {l} beyond near-ties (sequence {b}, KV head {h}: {sorted(diff)})")
+                        near_ties += len(diff)
+                # this layer and the reuse layers behind it are checked on the blocks the GPU kept
+                idx, cnt = gi_h.copy(), gc.cpu().numpy().copy()
+                out_ref, _ = O.verify_attn(x["q"], x["k_pool"], x["v_pool"], x["block_table"], x["seq_lens"],
+                                           x["k_draft"], x["v_draft"], x["draft_mask"], idx, cnt, cfg.block_size)
             worst = max(worst, float(np.abs(o.double().cpu().numpy() - out_ref).max()))
             del xg, x
         tol = 2e-2 if cfg.dtype == "bf16" else 1e-4
@@ -720,9 +785,12 @@ def main():
             raise SystemExit(f"bench: sampled parity check failed: max-abs {worst:.3e} > {tol}")
         cpu_us_step = wall / n_cpu * n_layers * 1e6
         cpu_baseline = {"value": round(cpu_us_step, 1), "unit": "us/step",
-                        "cores": max(1, int(round(cpu_t / max(wall, 1e-9)))), "kind": "oracle",
-                        "sample": f"oracle select+attention timed on layers 0..{n_cpu - 1} of {n_layers} "
-                                  f"({wall:.2f} s wall), scaled to {n_layers} layers; max-abs vs GPU {worst:.2e}"}
+                        "cores": os.cpu_count(), "kind": "oracle",
+                        "sample": f"fp64 numpy oracle (interpreted loops over sequences and KV heads around BLAS "
+                                  f"calls, not a tuned CPU kernel): select+attention timed on layers 0..{n_cpu - 1} "
+                                  f"of {n_layers} ({wall:.2f} s wall, {cpu_t / max(wall, 1e-9):.1f} threads busy on "
+                                  f"average of the {os.cpu_count()} host cores), scaled to {n_layers} layers; "
+                                  f"max-abs vs GPU {worst:.2e}; near-tie blocks excused {near_ties}"}
 
     value_us = ms_step * 1e3
     if cfg.dtype != "bf16" or cfg.d != 128:
@@ -752,11 +820,18 @@ def main():
                    "launch": "stream" if args.no_graph else "hipgraph"},
         "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if n_layers == cfg.n_layers and not args.hnd else None,
+                     "traffic": measured_traffic(cfg.name) if n_layers == cfg.n_layers and not args.hnd and not args.tree else None,
                      "algorithmic_bytes_per_launch": bytes_["verify_attn"],
-                     "avg_launch_us": round(attn_us, 3)},
+                     "avg_launch_us": round(attn_us, 3),
+                     # against a plain device copy that moves the same bytes per launch, timed above
+                     "stream_ceiling_GBps": round(copy_gbps, 1),
+                     "frac_of_stream_ceiling": round(attn_gbps / copy_gbps, 4)},
         "cpu_baseline": cpu_baseline,
         "extra": {"step_GBps": round(step_bytes / (value_us * 1e-6) / 1e9, 1),
+                  "step_us_median": step_stats["median"], "step_us_min": step_stats["min"],
+                  "step_us_p90": step_stats["p90"],
+                  "near_ties": near_ties,
+                  "copy_same_bytes_us_per_launch": round(copy_us, 3),
                   "step_us_stream_launches": round(ms_step_eager * 1e3, 2),
                   "anchor_layer_us": round(anchor_us, 3),
                   "anchor_layer_GBps": round((bytes_["verify_attn"] + bytes_["score_select"]) / (anchor_us * 1e-6) / 1e9, 1),

@@ -54,7 +54,8 @@ enum {
   SVF_ERR_DTYPE = -3,     /* dtype not SVF_F32 / SVF_BF16                                  */
   SVF_ERR_PAGING = -4,    /* page_size and block_size not multiples of one another, or
                              max_pages_per_seq too small for max_seq_len                   */
-  SVF_ERR_BUDGET = -5,    /* k_blocks < 1, or n_sink + n_local > k_blocks                  */
+  SVF_ERR_BUDGET = -5,    /* k_blocks < 1, n_sink + n_local > k_blocks, or more than 2^23
+                             tokens kept per (sequence, KV head)                           */
   SVF_ERR_WORKSPACE = -6, /* workspace NULL, misaligned (256 B) or smaller than required   */
   SVF_ERR_HIP = -7        /* the HIP runtime refused a launch                              */
 };
@@ -104,6 +105,19 @@ size_t svf_workspace_bytes(const svf_shape_t* shape);
 
 /* Enqueue the one-time clearing of a workspace (a fill kernel; safe under graph capture). */
 int svf_workspace_init(void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Tuning / test knob, carried by the workspace (the library keeps no state of its own).  The
+ * workgroups that share one (sequence, KV head, row group) wait for each other in two places: on
+ * anchor layers each scores a share of the blocks and waits for the others' keys, and every
+ * workgroup merges a slice of the rows once the others' partial results have landed.  Both waits
+ * are bounded by `polls` (default 64); a workgroup that runs out of patience scores all blocks
+ * itself, respectively leaves its slice to the workgroup that arrives last.  The results are the
+ * same bits whatever the number.  0 <= polls <= 4096 (0: never wait), -1 restores the default;
+ * anything else SVF_ERR_SHAPE.  Enqueued on `stream` (a small fill kernel); svf_workspace_init
+ * also restores the default.
+ */
+int svf_workspace_set_wait_polls(const svf_shape_t* shape, void* ws, size_t ws_bytes, int polls, void* stream);
 
 /*
  * Block representatives (Sec. 3.1: the cache is partitioned per KV head into blocks of
@@ -161,15 +175,6 @@ int svf_verify_attn(const svf_shape_t* shape, const void* q, const void* K, cons
  *   sizes that are multiples of four, or more than 1024 kept blocks) take the SVF_STEP_REUSE path.
  * Any other mode: SVF_ERR_SHAPE.
  */
-/*
- * Tuning / test knob of the retrieving attention kernel (SVF_STEP_ANCHOR, shapes with a gather
- * list): the workgroups of one (sequence, KV head, row group) each score a share of the blocks
- * and wait for the others' keys; `polls` bounds that wait (default 64), after which a workgroup
- * scores all blocks itself.  0 switches the exchange off.  The result is the same bits either
- * way.  Process-wide, takes effect at the next call; 0 <= polls <= 4096, else SVF_ERR_SHAPE.
- */
-int svf_set_exchange_polls(int polls);
-
 #define SVF_STEP_REUSE 0
 #define SVF_STEP_ANCHOR 1
 #define SVF_STEP_REUSE_GATHER 2

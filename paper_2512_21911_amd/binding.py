@@ -62,7 +62,7 @@ class SvfError(RuntimeError):
 _lib = None
 
 EXPORTS = ["svf_version", "svf_strerror", "svf_budget_blocks", "svf_workspace_bytes", "svf_workspace_init",
-           "svf_block_reps", "svf_score_select", "svf_verify_attn", "svf_verify_step", "svf_set_exchange_polls",
+           "svf_block_reps", "svf_score_select", "svf_verify_attn", "svf_verify_step", "svf_workspace_set_wait_polls",
            "svf_mask_words", "svf_analytics_workspace_bytes", "svf_select_per_draft", "svf_masks_from_selection",
            "svf_overlap_by_distance", "svf_jaccard_adjacent", "svf_topk_anchors",
            "svf_block_summaries", "svf_retrieve", "svf_ffn_workspace_bytes", "svf_sparse_ffn",
@@ -80,8 +80,8 @@ def lib() -> ctypes.CDLL:
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
         shp = ctypes.POINTER(SvfShape)
         L.svf_version.restype = ctypes.c_int
-        L.svf_set_exchange_polls.restype = ctypes.c_int
-        L.svf_set_exchange_polls.argtypes = [ctypes.c_int]
+        L.svf_workspace_set_wait_polls.restype = ctypes.c_int
+        L.svf_workspace_set_wait_polls.argtypes = [shp, vp, ctypes.c_size_t, ctypes.c_int, vp]
         L.svf_mask_words.restype = i32
         L.svf_mask_words.argtypes = [shp]
         L.svf_analytics_workspace_bytes.restype = ctypes.c_size_t
@@ -216,8 +216,9 @@ def svf_verify_attn(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, dra
 SVF_STEP_REUSE, SVF_STEP_ANCHOR, SVF_STEP_REUSE_GATHER = 0, 1, 2
 
 
-def svf_set_exchange_polls(polls):
-    _check(lib().svf_set_exchange_polls(int(polls)), "svf_set_exchange_polls")
+def svf_workspace_set_wait_polls(shape, ws, polls):
+    _check(lib().svf_workspace_set_wait_polls(ctypes.byref(shape), _ptr(ws), ws.numel(), int(polls), _stream()),
+           "svf_workspace_set_wait_polls")
 
 
 def svf_verify_step(shape, mode, q, reps, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask,

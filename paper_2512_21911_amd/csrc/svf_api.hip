@@ -3,7 +3,6 @@
 #include <math.h>
 #include <string.h>
 
-#include <atomic>
 #include <vector>
 
 #include "svf_device.h"
@@ -45,7 +44,9 @@ int check_shape(const svf_shape_t* s) {
   }
   if (s->k_blocks < 1 || s->n_sink < 0 || s->n_local < 0 ||
       (int64_t)s->n_sink + s->n_local > s->k_blocks) return SVF_ERR_BUDGET;
-  if ((int64_t)s->k_blocks * s->block_size > (int64_t)1 << 30) return SVF_ERR_BUDGET;
+  // (also keeps the number of splits per group, at most one per 8 tiles of 32 tokens, below 2^16:
+  // the arrival counters of the attention kernels are 16 bits wide)
+  if ((int64_t)s->k_blocks * s->block_size > (int64_t)1 << 23) return SVF_ERR_BUDGET;
   return SVF_OK;
 }
 
@@ -82,7 +83,8 @@ int hip_code(hipError_t e) { return e == hipSuccess ? SVF_OK : SVF_ERR_HIP; }
 
 }  // namespace
 
-// Workspace layout: [tickets | partial o | partial m | partial l | gather list | scores]
+// Workspace layout: [tickets | partial o | partial m, l / records | gather list | exchanged keys | epoch words],
+// then (svf_workspace_bytes) the block scores of a selection whose caller does not ask for them
 AttnPlan plan_attn(const svf_shape_t& s) {
   AttnPlan pl;
   const int G = s.Hq / s.Hkv;
@@ -100,32 +102,40 @@ AttnPlan plan_attn(const svf_shape_t& s) {
     pl.n_splits = (int)want;
   }
   const size_t pairs = (size_t)s.B * s.Hkv;
+  pl.groups = pairs * (pl.Mpad / 32);
+  pl.slice_rows = (32 + (pl.n_splits < 16 ? pl.n_splits : 16) - 1) / (pl.n_splits < 16 ? pl.n_splits : 16);
   size_t off = 0;
   pl.off_tickets = off;
-  off += align_up(pairs * (pl.Mpad / 32) * sizeof(uint64_t));   // one ticket per (pair, row group)
+  off += align_up(pl.groups * kTicketWords * sizeof(uint64_t));
+  // partial outputs: fp32 (vector-ALU kernel) or bf16 (matrix-core kernels) per split and row
   pl.off_o = off;
-  off += align_up(pairs * pl.n_splits * pl.Mpad * s.d * sizeof(float));
-  // maxima and denominators: two arrays for the vector-ALU kernel, one interleaved (m, l) array
-  // for the matrix-core kernel; same bytes either way
+  off += align_up(pairs * pl.n_splits * pl.Mpad * s.d * (pl.mfma ? sizeof(uint16_t) : sizeof(float)));
+  // maxima and denominators: two fp32 arrays for the vector-ALU kernel; 16 bytes per split and row
+  // for the matrix-core kernels (a tagged record, or an (m, l) pair in the many-rows kernel)
   pl.off_m = off;
   pl.off_l = off + pairs * pl.n_splits * pl.Mpad * sizeof(float);
-  off += align_up(2 * pairs * pl.n_splits * pl.Mpad * sizeof(float));
+  off += align_up((pl.mfma ? 4 : 2) * pairs * pl.n_splits * pl.Mpad * sizeof(float));
   pl.gather = pl.mfma && s.k_blocks <= kMaxGatherBlocks;
   pl.fused_select = pl.gather && nb_max_of(s) <= kMaxGatherBlocks;
   pl.gather_groups = pl.gather ? (int32_t)(((int64_t)s.k_blocks * s.block_size + 31) / 32 * 8) : 0;
   pl.off_gather = off;
   off += align_up(pairs * (size_t)pl.gather_groups * sizeof(uint64_t));
   // key exchange of the in-kernel retrieval: per (pair, row group)
-  const size_t groups = pairs * (pl.Mpad / 32);
   pl.off_xkeys = off;
-  off += align_up(pl.fused_select ? groups * (size_t)nb_max_of(s) * sizeof(uint64_t) : 0);
+  off += align_up(pl.fused_select ? pl.groups * (size_t)nb_max_of(s) * sizeof(uint64_t) : 0);
   pl.off_epochs = off;
-  off += align_up(pl.fused_select ? groups * sizeof(uint32_t) : 0);
+  off += align_up(pl.groups * sizeof(uint64_t));
   pl.bytes = off;
   return pl;
 }
 
 namespace {
+
+// high half of every group's epoch word: 0 (default wait budget) or the caller's number of polls plus one
+__global__ void set_wait_polls_kernel(uint64_t* epochs, size_t n, uint32_t high_half) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) reinterpret_cast<uint32_t*>(epochs + i)[1] = high_half;
+}
 
 __global__ void fill_zero_kernel(uint4* p, size_t n16) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -146,21 +156,11 @@ hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st) {
 
 }  // namespace svf
 
-// Polls a workgroup of the retrieving attention kernel spends waiting for the block keys of the
-// other workgroups of its group before it scores everything itself (svf_set_exchange_polls).
-static std::atomic<int> g_exchange_polls{64};
-
 using namespace svf;
 
 extern "C" {
 
 int svf_version(void) { return 100; }
-
-int svf_set_exchange_polls(int polls) {
-  if (polls < 0 || polls > 4096) return SVF_ERR_SHAPE;
-  g_exchange_polls.store(polls, std::memory_order_relaxed);
-  return SVF_OK;
-}
 
 const char* svf_strerror(int code) {
   switch (code) {
@@ -201,6 +201,19 @@ int svf_workspace_init(void* ws, size_t ws_bytes, void* stream) {
   if (!ws) return SVF_ERR_NULL;
   if (reinterpret_cast<uintptr_t>(ws) % kAlign || ws_bytes % 16) return SVF_ERR_WORKSPACE;
   return hip_code(launch_fill_zero(ws, ws_bytes, static_cast<hipStream_t>(stream)));
+}
+
+int svf_workspace_set_wait_polls(const svf_shape_t* shape, void* ws, size_t ws_bytes, int polls, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  rc = check_ws(shape, ws, ws_bytes);
+  if (rc) return rc;
+  if (polls < -1 || polls > kMaxWaitPolls) return SVF_ERR_SHAPE;
+  const AttnPlan pl = plan_attn(*shape);
+  uint64_t* epochs = reinterpret_cast<uint64_t*>(static_cast<char*>(ws) + pl.off_epochs);
+  hipLaunchKernelGGL(set_wait_polls_kernel, dim3((unsigned)((pl.groups + 255) / 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), epochs, pl.groups, polls < 0 ? 0u : (uint32_t)polls + 1u);
+  return hip_code(hipGetLastError());
 }
 
 static int block_reps_impl(const svf_shape_t* shape, const void* K, const int32_t* block_table,
@@ -266,8 +279,7 @@ static int score_select_impl(const svf_shape_t* shape, const void* q, const floa
       a.sel_cnt_out = sel_cnt;
       a.tickets = reinterpret_cast<uint64_t*>(w + pl.off_tickets);
       a.xkeys = reinterpret_cast<uint64_t*>(w + pl.off_xkeys);
-      a.epochs = reinterpret_cast<uint32_t*>(w + pl.off_epochs);
-      a.poll_budget = g_exchange_polls.load(std::memory_order_relaxed);
+      a.epochs = reinterpret_cast<uint64_t*>(w + pl.off_epochs);
       a.nb_max = nb_max_of(*shape);
       a.n_sink = shape->n_sink;
       a.n_local = shape->n_local;
@@ -363,6 +375,7 @@ static int verify_attn_impl(const svf_shape_t* shape, const void* q, const void*
   p.part_m = reinterpret_cast<float*>(w + pl.off_m);
   p.part_l = reinterpret_cast<float*>(w + pl.off_l);
   p.part_ml = p.part_m;
+  p.part_rec = reinterpret_cast<uint32_t*>(p.part_m);
   p.gather = (use_gather && pl.gather) ? reinterpret_cast<const uint64_t*>(w + pl.off_gather) : nullptr;
   p.gather_groups = pl.gather_groups;
   // retrieval inside the kernel: sel_idx / sel_cnt are then outputs (the caller passed them writable)
@@ -374,8 +387,8 @@ static int verify_attn_impl(const svf_shape_t* shape, const void* q, const void*
   p.n_sink = shape->n_sink;
   p.n_local = shape->n_local;
   p.xkeys = reinterpret_cast<uint64_t*>(w + pl.off_xkeys);
-  p.epochs = reinterpret_cast<uint32_t*>(w + pl.off_epochs);
-  p.poll_budget = g_exchange_polls.load(std::memory_order_relaxed);
+  p.epochs = reinterpret_cast<uint64_t*>(w + pl.off_epochs);
+  p.slice_rows = pl.slice_rows;
   if (reps_to_select_from && pl.fused_select) {
     p.reps = reps_to_select_from;
     p.sel_idx_out = const_cast<int32_t*>(sel_idx);

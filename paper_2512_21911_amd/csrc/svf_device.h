@@ -53,6 +53,9 @@ struct RepsParams {
 constexpr int kGatherCountShift = 56;
 constexpr uint64_t kGatherOffsetMask = (1ull << kGatherCountShift) - 1ull;
 constexpr int kMaxGatherBlocks = 1024;   // block budgets above this do without a gather list
+constexpr int kTicketWords = 4;          // 64-bit words per (pair, row group) in AttnParams::tickets
+constexpr int kDefaultWaitPolls = 64;    // polls a workgroup spends waiting for the others of its group
+constexpr int kMaxWaitPolls = 4096;
 
 struct SelectParams {
   const void* q;            // [B][gamma][Hq][d]
@@ -90,11 +93,21 @@ struct AttnParams {
   const int32_t* sel_cnt;
   void* out;
   float* lse;                  // may be null
-  float* part_o;               // [B][Hkv][S][Mpad][d]   unnormalised partial outputs
-  float* part_m;               // [B][Hkv][S][Mpad]      running maxima (log2 domain)
-  float* part_l;               // [B][Hkv][S][Mpad]      partial denominators
-  float* part_ml;              // [B][Hkv][S][Mpad][2]   (maximum, denominator) pairs; aliases part_m / part_l
-  uint64_t* tickets;           // [B][Hkv][row groups]   arrival counters, zero between calls
+  // split partials.  Vector-ALU kernel: fp32 unnormalised outputs [B][Hkv][S][Mpad][d] with their
+  // running maxima (log2 domain) and denominators in part_m / part_l.  Matrix-core kernels: outputs
+  // normalised by their own denominator and rounded to bf16, [B][Hkv][S][Mpad][d] 2-byte elements
+  // in part_o; the many-rows kernel keeps (maximum, denominator) pairs in part_ml, the kernel for up
+  // to two row groups 16-byte records (maximum, tag, denominator, tag) in part_rec, valid for the
+  // call whose tag both halves carry.  part_m, part_ml and part_rec name the same region.
+  float* part_o;
+  float* part_m;               // [B][Hkv][S][Mpad]
+  float* part_l;               // [B][Hkv][S][Mpad]
+  float* part_ml;              // [B][Hkv][S][Mpad][2]
+  uint32_t* part_rec;          // [B][Hkv][S][Mpad][4]
+  // per (pair, row group) four 64-bit words: [0], [1] arrival word of calls with an even / odd
+  // call counter (bits 15:0 arrivals, bits 31:16 slices given up), [2] arrival counter of the
+  // kernels that reset it themselves, [3] unused
+  uint64_t* tickets;
   const uint64_t* gather;      // [B][Hkv][gather_groups] gather list matching sel_idx, or NULL
   int32_t gather_groups;
   // in-kernel retrieval (matrix-core kernel on anchor layers): reps != NULL switches it on
@@ -104,10 +117,13 @@ struct AttnParams {
   uint64_t* gather_out;        // [B][Hkv][gather_groups]
   int32_t nb_max, n_sink, n_local;
   // exchange of block keys between the workgroups of a (pair, row group): one 64-bit word per
-  // block (key in the low half, the call's tag in the high half), one tag counter per group
+  // block (key in the low half, the call's tag in the high half)
   uint64_t* xkeys;             // [groups][nb_max]
-  uint32_t* epochs;            // [groups]
-  int32_t poll_budget;         // polls before a workgroup scores everything itself; 0: no exchange
+  // per group: low half = calls completed on this group (the tag of a call is that count plus
+  // one), high half = 0 or 1 + the number of polls a workgroup spends waiting for other workgroups
+  // (svf_workspace_set_wait_polls)
+  uint64_t* epochs;            // [groups]
+  int32_t slice_rows;          // rows of a row group that one workgroup merges: ceil(32 / min(n_splits, 16))
   int32_t B, gamma, Hq, Hkv, G, d, M, Mpad, block_size, k_blocks, n_splits, mask_per_batch, max_seq_len;
   int32_t block_shift;         // log2(block_size) if a power of two, else -1
   uint64_t g_magic;            // floor(2^32 / G) + 1: n / G == (n * g_magic) >> 32 for n, G < 65536
@@ -234,11 +250,13 @@ hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st);
 // Host-side planning shared by svf_workspace_bytes and the attention launcher.
 struct AttnPlan {
   int32_t M, Mpad, n_splits;
+  int32_t slice_rows;        // rows of a row group one workgroup merges: ceil(32 / min(n_splits, 16))
   bool mfma;                 // bf16, d = 128: matrix-core kernel; otherwise the vector-ALU kernel
   bool fused_select;         // anchor layers retrieve inside the attention kernel
   bool gather;               // the shape can use a gather list
   int32_t gather_groups;     // entries per (sequence, KV head): a whole number of 32-token tiles
   size_t off_o, off_m, off_l, off_tickets, off_gather, off_xkeys, off_epochs, bytes;
+  size_t groups;             // (sequence, KV head, row group) triples: entries of tickets / epochs
 };
 AttnPlan plan_attn(const svf_shape_t& s);
 

@@ -228,6 +228,13 @@ __device__ __forceinline__ void row_lanes_upto(uint32_t x, uint32_t (&out)[8]) {
   if constexpr (N > 0) row_lanes_upto<N - 1>(x, out);
 }
 
+// Lanes B0 .. B0 + N of every row of sixteen lanes.
+template <int B0, int N>
+__device__ __forceinline__ void row_lanes_from(uint32_t x, uint32_t (&out)[8]) {
+  out[N] = row_lane<B0 + N>(x);
+  if constexpr (N > 0) row_lanes_from<B0, N - 1>(x, out);
+}
+
 // The eight 16-byte fragments of a lane's query row, loaded by hand: not valid before a wait of
 // the caller's own has covered them and query_fragments_arrived() has been given the registers.
 __device__ __forceinline__ void load_query_fragments(bf16x8 (&qf)[8], const void* row) {
@@ -247,8 +254,8 @@ __device__ __forceinline__ uint32_t load4_plain(const void* p) {
   asm volatile("global_load_dword %0, %1, off" : "=v"(v) : "v"(p) : "memory");
   return v;
 }
-__device__ __forceinline__ void front_loads_arrived(u32x2& a, u32x2& b, uint32_t& c) {
-  asm volatile("" : "+v"(a), "+v"(b), "+v"(c) : : "memory");
+__device__ __forceinline__ void front_loads_arrived(u32x2& a, u32x2& b, uint32_t& c, u32x2& d) {
+  asm volatile("" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : : "memory");
 }
 __device__ __forceinline__ void query_fragments_arrived(bf16x8 (&qf)[8]) {
   asm volatile("" : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[4]), "+v"(qf[5]), "+v"(qf[6]), "+v"(qf[7])
@@ -426,7 +433,7 @@ __device__ __forceinline__ void merge_splits(const AttnParams& p, int64_t g_row,
     m_acc = mb;
   }
   if (row_ok) {
-    const float inv = 1.0f / l_acc;
+    const float inv = l_acc > 0.f ? 1.0f / l_acc : 0.f;      // a row that saw no key at all: zero, lse = -inf
     u32x4 o;
 #pragma unroll
     for (int c = 0; c < 4; ++c) o[c] = pack_bf16(acc[2 * c] * inv, acc[2 * c + 1] * inv);
@@ -434,6 +441,127 @@ __device__ __forceinline__ void merge_splits(const AttnParams& p, int64_t g_row,
     if (p.lse && cg == 0) p.lse[orow] = (m_acc + log2f(l_acc)) * 0.6931471805599453f;
   }
 }
+
+// Device-scope loads of what other workgroups have written through (they bypass the per-CU cache;
+// an L2 serves them, also for lines that a workgroup on another XCD has written through).  Issued by
+// hand.  load16_device_now() waits for its value; the values of load16_device() are not valid until
+// device_loads_wait() has been given the registers.
+__device__ __forceinline__ u32x4 load16_device_now(const void* p) {
+  u32x4 v;
+  asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+  return v;
+}
+__device__ __forceinline__ u32x4 load16_device(const void* p) {
+  u32x4 v;
+  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
+  return v;
+}
+__device__ __forceinline__ void device_loads_wait(u32x4 (&o)[8]) {
+  asm volatile("s_waitcnt vmcnt(0)"
+               : "+v"(o[0]), "+v"(o[1]), "+v"(o[2]), "+v"(o[3]), "+v"(o[4]), "+v"(o[5]), "+v"(o[6]), "+v"(o[7])
+               :
+               : "memory");
+}
+
+// What a thread of the combination (row r = tid / 16 of the row group, channels 8 cg .. 8 cg + 7)
+// knows about its own workgroup's partial of that row: it never has to come back from memory.
+struct OwnPartial {
+  u32x4 o;          // normalised output, bf16
+  float m, l;       // running maximum (log2 domain), denominator
+  int split;
+};
+
+// Splits sb + B0 .. sb + B0 + 7 of one row into the running merge (log-sum-exp rule, splits in
+// order).  rec: this lane's record (maximum, tag, denominator, tag) of split sb + cg; the records of
+// the row's other splits sit in the other lanes of its row of sixteen.
+template <int B0>
+__device__ __forceinline__ void merge_batch(const AttnParams& p, int64_t g_row, int sb, int cg, const u32x4& rec,
+                                            const OwnPartial& own, float (&acc)[8], float& m_acc, float& l_acc) {
+  const uint16_t* part_o = reinterpret_cast<const uint16_t*>(p.part_o);
+  const int S = p.n_splits;
+  u32x4 t[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    // past the last split: any valid address (weight 0 below); this workgroup's own split: its
+    // neighbour's (the value comes from registers, and a line just written through is slow to read back)
+    int sp = min(sb + B0 + u, S - 1);
+    if (sp == own.split) sp = own.split > 0 ? own.split - 1 : 1;
+    t[u] = load16_device(part_o + (g_row + (int64_t)sp * p.Mpad) * kD + cg * 8);
+  }
+  device_loads_wait(t);
+  uint32_t mbits[8], lbits[8];
+  row_lanes_from<B0, 7>(rec[0], mbits);
+  row_lanes_from<B0, 7>(rec[2], lbits);
+  float pm[8], pl[8];
+  float mb = m_acc;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const bool is_own = sb + B0 + u == own.split;
+    pm[u] = sb + B0 + u >= S ? -INFINITY : (is_own ? own.m : __uint_as_float(mbits[u]));
+    pl[u] = is_own ? own.l : __uint_as_float(lbits[u]);
+    if (is_own) t[u] = own.o;
+    mb = fmaxf(mb, pm[u]);
+  }
+  const float fa = m_acc == -INFINITY ? 0.f : fast_exp2(m_acc - mb);
+  l_acc *= fa;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] *= fa;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    // weight of split s: exp2(m_s - m) * l_s, applied to its normalised output
+    const float w = pm[u] != -INFINITY ? fast_exp2(pm[u] - mb) * pl[u] : 0.f;
+    l_acc += w;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      acc[2 * c] += w * bf16_lo(t[u][c]);
+      acc[2 * c + 1] += w * bf16_hi(t[u][c]);
+    }
+  }
+  m_acc = mb;
+}
+
+// Merges rows lo <= r < hi of a row group from the partials of all splits and writes out / lse:
+// every row by the sixteen threads (r, cg) that held it in the combination.  A split's partial is
+// valid once both halves of its record carry this call's tag; the wavefront polls the records of
+// its rows at most `budget` times and returns false (for the whole wavefront, nothing written) when
+// some record is still missing then.  Must be called by whole wavefronts.
+__device__ __forceinline__ bool merge_slice(const AttnParams& p, int lo, int hi, int budget, uint32_t tag, int pair,
+                                            int row0, int r, int cg, int64_t orow, bool rok, const OwnPartial& own) {
+  const bool mine = r >= lo && r < hi;
+  if (!__any(mine)) return true;
+  const int S = p.n_splits;
+  const int64_t g_row = (int64_t)pair * S * p.Mpad + row0 + r;       // + split * Mpad
+  float acc[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] = 0.f;
+  float m_acc = -INFINITY, l_acc = 0.f;
+  for (int sb = 0; sb < S; sb += 16) {
+    // lane cg of a row waits for the record of split sb + cg
+    const uint32_t* recp = p.part_rec + (g_row + (int64_t)min(sb + cg, S - 1) * p.Mpad) * 4;
+    u32x4 rec = {0u, 0u, 0u, 0u};
+    bool pending = mine && sb + cg < S && sb + cg != own.split;
+    for (int it = 0;; ++it) {
+      if (!__any(pending)) break;
+      if (it >= budget) return false;
+      if (pending) {
+        rec = load16_device_now(recp);
+        pending = !(rec[1] == tag && rec[3] == tag);
+      }
+    }
+    merge_batch<0>(p, g_row, sb, cg, rec, own, acc, m_acc, l_acc);
+    if (sb + 8 < S) merge_batch<8>(p, g_row, sb, cg, rec, own, acc, m_acc, l_acc);
+  }
+  if (mine && rok) {
+    const float inv = l_acc > 0.f ? 1.0f / l_acc : 0.f;      // a row that saw no key at all: zero, lse = -inf
+    u32x4 o;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) o[c] = pack_bf16(acc[2 * c] * inv, acc[2 * c + 1] * inv);
+    *reinterpret_cast<u32x4*>(static_cast<__hip_bfloat16*>(p.out) + orow * kD + cg * 8) = o;
+    if (p.lse && cg == 0) p.lse[orow] = (m_acc + log2f(l_acc)) * 0.6931471805599453f;
+  }
+  return true;
+}
+constexpr int kLastResortPolls = 1 << 16;   // for waits that are known to end: every writer has arrived
 
 // Where the kernel learns which rows to fetch.
 constexpr int kResolve = 0;   // sel_idx / sel_cnt in memory, page table walked per tile
@@ -527,6 +655,21 @@ __device__ __forceinline__ void workgroup_select(const uint32_t* keys, SelectScr
 constexpr int kScoreChunks = kD / (4 * kScoreLanes);   // 16-byte chunks of a representative per lane
 constexpr int kScoreBatch = 8;                         // passes (of 64 blocks) in flight
 
+// Polls a workgroup spends waiting for the other workgroups of its group, from the high half of
+// the group's epoch word: 0 = the default, else the caller's number plus one.
+__device__ __forceinline__ int wait_polls_of(int high_half) {
+  return high_half == 0 ? kDefaultWaitPolls : min(high_half - 1, kMaxWaitPolls);
+}
+
+// The call with tag `tag` is over for this group (every workgroup has read the call counter and is
+// past every wait on the others): the counter moves on, and the arrival word that the next call's
+// workgroups will count in starts from zero.  Called by one thread.
+__device__ __forceinline__ void finish_call(const AttnParams& p, int64_t group, uint32_t tag) {
+  __hip_atomic_store(p.tickets + group * kTicketWords + ((tag & 1u) ^ 1u), 0ull, __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+  *reinterpret_cast<uint32_t*>(p.epochs + group) = tag;      // the low half
+}
+
 // What a retrieving workgroup loads up front, together with its query loads.
 struct RetrievalLoads {
   QueryHeads<__hip_bfloat16> q0h;       // channel tid mod 128 of the group's first-draft query heads
@@ -536,7 +679,7 @@ struct RetrievalLoads {
   bool table_in_lds;
   bool table_wide;                      // entries 4 tid .. 4 tid + 3 (16-byte loads) instead of tid, tid + 512, ...
   bool share_scores;
-  uint32_t tag;                         // the group's counter as loaded; retrieve_blocks() adds one
+  uint64_t epoch_word;                  // the group's call counter (low half) and wait budget (high half) as loaded
   int rot;                              // first pass of a workgroup that scores alone
   float4 r[kScoreBatch][kScoreChunks];  // first batch of representative rows
 };
@@ -572,8 +715,8 @@ __device__ __forceinline__ RetrievalLoads issue_retrieval_loads(const AttnParams
   // into addresses afterwards costs no further trip to memory
   R.table_row = p.table + (int64_t)b * p.kv.max_pages;
   R.table_in_lds = p.kv.page_size != 0 && p.kv.max_pages <= kTableLoads * kThreads;
-  R.share_scores = p.n_splits >= 2 && p.poll_budget > 0;
-  R.tag = p.epochs[xgroup + vzero];
+  R.share_scores = p.n_splits >= 2;
+  R.epoch_word = p.epochs[xgroup + vzero];
   R.rot = rot;
   R.table_wide = (p.kv.max_pages & 3) == 0 && (reinterpret_cast<uintptr_t>(p.table) & 15) == 0;
   if (R.table_in_lds) {
@@ -651,8 +794,9 @@ __device__ __forceinline__ Retrieved retrieve_blocks(const AttnParams& p, Retrie
   out.s_table = s_table;
   const int nb = (out.L + p.block_size - 1) / p.block_size;
   out.cnt = min(p.k_blocks, nb);
-  out.tag = (uint32_t)__builtin_amdgcn_readfirstlane((int)R.tag) + 1u;
+  out.tag = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)R.epoch_word) + 1u;
   const uint32_t tag = out.tag;
+  const int poll_budget = wait_polls_of(__builtin_amdgcn_readfirstlane((int)(uint32_t)(R.epoch_word >> 32)));
   float4 qv[kScoreChunks];
 #pragma unroll
   for (int i = 0; i < kScoreChunks; ++i) qv[i] = *reinterpret_cast<const float4*>(s_q0 + sub * 4 + i * 4 * kScoreLanes);
@@ -686,7 +830,7 @@ __device__ __forceinline__ Retrieved retrieve_blocks(const AttnParams& p, Retrie
     bool need1 = j1 < nb && ((j1 >> 6) % p.n_splits) != split;
     const bool mine0 = need0, mine1 = need1;
     uint32_t got0 = 0, got1 = 0;
-    for (int it = 0; it < p.poll_budget; ++it) {
+    for (int it = 0; it < poll_budget; ++it) {
       if (need0) {
         const uint64_t w = __hip_atomic_load(xk + j0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if ((uint32_t)(w >> 32) == tag) { got0 = (uint32_t)w; need0 = false; }
@@ -861,7 +1005,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   // valid either way; nothing of them is used before front_loads_arrived().
   uint64_t rmask = 0;
   uint64_t gent = 0;
-  u32x2 rmask_raw = {0u, 0u}, gent_raw = {0u, 0u};
+  u32x2 rmask_raw = {0u, 0u}, gent_raw = {0u, 0u}, epoch_raw = {0u, 0u};
   uint32_t cnt_raw = 0;
   bool gent_wanted = false;
   auto request_entries = [&]() {
@@ -873,6 +1017,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     gent_raw = load8_plain(gsrc);
     rmask_raw = load8_plain(msrc);
     cnt_raw = load4_plain(p.sel_cnt + pair + vzero);
+    epoch_raw = load8_plain(p.epochs + group + vzero);
   };
   if (MODE == kGather && kOneTile) request_entries();
   bf16x8 qf[8];
@@ -937,8 +1082,12 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     *reinterpret_cast<u32x4*>(q_stage + r * kRowBytes + (((tid & 15) ^ (r & 15)) << 4)) = qpiece;
   }
   int cnt;
-  uint32_t tag = 0;                  // (retrieval only) this call's tag of the key exchange
+  // the group's epoch word: this call's tag (for the key exchange of a retrieval and for the
+  // split partials) is its low half plus one, its high half the wait budget
+  uint64_t epoch_word = 0;
+  if (MODE == kResolve) epoch_word = p.epochs[group + vzero];
   if (MODE == kSelect) {
+    epoch_word = rl.epoch_word;
     const Retrieved rt = retrieve_blocks(p, rl, smem, s_sel, &s_exchange_failed, L, pair, split, group, tid, lane, wave, [&]() {
       if (computes) {
 #pragma unroll
@@ -948,7 +1097,6 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     });
     L = rt.L;
     cnt = rt.cnt;
-    tag = rt.tag;
     // gather entries of this wavefront's tiles (lane 8u + n: group n of its u-th tile), kept for
     // the loads below; they are written out for the layers that reuse the selection, and the
     // selection itself, behind the combination of the wavefronts: a store in front of the stream
@@ -962,7 +1110,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   } else if (MODE == kGather) {
     // everything requested ahead of the eight query fragments (and of an early draft tile), or everything
     if (kOneTile && computes) wait_vmcnt_upto24(8 + early_draft_loads); else wait_vmcnt_upto24(early_draft_loads);
-    front_loads_arrived(gent_raw, rmask_raw, cnt_raw);
+    front_loads_arrived(gent_raw, rmask_raw, cnt_raw, epoch_raw);
+    epoch_word = (uint64_t)epoch_raw[0] | ((uint64_t)epoch_raw[1] << 32);
     if (gent_wanted) gent = (uint64_t)gent_raw[0] | ((uint64_t)gent_raw[1] << 32);
     if (p.draft_mask) rmask = (uint64_t)rmask_raw[0] | ((uint64_t)rmask_raw[1] << 32);
     cnt = __builtin_amdgcn_readfirstlane(min(max((int)cnt_raw, 0), p.k_blocks));
@@ -1212,6 +1361,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     oj = orow_row - oi * p.G;
   }
   const int64_t orow = orow_pair + (int64_t)oi * p.Hq + oj;
+  OwnPartial own;
   {
     const float inv = lw > 0.f ? 1.0f / lw : 0.f;
     u32x4 o;
@@ -1224,48 +1374,65 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       }
       return;
     }
-    if (orow_row < p.Mpad) {
-      // this split's partial: normalised output in bf16, (m, l) in fp32, written through
-      const int64_t pr = ((int64_t)pair * p.n_splits + split) * p.Mpad + orow_row;
-      store_coherent16(reinterpret_cast<uint16_t*>(p.part_o) + pr * kD + cg * 8, o);
-      if (cg == 0) store_coherent2(p.part_ml + 2 * pr, mw, lw);
-    }
+    own.o = o;
   }
 
-  // ---- last workgroup of the group merges the splits ------------------------------------------
-  // Once the write-through stores have been acknowledged (vmcnt = 0) the ticket may be taken.
-  // The ticket is one 64-bit counter: bits [15:0] count arrivals, and eight 6-bit fields above
-  // count arrivals per XCD, so that the last workgroup learns whether every partial of its
-  // group was written through the L2 it is about to read from.
-  wait_vmcnt<0>();
-  __syncthreads();
-  if (tid == 0) {
-    uint32_t xcc;
-    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-    const int field = 16 + 6 * (int)(xcc & 7u);
-    const uint64_t prev = __hip_atomic_fetch_add(&p.tickets[group], 1ull | (1ull << field), __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT);
-    const bool last = (prev & 0xffffull) == (uint64_t)(p.n_splits - 1);
-    const bool same_xcd = p.n_splits <= 63 && ((prev >> field) & 63ull) == (uint64_t)(p.n_splits - 1);
-    // leave the counter ready for the next call
-    if (last) __hip_atomic_store(&p.tickets[group], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    sm_last = last ? (same_xcd ? 2 : 1) : 0;
+  // ---- the splits of a group are merged by all its workgroups, each a slice of the rows -----------
+  // Every workgroup writes its partial (normalised output in bf16) through to device-coherent
+  // memory and, once those stores have been acknowledged, a 16-byte record per row: (maximum, tag,
+  // denominator, tag), tag = this call's.  The rows of a row group are cut into slices of
+  // p.slice_rows; workgroup s then waits until the records of slice s carry the tag for every
+  // split, merges those rows in split order (bit-stable: the same sums whoever computes them) and
+  // writes out / lse.  Nothing in between needs a return trip through an atomic: after the last
+  // partial has landed the merge is one poll and one round of loads away.
+  // The wait is bounded.  A wavefront that runs out of patience marks its workgroup's slice as given
+  // up in the group's arrival word, unless that word shows that every workgroup has arrived (then
+  // every partial is on its way and it simply keeps waiting).  Every workgroup takes a ticket from
+  // that word when it has stored its partial; the one that arrives last sees which slices were
+  // given up before it and merges them too.  So every row is merged whatever is resident when, and
+  // every wait ends.  The word of calls with an even / odd tag alternate, the last arriver clears
+  // the other one and moves the call counter on (the layout also works under graph replay).
+  own.m = mw;
+  own.l = lw;
+  own.split = split;
+  const uint32_t tag = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)epoch_word) + 1u;
+  const int wait_polls = wait_polls_of(__builtin_amdgcn_readfirstlane((int)(uint32_t)(epoch_word >> 32)));
+  uint64_t* const arrivals = p.tickets + (int64_t)group * kTicketWords + (tag & 1u);
+  {
+    const int64_t pr = ((int64_t)pair * p.n_splits + split) * p.Mpad + orow_row;
+    store_coherent16(reinterpret_cast<uint16_t*>(p.part_o) + pr * kD + cg * 8, own.o);
+    // rows 4 * wave .. 4 * wave + 3 are all this wavefront's: its own acknowledgements are enough
+    wait_vmcnt<0>();
+    if (cg == 0) {
+      const u32x4 rec = {__float_as_uint(mw), tag, __float_as_uint(lw), tag};
+      store_coherent16(p.part_rec + pr * 4, rec);
+    }
+  }
+  uint64_t prev = 0;
+  if (tid == 0) prev = __hip_atomic_fetch_add(arrivals, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const int R = p.slice_rows;
+  if (!merge_slice(p, split * R, split * R + R, wait_polls, tag, pair, row0, r, cg, orow, rok, own)) {
+    // (wave-uniform) this wavefront's rows of the slice are not merged
+    uint64_t seen = 0;
+    if (lane == 0)
+      seen = __hip_atomic_fetch_or(arrivals, 1ull << (16 + split), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)seen) & 0xffffu;
+    // everybody has arrived, the last arriver may not have seen the mark: keep waiting (it ends)
+    if (arrived == (uint32_t)p.n_splits)
+      merge_slice(p, split * R, split * R + R, kLastResortPolls, tag, pair, row0, r, cg, orow, rok, own);
   }
   __syncthreads();
-  const int last_kind = sm_last;
-  if (last_kind == 0) return;
-  // Remote writers: acquire at device scope, which drops whatever this XCD's caches still hold
-  // of the partial buffers (they are reused by every call); ordinary loads then fetch the
-  // written-through data.  Local writers only (the normal case): this XCD's L2 is their common
-  // coherence point, loads that bypass the per-CU cache are enough.
-  const int64_t g_row = (int64_t)pair * p.n_splits * p.Mpad + orow_row;
-  // every workgroup of the group is past the exchange of block keys: the next call gets a new tag
-  if (MODE == kSelect && rl.share_scores && tid == 0) p.epochs[group] = tag;
-  if (last_kind == 2) {
-    merge_splits<true>(p, g_row, orow, rok, cg);
-  } else {
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    merge_splits<false>(p, g_row, orow, rok, cg);
+  if (tid == 0) {
+    const bool last = (prev & 0xffffull) == (uint64_t)(p.n_splits - 1);
+    sm_last = last ? (int)(0x10000u | (uint32_t)((prev >> 16) & 0xffffull)) : 0;
+    if (last) finish_call(p, group, tag);
+  }
+  __syncthreads();
+  uint32_t given_up = (uint32_t)sm_last & 0xffffu;
+  while (given_up) {                       // (only in the last arriver, and only after a starved wait)
+    const int x = __builtin_ctz(given_up);
+    given_up &= given_up - 1u;
+    merge_slice(p, x * R, x * R + R, kLastResortPolls, tag, pair, row0, r, cg, orow, rok, own);
   }
 }
 
@@ -1595,8 +1762,8 @@ __global__ __launch_bounds__(kThreads) void merge_rows_kernel(AttnParams p, int 
   const int64_t orow = (int64_t)b * p.gamma * p.Hq + h * p.G + (int64_t)oi * p.Hq + oj;
   const int64_t g_row = (int64_t)pair * p.n_splits * p.Mpad + orow_row;
   if (advance_tags && tid == 0 && rg % kWaves == 0) {
-    uint32_t* e = p.epochs + (int64_t)(rg / kWaves) * pairs + pair;
-    *e = *e + 1u;
+    const int64_t xg = (int64_t)(rg / kWaves) * pairs + pair;
+    finish_call(p, xg, *reinterpret_cast<const uint32_t*>(p.epochs + xg) + 1u);
   }
   merge_splits<false>(p, g_row, orow, rok, cg);
 }
@@ -1677,10 +1844,11 @@ __global__ __launch_bounds__(kThreads) void retrieve_only_kernel(AttnParams p, i
   if (split == p.n_splits - 1) publish_selection(p, s_sel, rt.cnt, pair, tid);
   if (rl.share_scores && tid == 0) {
     // every workgroup that takes a ticket has read all the keys it needed
-    const uint64_t prev = __hip_atomic_fetch_add(&p.tickets[pair], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint64_t* const counter = p.tickets + (int64_t)pair * kTicketWords + 2;
+    const uint64_t prev = __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (prev == (uint64_t)(p.n_splits - 1)) {
-      __hip_atomic_store(&p.tickets[pair], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      p.epochs[pair] = rt.tag;
+      __hip_atomic_store(counter, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      finish_call(p, pair, rt.tag);
     }
   }
 }
@@ -1703,7 +1871,7 @@ hipError_t launch_verify_attn_mfma(const AttnParams& p, hipStream_t st) {
     else hipLaunchKernelGGL(verify_attn_mfma_rows_kernel<kResolve>, grid, dim3(kThreads), 0, st, p, pairs);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.n_splits == 1) return e;
-    const int advance_tags = p.reps != nullptr && p.n_splits >= 2 && p.poll_budget > 0;
+    const int advance_tags = p.reps != nullptr && p.n_splits >= 2;
     hipLaunchKernelGGL(merge_rows_kernel, dim3((unsigned)pairs, (unsigned)row_groups), dim3(kThreads), 0, st, p, pairs,
                        advance_tags);
     return hipGetLastError();

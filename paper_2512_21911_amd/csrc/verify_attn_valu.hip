@@ -209,7 +209,8 @@ __global__ void merge_splits_kernel(AttnParams p) {
   }
   const int i = row / p.G, j = h * p.G + row % p.G;
   const int64_t orow = ((int64_t)b * p.gamma + i) * p.Hq + j;
-  store_out<T>(static_cast<T*>(p.out) + orow * D + c, o / l);
+  // a row that saw no key at all (no kept block, a draft mask without its own bit): zero, lse = -inf
+  store_out<T>(static_cast<T*>(p.out) + orow * D + c, l > 0.f ? o / l : 0.f);
   if (p.lse && c == 0) p.lse[orow] = (m + log2f(l)) * 0.6931471805599453f;
 }
 

@@ -94,8 +94,10 @@ def test_null_alignment_and_workspace_checks():
     assert L.svf_verify_step(ctypes.byref(sh), 1, *sargs, need, None) == -1
     assert L.svf_verify_step(ctypes.byref(sh), 3, *([ok] * 14), need, None) == -2           # no such step mode
     assert L.svf_verify_step(ctypes.byref(sh), -1, *([ok] * 14), need, None) == -2
-    assert L.svf_set_exchange_polls(-1) == -2 and L.svf_set_exchange_polls(4097) == -2
-    assert L.svf_set_exchange_polls(64) == 0
+    assert L.svf_workspace_set_wait_polls(ctypes.byref(sh), ok, need, -2, None) == -2      # polls out of range
+    assert L.svf_workspace_set_wait_polls(ctypes.byref(sh), ok, need, 4097, None) == -2
+    assert L.svf_workspace_set_wait_polls(ctypes.byref(sh), null, need, 8, None) == -6     # no workspace
+    assert L.svf_workspace_set_wait_polls(ctypes.byref(sh), ok, need - 256, 8, None) == -6
     assert L.svf_score_select(ctypes.byref(sh), ok, ok, ok, ok, ok, null, ok, need - 256, None) == -6
     assert L.svf_workspace_init(null, 256, None) == -1
     assert L.svf_workspace_init(ctypes.c_void_p(0x10010), 256, None) == -6
