@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 
@@ -18,7 +19,13 @@ HIPCC_FLAGS = [
     # packed fp32 instruction forms are kept out of the generated code on this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    # per-kernel register / scratch report on stderr, checked below
+    "-Rpass-analysis=kernel-resource-usage",
 ]
+
+# Kernels that must not use scratch memory (a private segment makes every dispatch slower, and an
+# array the compiler moved there turns register accesses into memory round trips).
+NO_SCRATCH = ("verify_attn_mfma_kernel", "verify_attn_mfma_rows_kernel", "retrieve_only_kernel")
 
 
 def hipcc_path() -> str:
@@ -36,11 +43,24 @@ def build_lib(verbose: bool = True) -> str:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    lines = [l for l in res.stderr.splitlines() if noise not in l]
+    remarks = [l for l in lines if "remark:" in l]
+    # (a remark is followed by the source line it points at and a caret line)
+    context = re.compile(r"^\s*(\d+\s*)?\|")
+    err = "\n".join(l for l in lines if "remark:" not in l and not context.match(l))
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + "\n" + err)
     if verbose and err.strip():
         print(err, file=sys.stderr)
+    # the report names a kernel ("Function Name: ...") and then lists its resources
+    name = None
+    for l in remarks:
+        if "Function Name:" in l:
+            name = l.split("Function Name:")[1].split("[-Rpass")[0].strip()
+        elif "ScratchSize [bytes/lane]:" in l and name and any(k in name for k in NO_SCRATCH):
+            size = int(l.split("ScratchSize [bytes/lane]:")[1].split()[0])
+            if size != 0:
+                raise RuntimeError(f"{name} uses {size} bytes of scratch memory per lane")
     return LIB_PATH
 
 

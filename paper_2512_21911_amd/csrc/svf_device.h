@@ -53,7 +53,7 @@ struct RepsParams {
 constexpr int kGatherCountShift = 56;
 constexpr uint64_t kGatherOffsetMask = (1ull << kGatherCountShift) - 1ull;
 constexpr int kMaxGatherBlocks = 1024;   // block budgets above this do without a gather list
-constexpr int kTicketWords = 4;          // 64-bit words per (pair, row group) in AttnParams::tickets
+constexpr int kTicketWords = 8;          // 64-bit words per (pair, row group) in AttnParams::tickets
 constexpr int kDefaultWaitPolls = 64;    // polls a workgroup spends waiting for the others of its group
 constexpr int kMaxWaitPolls = 4096;
 
@@ -104,9 +104,10 @@ struct AttnParams {
   float* part_l;               // [B][Hkv][S][Mpad]
   float* part_ml;              // [B][Hkv][S][Mpad][2]
   uint32_t* part_rec;          // [B][Hkv][S][Mpad][4]
-  // per (pair, row group) four 64-bit words: [0], [1] arrival word of calls with an even / odd
-  // call counter (bits 15:0 arrivals, bits 31:16 slices given up), [2] arrival counter of the
-  // kernels that reset it themselves, [3] unused
+  // per (pair, row group) eight 64-bit words: [0], [1] arrival word of calls with an even / odd
+  // tag (bits 15:0 arrivals, bits 31:16 slices given up), [2] arrival counter of the kernels that
+  // reset it themselves, [4], [5] (even / odd tag) where the group's workgroups run: eight 8-bit
+  // counters, one per XCD, to which every workgroup adds one when it starts; the others unused
   uint64_t* tickets;
   const uint64_t* gather;      // [B][Hkv][gather_groups] gather list matching sel_idx, or NULL
   int32_t gather_groups;

@@ -153,6 +153,16 @@ __device__ __forceinline__ float halves_sum(float x) {
 __device__ __forceinline__ void store_coherent16(void* p, u32x4 bits) {
   asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(bits) : "memory");
 }
+// The same store left in the L2 (written back when the kernel ends): enough, and acknowledged much
+// sooner, when every reader is known to sit behind the same L2.
+__device__ __forceinline__ void store_l2_16(void* p, u32x4 bits) {
+  asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 1" : : "v"(p), "v"(bits) : "memory");
+}
+__device__ __forceinline__ uint32_t xcc_id() {
+  uint32_t xcc;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+  return xcc & 7u;
+}
 __device__ __forceinline__ void store_coherent2(float* p, float a, float b) {
   const uint64_t bits = (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32);
   __hip_atomic_store(reinterpret_cast<uint64_t*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -220,7 +230,7 @@ __device__ __forceinline__ void merge_loads_wait(u32x4 (&o)[8], u32x2& ml) {
 // Lane N of every row of sixteen lanes, to all lanes of that row.
 template <int N>
 __device__ __forceinline__ uint32_t row_lane(uint32_t x) {
-  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x150 + N, 0xf, 0xf, false);   // row_newbcast:N
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x150 + N, 0xf, 0xf, true);    // row_newbcast:N
 }
 template <int N>
 __device__ __forceinline__ void row_lanes_upto(uint32_t x, uint32_t (&out)[8]) {
@@ -442,126 +452,244 @@ __device__ __forceinline__ void merge_splits(const AttnParams& p, int64_t g_row,
   }
 }
 
+// ---- merging the splits of a group ----------------------------------------------------------------
+// A split's partial of a row is its output normalised by its own denominator (bf16) and a 16-byte
+// record (maximum, tag, denominator, tag); the record is written after the output has been
+// acknowledged, so a record whose two tags are this call's vouches for the output beside it.
+// Merge rule (log-sum-exp), the same sums in the same order whoever computes them: splits in
+// order, in batches of eight, each batch brought to the running maximum.
+// The merging threads are two wavefronts (128 threads): CH channels per thread (4 or 8), 128 / CH
+// threads per row, 4 or 8 rows per pass.
+
 // Device-scope loads of what other workgroups have written through (they bypass the per-CU cache;
-// an L2 serves them, also for lines that a workgroup on another XCD has written through).  Issued by
-// hand.  load16_device_now() waits for its value; the values of load16_device() are not valid until
-// device_loads_wait() has been given the registers.
-__device__ __forceinline__ u32x4 load16_device_now(const void* p) {
+// an L2 serves them, also for lines that a workgroup on another XCD has written through).  Issued
+// by hand: scalar base + per-lane offset.  load_record_now() waits for its value; the values of
+// load_chunk() are not valid before chunks_wait() has been given the registers.
+__device__ __forceinline__ u32x4 load_record_now(const void* p) {
   u32x4 v;
   asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
   return v;
 }
-__device__ __forceinline__ u32x4 load16_device(const void* p) {
-  u32x4 v;
-  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
-  return v;
+__device__ __forceinline__ void load_chunk(u32x2& v, uint64_t base, uint32_t off) {
+  asm volatile("global_load_dwordx2 %0, %1, %2 sc1" : "=v"(v) : "v"(off), "s"(base) : "memory");
 }
-__device__ __forceinline__ void device_loads_wait(u32x4 (&o)[8]) {
+__device__ __forceinline__ void load_chunk(u32x4& v, uint64_t base, uint32_t off) {
+  asm volatile("global_load_dwordx4 %0, %1, %2 sc1" : "=v"(v) : "v"(off), "s"(base) : "memory");
+}
+template <typename T>
+__device__ __forceinline__ void chunks_wait(T (&o)[8]) {
   asm volatile("s_waitcnt vmcnt(0)"
                : "+v"(o[0]), "+v"(o[1]), "+v"(o[2]), "+v"(o[3]), "+v"(o[4]), "+v"(o[5]), "+v"(o[6]), "+v"(o[7])
                :
                : "memory");
 }
+template <int CH> struct ChunkOf;
+template <> struct ChunkOf<4> { typedef u32x2 type; };
+template <> struct ChunkOf<8> { typedef u32x4 type; };
 
-// What a thread of the combination (row r = tid / 16 of the row group, channels 8 cg .. 8 cg + 7)
-// knows about its own workgroup's partial of that row: it never has to come back from memory.
-struct OwnPartial {
-  u32x4 o;          // normalised output, bf16
-  float m, l;       // running maximum (log2 domain), denominator
+constexpr int kMergeThreads = 128;          // wavefronts kMergeWave0 and kMergeWave0 + 1
+constexpr int kMergeWave0 = 4;
+constexpr int kLastResortPolls = 1 << 16;   // for waits that are known to end: every writer has arrived
+
+// One merging thread's view of one pass over rows r0 .. r0 + rows per pass.
+template <int CH>
+struct MergeLane {
+  typedef typename ChunkOf<CH>::type Chunk;
+  static constexpr int kLanesPerRow = kD / CH;                  // 32 or 16
+  static constexpr int kRowsPerPass = kMergeThreads / kLanesPerRow;
+  int row;            // row of the row group (clamped to a valid one), cl: which CH channels
+  int cl;
+  bool active;        // the row is one of those to merge
+  float acc[CH];
+  float m_acc, l_acc;
+  u32x4 rec;          // record of split c0 + cl % 16 of this row
+  Chunk t0[8], t1[8]; // fetched outputs of splits c0 .. c0 + 7 and c0 + 8 .. c0 + 15
+};
+
+// This workgroup's own partial of the rows it merges, left in LDS by the threads that formed it:
+// [rows][kD] bf16, then (maximum, denominator) per row.  own_split < 0: nothing is taken from LDS.
+struct OwnRows {
+  const unsigned char* o;
+  const float* ml;
+  int lo;             // first row held
   int split;
 };
 
-// Splits sb + B0 .. sb + B0 + 7 of one row into the running merge (log-sum-exp rule, splits in
-// order).  rec: this lane's record (maximum, tag, denominator, tag) of split sb + cg; the records of
-// the row's other splits sit in the other lanes of its row of sixteen.
-template <int B0>
-__device__ __forceinline__ void merge_batch(const AttnParams& p, int64_t g_row, int sb, int cg, const u32x4& rec,
-                                            const OwnPartial& own, float (&acc)[8], float& m_acc, float& l_acc) {
-  const uint16_t* part_o = reinterpret_cast<const uint16_t*>(p.part_o);
+// Waits (at most `budget` polls) until the records of splits c0 .. c0 + 15 of the lane's row carry
+// the tag; the own split's record is not waited for when its partial comes from LDS.  Returns false
+// for the whole wavefront when some record is still missing.
+template <int CH>
+__device__ __forceinline__ bool poll_records(const AttnParams& p, MergeLane<CH>& L, int64_t g_row, int c0, uint32_t tag,
+                                             int budget, int own_split) {
   const int S = p.n_splits;
-  u32x4 t[8];
+  const int sp = c0 + (L.cl & 15);
+  const uint32_t* recp = p.part_rec + (g_row + (int64_t)min(sp, S - 1) * p.Mpad) * 4;
+  // (past the last split: a record that weighs nothing)
+  L.rec = u32x4{sp < S ? 0u : 0xff800000u, 0u, 0u, 0u};
+  bool pending = L.active && sp < S && sp != own_split;
+  for (int it = 0;; ++it) {
+    if (!__any(pending)) return true;
+    if (it >= budget) return false;
+    if (pending) {
+      L.rec = load_record_now(recp);
+      pending = !(L.rec[1] == tag && L.rec[3] == tag);
+    }
+  }
+}
+
+// Requests the outputs of splits c0 + B0 .. c0 + B0 + 7 of the lane's row (past the last split: the
+// batch's first split again, weight 0 later; the own split's is fetched like the others even when
+// LDS holds it: one address chain, a step of one split's partial at a time).
+template <int CH, int B0>
+__device__ __forceinline__ void fetch_batch(const AttnParams& p, typename ChunkOf<CH>::type (&t)[8], int pair, uint32_t voff,
+                                            int c0) {
+  const int S = p.n_splits;
+  const uint64_t step = (uint64_t)p.Mpad * kRowBytes;
+  const uint64_t first = (uint64_t)(uintptr_t)p.part_o + ((uint64_t)pair * S + (uint64_t)(c0 + B0)) * step;
+  const int n = S - c0 - B0;                             // splits of this batch that exist (>= 1)
+  uint64_t at = first;
 #pragma unroll
   for (int u = 0; u < 8; ++u) {
-    // past the last split: any valid address (weight 0 below); this workgroup's own split: its
-    // neighbour's (the value comes from registers, and a line just written through is slow to read back)
-    int sp = min(sb + B0 + u, S - 1);
-    if (sp == own.split) sp = own.split > 0 ? own.split - 1 : 1;
-    t[u] = load16_device(part_o + (g_row + (int64_t)sp * p.Mpad) * kD + cg * 8);
+    load_chunk(t[u], u < n ? at : first, voff);
+    at += step;
   }
-  device_loads_wait(t);
+}
+
+template <int CH>
+__device__ __forceinline__ float chunk_value(const typename ChunkOf<CH>::type& t, int c) {
+  return (c & 1) ? bf16_hi(t[c >> 1]) : bf16_lo(t[c >> 1]);
+}
+
+// Splits c0 + B0 .. c0 + B0 + 7 into the running merge.
+template <int CH, int B0>
+__device__ __forceinline__ void finish_batch(const AttnParams& p, MergeLane<CH>& L, typename ChunkOf<CH>::type (&t)[8], int c0,
+                                             const OwnRows& own) {
+  const int ou = own.split - c0 - B0;                  // (uniform) the own split's place in this batch
+  uint32_t mrec = L.rec[0], lrec = L.rec[2];
+  if (ou >= 0 && ou < 8) {
+    // the own split's partial comes from LDS: its (maximum, denominator) into the lane that holds
+    // that split's record, its output in place of what was fetched
+    const int orow = min(max(L.row - own.lo, 0), 31);
+    const typename ChunkOf<CH>::type oc =
+        *reinterpret_cast<const typename ChunkOf<CH>::type*>(own.o + orow * kRowBytes + L.cl * (CH * 2));
+    if ((L.cl & 15) == B0 + ou) {
+      mrec = __float_as_uint(own.ml[2 * orow]);
+      lrec = __float_as_uint(own.ml[2 * orow + 1]);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      // (eight separate comparisons: folded into one store with a run-time index they would move
+      // the fetched outputs from registers to scratch memory)
+      int o = ou;
+      asm volatile("" : "+s"(o));
+      if (o == u) t[u] = oc;
+    }
+  }
   uint32_t mbits[8], lbits[8];
-  row_lanes_from<B0, 7>(rec[0], mbits);
-  row_lanes_from<B0, 7>(rec[2], lbits);
-  float pm[8], pl[8];
-  float mb = m_acc;
+  row_lanes_from<B0, 7>(mrec, mbits);
+  row_lanes_from<B0, 7>(lrec, lbits);
+  float mb = L.m_acc;
 #pragma unroll
-  for (int u = 0; u < 8; ++u) {
-    const bool is_own = sb + B0 + u == own.split;
-    pm[u] = sb + B0 + u >= S ? -INFINITY : (is_own ? own.m : __uint_as_float(mbits[u]));
-    pl[u] = is_own ? own.l : __uint_as_float(lbits[u]);
-    if (is_own) t[u] = own.o;
-    mb = fmaxf(mb, pm[u]);
-  }
-  const float fa = m_acc == -INFINITY ? 0.f : fast_exp2(m_acc - mb);
-  l_acc *= fa;
+  for (int u = 0; u < 8; ++u) mb = fmaxf(mb, __uint_as_float(mbits[u]));
+  // (a row that no split saw a token for: every maximum is -inf; exp2(-inf - 0) = 0 for all of them)
+  const float ref = mb == -INFINITY ? 0.f : mb;
+  const float fa = fast_exp2(L.m_acc - ref);
+  L.l_acc *= fa;
 #pragma unroll
-  for (int c = 0; c < 8; ++c) acc[c] *= fa;
+  for (int c = 0; c < CH; ++c) L.acc[c] *= fa;
 #pragma unroll
   for (int u = 0; u < 8; ++u) {
     // weight of split s: exp2(m_s - m) * l_s, applied to its normalised output
-    const float w = pm[u] != -INFINITY ? fast_exp2(pm[u] - mb) * pl[u] : 0.f;
-    l_acc += w;
+    const float w = fast_exp2(__uint_as_float(mbits[u]) - ref) * __uint_as_float(lbits[u]);
+    L.l_acc += w;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      acc[2 * c] += w * bf16_lo(t[u][c]);
-      acc[2 * c + 1] += w * bf16_hi(t[u][c]);
-    }
+    for (int c = 0; c < CH; ++c) L.acc[c] += w * chunk_value<CH>(t[u], c);
   }
-  m_acc = mb;
+  L.m_acc = mb;
 }
 
-// Merges rows lo <= r < hi of a row group from the partials of all splits and writes out / lse:
-// every row by the sixteen threads (r, cg) that held it in the combination.  A split's partial is
-// valid once both halves of its record carry this call's tag; the wavefront polls the records of
-// its rows at most `budget` times and returns false (for the whole wavefront, nothing written) when
-// some record is still missing then.  Must be called by whole wavefronts.
-__device__ __forceinline__ bool merge_slice(const AttnParams& p, int lo, int hi, int budget, uint32_t tag, int pair,
-                                            int row0, int r, int cg, int64_t orow, bool rok, const OwnPartial& own) {
-  const bool mine = r >= lo && r < hi;
-  if (!__any(mine)) return true;
+template <int CH>
+__device__ __forceinline__ void init_lane(MergeLane<CH>& L, int mt, int r0, int hi) {
+  const int rr = r0 + mt / MergeLane<CH>::kLanesPerRow;
+  L.cl = mt % MergeLane<CH>::kLanesPerRow;
+  L.active = rr < hi && rr < 32;
+  L.row = L.active ? rr : r0;
+#pragma unroll
+  for (int c = 0; c < CH; ++c) L.acc[c] = 0.f;
+  L.m_acc = -INFINITY;
+  L.l_acc = 0.f;
+}
+
+// The merged row goes out (CH channels per thread) with its log-sum-exp.
+template <int CH>
+__device__ __forceinline__ void store_merged(const AttnParams& p, const MergeLane<CH>& L, int row0, int64_t orow_pair) {
+  const int grow = row0 + L.row;
+  if (!L.active || grow >= p.M) return;
+  const int oi = (int)(((uint64_t)(uint32_t)grow * p.g_magic) >> 32), oj = grow - oi * p.G;
+  const int64_t orow = orow_pair + (int64_t)oi * p.Hq + oj;
+  const float inv = L.l_acc > 0.f ? __builtin_amdgcn_rcpf(L.l_acc) : 0.f;   // a row that saw no key at all: zero, lse = -inf
+  typename ChunkOf<CH>::type o;
+#pragma unroll
+  for (int c = 0; c < CH / 2; ++c) o[c] = pack_bf16(L.acc[2 * c] * inv, L.acc[2 * c + 1] * inv);
+  *reinterpret_cast<typename ChunkOf<CH>::type*>(static_cast<__hip_bfloat16*>(p.out) + orow * kD + L.cl * CH) = o;
+  if (p.lse && L.cl == 0) p.lse[orow] = (L.m_acc + log2f(L.l_acc)) * 0.6931471805599453f;
+}
+
+template <typename T>
+__device__ __forceinline__ void chunks_wait16(T (&a)[8], T (&b)[8]) {
+  asm volatile("s_waitcnt vmcnt(0)"
+               : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]),
+                 "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7])
+               :
+               : "memory");
+}
+
+// Splits c0 .. c0 + 15 of the lane's row: waits for their records (bounded), then fetches their
+// outputs.  False for the whole wavefront when a record was still missing.
+template <int CH>
+__device__ __forceinline__ bool merge_fetch(const AttnParams& p, MergeLane<CH>& L, int pair, int row0, int c0, uint32_t tag,
+                                            int budget, int own_split) {
   const int S = p.n_splits;
-  const int64_t g_row = (int64_t)pair * S * p.Mpad + row0 + r;       // + split * Mpad
-  float acc[8];
-#pragma unroll
-  for (int c = 0; c < 8; ++c) acc[c] = 0.f;
-  float m_acc = -INFINITY, l_acc = 0.f;
-  for (int sb = 0; sb < S; sb += 16) {
-    // lane cg of a row waits for the record of split sb + cg
-    const uint32_t* recp = p.part_rec + (g_row + (int64_t)min(sb + cg, S - 1) * p.Mpad) * 4;
-    u32x4 rec = {0u, 0u, 0u, 0u};
-    bool pending = mine && sb + cg < S && sb + cg != own.split;
-    for (int it = 0;; ++it) {
-      if (!__any(pending)) break;
-      if (it >= budget) return false;
-      if (pending) {
-        rec = load16_device_now(recp);
-        pending = !(rec[1] == tag && rec[3] == tag);
-      }
-    }
-    merge_batch<0>(p, g_row, sb, cg, rec, own, acc, m_acc, l_acc);
-    if (sb + 8 < S) merge_batch<8>(p, g_row, sb, cg, rec, own, acc, m_acc, l_acc);
-  }
-  if (mine && rok) {
-    const float inv = l_acc > 0.f ? 1.0f / l_acc : 0.f;      // a row that saw no key at all: zero, lse = -inf
-    u32x4 o;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) o[c] = pack_bf16(acc[2 * c] * inv, acc[2 * c + 1] * inv);
-    *reinterpret_cast<u32x4*>(static_cast<__hip_bfloat16*>(p.out) + orow * kD + cg * 8) = o;
-    if (p.lse && cg == 0) p.lse[orow] = (m_acc + log2f(l_acc)) * 0.6931471805599453f;
+  const int64_t g_row = (int64_t)pair * S * p.Mpad + row0 + L.row;
+  const uint32_t voff = (uint32_t)(((row0 + L.row) * kD + L.cl * CH) * 2);
+  if (!poll_records(p, L, g_row, c0, tag, budget, own_split)) return false;
+  // (straight-line code between every hand-issued load and its wait: the compiler does not know
+  // that the registers are still in flight, and a copy it places at a branch or a join in between
+  // would copy what was there before)
+  if (c0 + 8 < S) {
+    fetch_batch<CH, 0>(p, L.t0, pair, voff, c0);
+    fetch_batch<CH, 8>(p, L.t1, pair, voff, c0);
+    chunks_wait16(L.t0, L.t1);
+  } else {
+    fetch_batch<CH, 0>(p, L.t0, pair, voff, c0);
+    chunks_wait(L.t0);
   }
   return true;
 }
-constexpr int kLastResortPolls = 1 << 16;   // for waits that are known to end: every writer has arrived
+template <int CH>
+__device__ __forceinline__ void merge_finish(const AttnParams& p, MergeLane<CH>& L, int c0, const OwnRows& own) {
+  finish_batch<CH, 0>(p, L, L.t0, c0, own);
+  if (c0 + 8 < p.n_splits) finish_batch<CH, 8>(p, L, L.t1, c0, own);
+}
+
+// Merges rows lo <= r < hi of the row group (all passes, all splits) and writes them out.  Returns
+// false for the whole wavefront, with nothing of the current pass written, when a record was still
+// missing after `budget` polls.  Called by the two merging wavefronts, each for itself.
+template <int CH>
+__device__ __forceinline__ bool merge_rows(const AttnParams& p, int lo, int hi, int budget, uint32_t tag, int pair, int row0,
+                                           int64_t orow_pair, int mt, const OwnRows& own) {
+  for (int r0 = lo; r0 < hi; r0 += MergeLane<CH>::kRowsPerPass) {
+    MergeLane<CH> L;
+    init_lane(L, mt, r0, hi);
+    if (!__any(L.active)) continue;
+    for (int c0 = 0; c0 < p.n_splits; c0 += 16) {
+      if (!merge_fetch(p, L, pair, row0, c0, tag, budget, own.split)) return false;
+      merge_finish(p, L, c0, own);
+    }
+    store_merged(p, L, row0, orow_pair);
+  }
+  return true;
+}
 
 // Where the kernel learns which rows to fetch.
 constexpr int kResolve = 0;   // sel_idx / sel_cnt in memory, page table walked per tile
@@ -666,6 +794,8 @@ __device__ __forceinline__ int wait_polls_of(int high_half) {
 // workgroups will count in starts from zero.  Called by one thread.
 __device__ __forceinline__ void finish_call(const AttnParams& p, int64_t group, uint32_t tag) {
   __hip_atomic_store(p.tickets + group * kTicketWords + ((tag & 1u) ^ 1u), 0ull, __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(p.tickets + group * kTicketWords + 4 + ((tag & 1u) ^ 1u), 0ull, __ATOMIC_RELAXED,
                      __HIP_MEMORY_SCOPE_AGENT);
   *reinterpret_cast<uint32_t*>(p.epochs + group) = tag;      // the low half
 }
@@ -924,6 +1054,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   __shared__ uint32_t sm_pair_valid[kWaves / 2];   // (kOneTile) what wavefront w + 4 fetched: valid slots,
   __shared__ int sm_pair_draft[kWaves / 2];        // draft base (-1: cache tile, -2: nothing)
   __shared__ int sm_last;
+  __shared__ int sm_own_ready;                     // wavefronts 0 .. 3 that have left their part of the own rows in LDS
+  __shared__ int sm_one_xcd;                       // every workgroup of the group is known to run on this XCD
   __shared__ int32_t s_sel[MODE == kSelect ? kMaxSelectBlocks : 1];   // kept blocks, ascending
   __shared__ int s_exchange_failed;
 
@@ -1123,6 +1255,16 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   int n_my = 0;
   if (gw < tiles) n_my = (tiles - gw + NW - 1) / NW;
   n_my = min(n_my, kMaxTiles);
+  // Where the group's workgroups run.  Workgroups are dealt to the XCDs so that all splits of a
+  // group should share one, but nothing guarantees it: every workgroup adds one to its XCD's
+  // counter in a word of the group (no answer needed; by the last wavefront, which never waits
+  // for a particular number of its loads), and looks at the word later.  A workgroup that then
+  // finds all n_splits of them counted on its own XCD knows that every reader of its partial sits
+  // behind the same L2, and may leave the partial there instead of writing it through to memory.
+  uint64_t* const where_word = p.tickets + (int64_t)group * kTicketWords + 4 + (((uint32_t)epoch_word + 1u) & 1u);
+  const bool counts_xcds = p.n_splits >= 2 && p.n_splits <= 255;
+  if (counts_xcds && wave == kWaves - 1 && lane == 0)
+    __hip_atomic_fetch_add(where_word, 1ull << (8 * xcc_id()), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
   // per-lane parts of the load addresses: load n of a tile covers slots 4n .. 4n+3, sixteen lanes
   // per slot; chunk swizzle: 16-byte chunk c of the row in slot s sits at position c ^ (s & 15)
@@ -1253,6 +1395,10 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     wait_vmcnt<0>();
   }
   if (MODE == kGather && computes) query_fragments_arrived(qf);
+  // (the word comes back behind this wavefront's tile, which it waits for anyway)
+  uint64_t where = 0;
+  if (counts_xcds && wave == kWaves - 1 && lane == 0)
+    where = __hip_atomic_load(where_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   for (int u = 0; computes && u < n_my; ++u) {
     if (u >= issued) {                   // the single stage is free again: fetch the next tile
       cur = issue_tile(gw + u * NW, u, my_stage, false);
@@ -1292,12 +1438,13 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   }
 
   // ---- combine the computing wavefronts through LDS ---------------------------------------------
-  // Wavefront w parks its fp32 output, as it stands (relative to its own running maximum), in
-  // its own stage as [32 rows][32 float4], as soon as it is done; float4 chunk c4 of row r sits
-  // at position (c4 / 2 + 16 (c4 mod 2)) ^ r (even chunks in one half of the row, odd ones in the
-  // other), which keeps both the row-per-lane writes and the reads (sixteen lanes take the even,
-  // then the odd chunks of a row) off each other's banks.  After the one barrier the readers bring the eight slices to the
-  // common maximum while they add them.
+  // Wavefront w parks its fp32 output, as it stands (relative to its own running maximum), in its
+  // own stage as [32 rows][32 float4] straight out of the accumulator registers: float4 k * 8 +
+  // g * 4 + nt of a row holds accumulator nt, values 4k .. 4k + 3, i.e. channels 32k + 16g + 4j + nt
+  // (j = 0 .. 3), at position (that index) ^ row, which keeps the row-per-lane writes and the reads
+  // off each other's banks.  After the one barrier wavefronts 0 .. 3 (256 threads: eight per row,
+  // sixteen consecutive channels each = the four float4 with the same k, g) bring the slices to
+  // the common maximum while they add them.
   l_run = halves_sum(l_run);
   if (computes) {
     if (g == 0) {
@@ -1306,11 +1453,15 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     }
     float4* mine = reinterpret_cast<float4*>(my_stage);
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int i = 8 * (v >> 2) + 4 * g + (v & 3);        // dims 4*i .. 4*i+3
-      mine[l32 * 32 + (((i >> 1) | ((i & 1) << 4)) ^ l32)] = make_float4(oacc[0][v], oacc[1][v], oacc[2][v], oacc[3][v]);
-    }
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+        mine[l32 * 32 + ((k * 8 + g * 4 + nt) ^ l32)] =
+            make_float4(oacc[nt][4 * k], oacc[nt][4 * k + 1], oacc[nt][4 * k + 2], oacc[nt][4 * k + 3]);
   }
+  if (tid == kMergeWave0 * 64) sm_own_ready = 0;
+  if (wave == kWaves - 1 && lane == 0)
+    sm_one_xcd = counts_xcds && where == (uint64_t)p.n_splits << (8 * xcc_id()) ? 1 : 0;
   __syncthreads();
 
   if (MODE == kSelect) {
@@ -1325,114 +1476,215 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       p.gather_out[(int64_t)pair * p.gather_groups + e] = gent;
   }
 
-  // 512 threads: sixteen per row, 8 channels (two float4 chunks) each
-  const bool single = p.n_splits == 1;
-  const int r = tid >> 4, cg = tid & 15;
-  float mw = -INFINITY, lw = 0.f;
-  float fw[kSlices];
-#pragma unroll
-  for (int w = 0; w < kSlices; ++w) {
-    fw[w] = sm_m[w][r];
-    mw = fmaxf(mw, fw[w]);
-  }
-#pragma unroll
-  for (int w = 0; w < kSlices; ++w) {
-    fw[w] = fw[w] == -INFINITY ? 0.f : fast_exp2(fw[w] - mw);      // a slice that saw no token counts nothing
-    lw = __builtin_fmaf(sm_l[w][r], fw[w], lw);
-  }
-  float racc[8];
-#pragma unroll
-  for (int c = 0; c < 8; ++c) racc[c] = 0.f;
-#pragma unroll
-  for (int w = 0; w < kSlices; ++w)
-#pragma unroll
-    for (int c = 0; c < 2; ++c) {
-      const float4 t = reinterpret_cast<const float4*>(smem + w * kStageBytes)[r * 32 + ((cg | (c << 4)) ^ r)];
-      racc[4 * c] = __builtin_fmaf(t.x, fw[w], racc[4 * c]);
-      racc[4 * c + 1] = __builtin_fmaf(t.y, fw[w], racc[4 * c + 1]);
-      racc[4 * c + 2] = __builtin_fmaf(t.z, fw[w], racc[4 * c + 2]);
-      racc[4 * c + 3] = __builtin_fmaf(t.w, fw[w], racc[4 * c + 3]);
-    }
-  const int orow_row = row0 + r;
-  const bool rok = orow_row < p.M;
-  int oi = 0, oj = 0;
-  if (rok) {
-    oi = (int)(((uint64_t)(uint32_t)orow_row * p.g_magic) >> 32);
-    oj = orow_row - oi * p.G;
-  }
-  const int64_t orow = orow_pair + (int64_t)oi * p.Hq + oj;
-  OwnPartial own;
-  {
-    const float inv = lw > 0.f ? 1.0f / lw : 0.f;
-    u32x4 o;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) o[c] = pack_bf16(racc[2 * c] * inv, racc[2 * c + 1] * inv);
-    if (single) {
-      if (rok) {
-        *reinterpret_cast<u32x4*>(static_cast<__hip_bfloat16*>(p.out) + orow * kD + cg * 8) = o;
-        if (p.lse && cg == 0) p.lse[orow] = (mw + log2f(lw)) * 0.6931471805599453f;
-      }
-      return;
-    }
-    own.o = o;
-  }
-
-  // ---- the splits of a group are merged by all its workgroups, each a slice of the rows -----------
-  // Every workgroup writes its partial (normalised output in bf16) through to device-coherent
-  // memory and, once those stores have been acknowledged, a 16-byte record per row: (maximum, tag,
-  // denominator, tag), tag = this call's.  The rows of a row group are cut into slices of
-  // p.slice_rows; workgroup s then waits until the records of slice s carry the tag for every
-  // split, merges those rows in split order (bit-stable: the same sums whoever computes them) and
-  // writes out / lse.  Nothing in between needs a return trip through an atomic: after the last
-  // partial has landed the merge is one poll and one round of loads away.
+  // ---- what happens to the workgroup's result --------------------------------------------------------
+  // One split: wavefronts 0 .. 3 write out / lse.  Otherwise the splits of a group are merged by
+  // all its workgroups, each a slice of p.slice_rows rows:
+  //  - wavefronts 0 .. 3 write the workgroup's partial (normalised output in bf16) through to
+  //    device-coherent memory, leave the rows of the workgroup's own slice in LDS as well, and,
+  //    once the stores have been acknowledged, write a record per row (maximum, tag, denominator,
+  //    tag; tag = this call's);
+  //  - meanwhile wavefronts 4 and 5 wait (bounded) until the other splits' records of the slice's
+  //    rows carry the tag and fetch those partials; behind one barrier they add the own rows from
+  //    LDS, in split order (bit-stable: the same sums whoever computes them), and write out / lse.
+  //    In the workgroup that is last of its group everything but that final sum has happened by
+  //    the time its own partial exists; in the others the merge is one poll and one round of loads
+  //    behind the last record.  No return trip through an atomic lies on that path.
   // The wait is bounded.  A wavefront that runs out of patience marks its workgroup's slice as given
   // up in the group's arrival word, unless that word shows that every workgroup has arrived (then
-  // every partial is on its way and it simply keeps waiting).  Every workgroup takes a ticket from
-  // that word when it has stored its partial; the one that arrives last sees which slices were
-  // given up before it and merges them too.  So every row is merged whatever is resident when, and
-  // every wait ends.  The word of calls with an even / odd tag alternate, the last arriver clears
-  // the other one and moves the call counter on (the layout also works under graph replay).
-  own.m = mw;
-  own.l = lw;
-  own.split = split;
+  // every partial is on its way and it keeps waiting).  Every workgroup takes a ticket from that
+  // word when it has stored its partial; the one that arrives last sees which slices were given up
+  // before it and merges them too.  So every row is merged whatever is resident when, and every
+  // wait ends.  The words of calls with an even / odd tag alternate; the last arriver clears the
+  // other one and moves the call counter on (which also works under graph replay).
+  const int S = p.n_splits;
+  const bool single = S == 1;
   const uint32_t tag = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)epoch_word) + 1u;
   const int wait_polls = wait_polls_of(__builtin_amdgcn_readfirstlane((int)(uint32_t)(epoch_word >> 32)));
   uint64_t* const arrivals = p.tickets + (int64_t)group * kTicketWords + (tag & 1u);
-  {
-    const int64_t pr = ((int64_t)pair * p.n_splits + split) * p.Mpad + orow_row;
-    store_coherent16(reinterpret_cast<uint16_t*>(p.part_o) + pr * kD + cg * 8, own.o);
-    // rows 4 * wave .. 4 * wave + 3 are all this wavefront's: its own acknowledgements are enough
-    wait_vmcnt<0>();
-    if (cg == 0) {
-      const u32x4 rec = {__float_as_uint(mw), tag, __float_as_uint(lw), tag};
-      store_coherent16(p.part_rec + pr * 4, rec);
+  const int R = p.slice_rows;
+  const int lo = split * R, hi = min(lo + R, 32);            // the workgroup's own slice (empty if lo >= 32)
+  unsigned char* const own_o = x_stage;                     // [R][kD] bf16, R <= 16
+  float* const own_ml = reinterpret_cast<float*>(x_stage + 16 * kRowBytes);
+  uint64_t prev = 0;
+  int64_t pr_rec = 0;
+  float mw = -INFINITY, lw = 0.f;
+  const int r = tid >> 3, c16 = tid & 7;                     // (wavefronts 0 .. 3) row, block of 16 channels
+  if (wave < 4) {
+    float fw[kSlices];
+#pragma unroll
+    for (int w = 0; w < kSlices; ++w) {
+      fw[w] = sm_m[w][r];
+      mw = fmaxf(mw, fw[w]);
+    }
+#pragma unroll
+    for (int w = 0; w < kSlices; ++w) {
+      fw[w] = fw[w] == -INFINITY ? 0.f : fast_exp2(fw[w] - mw);      // a slice that saw no token counts nothing
+      lw = __builtin_fmaf(sm_l[w][r], fw[w], lw);
+    }
+    float racc[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) racc[c] = 0.f;
+#pragma unroll
+    for (int w = 0; w < kSlices; ++w)
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) {
+        const float4 t = reinterpret_cast<const float4*>(smem + w * kStageBytes)[r * 32 + ((c16 * 4 + nt) ^ r)];
+        racc[nt] = __builtin_fmaf(t.x, fw[w], racc[nt]);
+        racc[4 + nt] = __builtin_fmaf(t.y, fw[w], racc[4 + nt]);
+        racc[8 + nt] = __builtin_fmaf(t.z, fw[w], racc[8 + nt]);
+        racc[12 + nt] = __builtin_fmaf(t.w, fw[w], racc[12 + nt]);
+      }
+    const float inv = lw > 0.f ? __builtin_amdgcn_rcpf(lw) : 0.f;
+    u32x4 o0, o1;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      o0[c] = pack_bf16(racc[2 * c] * inv, racc[2 * c + 1] * inv);
+      o1[c] = pack_bf16(racc[8 + 2 * c] * inv, racc[8 + 2 * c + 1] * inv);
+    }
+    const int orow_row = row0 + r;
+    if (single) {
+      if (orow_row < p.M) {
+        const int oi = (int)(((uint64_t)(uint32_t)orow_row * p.g_magic) >> 32), oj = orow_row - oi * p.G;
+        const int64_t orow = orow_pair + (int64_t)oi * p.Hq + oj;
+        __hip_bfloat16* dst = static_cast<__hip_bfloat16*>(p.out) + orow * kD + c16 * 16;
+        *reinterpret_cast<u32x4*>(dst) = o0;
+        *reinterpret_cast<u32x4*>(dst + 8) = o1;
+        if (p.lse && c16 == 0) p.lse[orow] = (mw + log2f(lw)) * 0.6931471805599453f;
+      }
+    } else {
+      pr_rec = ((int64_t)pair * S + split) * p.Mpad + orow_row;
+      uint16_t* dst = reinterpret_cast<uint16_t*>(p.part_o) + pr_rec * kD + c16 * 16;
+      const bool one_xcd = sm_one_xcd != 0;               // (the same for the whole workgroup)
+      if (one_xcd) {
+        store_l2_16(dst, o0);
+        store_l2_16(dst + 8, o1);
+      } else {
+        store_coherent16(dst, o0);
+        store_coherent16(dst + 8, o1);
+      }
+      if (r >= lo && r < hi) {
+        *reinterpret_cast<u32x4*>(own_o + (r - lo) * kRowBytes + c16 * 32) = o0;
+        *reinterpret_cast<u32x4*>(own_o + (r - lo) * kRowBytes + c16 * 32 + 16) = o1;
+        if (c16 == 0) {
+          own_ml[2 * (r - lo)] = mw;
+          own_ml[2 * (r - lo) + 1] = lw;
+        }
+      }
+      // The merging wavefronts are told through a counter in LDS, not through a barrier: this
+      // wavefront must get its records out whatever they are waiting for (they wait for other
+      // workgroups' records, and those workgroups' merging wavefronts for ours).  Only the LDS
+      // writes above have to be complete, not the stores of the partial.
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      if (lane == 0) {
+        const uint32_t ready = (uint32_t)(uintptr_t)SVF_LDS_PTR(&sm_own_ready);
+        asm volatile("ds_add_u32 %0, %1" : : "v"(ready), "v"(1u) : "memory");
+      }
+      // every row is held by eight threads of one wavefront: its own acknowledgements are enough
+      wait_vmcnt<0>();
+      if (c16 == 0) {
+        const u32x4 rec = {__float_as_uint(mw), tag, __float_as_uint(lw), tag};
+        if (one_xcd) store_l2_16(p.part_rec + pr_rec * 4, rec);
+        else store_coherent16(p.part_rec + pr_rec * 4, rec);
+      }
+      if (tid == 0) prev = __hip_atomic_fetch_add(arrivals, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
-  uint64_t prev = 0;
-  if (tid == 0) prev = __hip_atomic_fetch_add(arrivals, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  const int R = p.slice_rows;
-  if (!merge_slice(p, split * R, split * R + R, wait_polls, tag, pair, row0, r, cg, orow, rok, own)) {
-    // (wave-uniform) this wavefront's rows of the slice are not merged
-    uint64_t seen = 0;
-    if (lane == 0)
-      seen = __hip_atomic_fetch_or(arrivals, 1ull << (16 + split), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const uint32_t arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)seen) & 0xffffu;
-    // everybody has arrived, the last arriver may not have seen the mark: keep waiting (it ends)
-    if (arrived == (uint32_t)p.n_splits)
-      merge_slice(p, split * R, split * R + R, kLastResortPolls, tag, pair, row0, r, cg, orow, rok, own);
+  if (single) return;
+
+  const bool merger = wave == kMergeWave0 || wave == kMergeWave0 + 1;
+  const int mt = tid - kMergeWave0 * 64;
+  const bool ch4 = R <= 4;                                   // 4 channels per merging thread, else 8
+  // one pass over the rows and one batch of records: the other splits' partials are fetched now
+#ifdef SVF_DBG_NOPREFETCH
+  const bool prefetch = false;
+#else
+  const bool prefetch = S <= 16 && R <= (ch4 ? 4 : 8) && lo < 32;
+#endif
+  MergeLane<4> L4;
+  MergeLane<8> L8;
+  bool fetched = false;
+  if (merger && prefetch) {
+    if (ch4) {
+      init_lane(L4, mt, lo, hi);
+      fetched = !__any(L4.active) || merge_fetch(p, L4, pair, row0, 0, tag, wait_polls, split);
+    } else {
+      init_lane(L8, mt, lo, hi);
+      fetched = !__any(L8.active) || merge_fetch(p, L8, pair, row0, 0, tag, wait_polls, split);
+    }
   }
-  __syncthreads();
-  if (tid == 0) {
-    const bool last = (prev & 0xffffull) == (uint64_t)(p.n_splits - 1);
-    sm_last = last ? (int)(0x10000u | (uint32_t)((prev >> 16) & 0xffffull)) : 0;
-    if (last) finish_call(p, group, tag);
+  if (merger) {
+    // the own rows are in LDS once wavefronts 0 .. 3 have all said so (they wait for nobody)
+    const uint32_t ready = (uint32_t)(uintptr_t)SVF_LDS_PTR(&sm_own_ready);
+    for (int it = 0; it < kLastResortPolls; ++it) {
+      uint32_t n;
+      asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(n) : "v"(ready) : "memory");
+      if (__builtin_amdgcn_readfirstlane((int)n) == 4) break;
+      __builtin_amdgcn_s_sleep(1);
+    }
   }
-  __syncthreads();
-  uint32_t given_up = (uint32_t)sm_last & 0xffffu;
-  while (given_up) {                       // (only in the last arriver, and only after a starved wait)
-    const int x = __builtin_ctz(given_up);
-    given_up &= given_up - 1u;
-    merge_slice(p, x * R, x * R + R, kLastResortPolls, tag, pair, row0, r, cg, orow, rok, own);
+  // Slices this wavefront still has to merge (bit x: slice x), the patience it has with them, and
+  // whether the last attempt ran out of it.
+  uint32_t todo = (merger && lo < 32) ? 1u << split : 0u;
+  int budget = wait_polls;
+  bool gave_up = false;
+  if (merger && prefetch) {
+    todo = 0u;
+    if (!fetched) {
+      gave_up = true;
+    } else {
+      const OwnRows own = {own_o, own_ml, lo, split};
+      if (ch4) {
+        if (__any(L4.active)) {
+          merge_finish(p, L4, 0, own);
+          store_merged(p, L4, row0, orow_pair);
+        }
+      } else if (__any(L8.active)) {
+        merge_finish(p, L8, 0, own);
+        store_merged(p, L8, row0, orow_pair);
+      }
+    }
+  }
+  for (int round = 0; round < 2; ++round) {
+    while (todo != 0u || gave_up) {
+      int x = split;
+      if (!gave_up) {
+        x = __builtin_ctz(todo);
+        todo &= todo - 1u;
+#ifdef SVF_DBG_NOLDS
+        const bool from_lds = false;
+#else
+        const bool from_lds = x == split;                  // the own slice's own rows are in LDS
+#endif
+        const OwnRows own = {own_o, own_ml, lo, from_lds ? split : -1};
+        const bool ok = ch4 ? merge_rows<4>(p, x * R, min(x * R + R, 32), budget, tag, pair, row0, orow_pair, mt, own)
+                            : merge_rows<8>(p, x * R, min(x * R + R, 32), budget, tag, pair, row0, orow_pair, mt, own);
+        gave_up = !ok;                                     // (only with a bounded budget: the own slice in round 0)
+      }
+      if (gave_up) {
+        gave_up = false;
+        uint64_t seen = 0;
+        if (lane == 0)
+          seen = __hip_atomic_fetch_or(arrivals, 1ull << (16 + x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)seen) & 0xffffu;
+        // everybody has arrived, the last arriver may not have seen the mark: keep waiting (it ends)
+        if (arrived == (uint32_t)S) {
+          todo |= 1u << x;
+          budget = kLastResortPolls;
+        }
+      }
+    }
+    if (round == 0) {
+      __syncthreads();
+      if (tid == 0) {
+        const bool last = (prev & 0xffffull) == (uint64_t)(S - 1);
+        sm_last = last ? (int)((uint32_t)(prev >> 16) & 0xffffu) : 0;
+        if (last) finish_call(p, group, tag);
+      }
+      __syncthreads();
+      // (only in the last arriver, and only after a starved wait somewhere in the group)
+      todo = merger ? (uint32_t)sm_last : 0u;
+      budget = kLastResortPolls;
+    }
   }
 }
 
