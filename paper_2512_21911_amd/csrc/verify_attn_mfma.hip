@@ -1595,11 +1595,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   const int mt = tid - kMergeWave0 * 64;
   const bool ch4 = R <= 4;                                   // 4 channels per merging thread, else 8
   // one pass over the rows and one batch of records: the other splits' partials are fetched now
-#ifdef SVF_DBG_NOPREFETCH
-  const bool prefetch = false;
-#else
   const bool prefetch = S <= 16 && R <= (ch4 ? 4 : 8) && lo < 32;
-#endif
   MergeLane<4> L4;
   MergeLane<8> L8;
   bool fetched = false;
@@ -1650,11 +1646,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       if (!gave_up) {
         x = __builtin_ctz(todo);
         todo &= todo - 1u;
-#ifdef SVF_DBG_NOLDS
-        const bool from_lds = false;
-#else
         const bool from_lds = x == split;                  // the own slice's own rows are in LDS
-#endif
         const OwnRows own = {own_o, own_ml, lo, from_lds ? split : -1};
         const bool ok = ch4 ? merge_rows<4>(p, x * R, min(x * R + R, 32), budget, tag, pair, row0, orow_pair, mt, own)
                             : merge_rows<8>(p, x * R, min(x * R + R, 32), budget, tag, pair, row0, orow_pair, mt, own);
