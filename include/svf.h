@@ -158,6 +158,23 @@ int svf_verify_attn(const svf_shape_t* shape, const void* q, const void* K, cons
                     void* out, float* lse_or_null, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * svf_verify_attn for callers that cannot allocate (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same result, bit for bit, with the workspace in a
+ * static device array of svf_static_workspace_bytes() bytes (16 MiB) that every GPU the library
+ * runs on holds until the process ends.  The call allocates and frees nothing and does not
+ * synchronise; it enqueues one small fill kernel ahead of the attention kernels (the array keeps
+ * the last call's contents, of whatever shape).  A shape whose svf_workspace_bytes exceeds the
+ * array: SVF_ERR_WORKSPACE, nothing enqueued.  All calls on one GPU share that GPU's array:
+ * calls that overlap in time on one GPU (different streams, different threads) race; order them.
+ */
+size_t svf_static_workspace_bytes(void);
+int svf_verify_attn_static_ws(const svf_shape_t* shape, const void* q, const void* K, const void* V,
+                              const int32_t* block_table, const int32_t* seq_lens,
+                              const void* k_draft, const void* v_draft, const uint64_t* draft_mask_or_null,
+                              const int32_t* sel_idx, const int32_t* sel_cnt,
+                              void* out, float* lse_or_null, void* stream);
+
+/*
  * One layer of one verification step with inter-layer retrieval reuse (Sec. 3.3, Eq. 9).
  * mode SVF_STEP_ANCHOR (anchor layer): svf_score_select into sel_idx / sel_cnt, then
  *   svf_verify_attn.  The call also leaves in `ws` a gather list: where in the cache pools the

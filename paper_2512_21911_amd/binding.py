@@ -63,6 +63,7 @@ _lib = None
 
 EXPORTS = ["svf_version", "svf_strerror", "svf_budget_blocks", "svf_workspace_bytes", "svf_workspace_init",
            "svf_block_reps", "svf_score_select", "svf_verify_attn", "svf_verify_step", "svf_workspace_set_wait_polls",
+           "svf_static_workspace_bytes", "svf_verify_attn_static_ws",
            "svf_mask_words", "svf_analytics_workspace_bytes", "svf_select_per_draft", "svf_masks_from_selection",
            "svf_overlap_by_distance", "svf_jaccard_adjacent", "svf_topk_anchors",
            "svf_block_summaries", "svf_retrieve", "svf_ffn_workspace_bytes", "svf_sparse_ffn",
@@ -80,6 +81,10 @@ def lib() -> ctypes.CDLL:
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
         shp = ctypes.POINTER(SvfShape)
         L.svf_version.restype = ctypes.c_int
+        L.svf_static_workspace_bytes.restype = ctypes.c_size_t
+        L.svf_static_workspace_bytes.argtypes = []
+        L.svf_verify_attn_static_ws.restype = ctypes.c_int
+        L.svf_verify_attn_static_ws.argtypes = [shp] + [vp] * 13
         L.svf_workspace_set_wait_polls.restype = ctypes.c_int
         L.svf_workspace_set_wait_polls.argtypes = [shp, vp, ctypes.c_size_t, ctypes.c_int, vp]
         L.svf_mask_words.restype = i32
@@ -211,6 +216,18 @@ def svf_verify_attn(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, dra
                                  _ptr(seq_lens), _ptr(k_draft), _ptr(v_draft), _ptr(draft_mask),
                                  _ptr(sel_idx), _ptr(sel_cnt), _ptr(out), _ptr(lse), _ptr(ws), ws.numel(),
                                  _stream()), "svf_verify_attn")
+
+
+def svf_verify_attn_static_ws(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask, sel_idx, sel_cnt,
+                              out, lse=None):
+    _check(lib().svf_verify_attn_static_ws(ctypes.byref(shape), _ptr(q), _ptr(K), _ptr(V), _ptr(block_table),
+                                           _ptr(seq_lens), _ptr(k_draft), _ptr(v_draft), _ptr(draft_mask),
+                                           _ptr(sel_idx), _ptr(sel_cnt), _ptr(out), _ptr(lse), _stream()),
+           "svf_verify_attn_static_ws")
+
+
+def svf_static_workspace_bytes() -> int:
+    return int(lib().svf_static_workspace_bytes())
 
 
 SVF_STEP_REUSE, SVF_STEP_ANCHOR, SVF_STEP_REUSE_GATHER = 0, 1, 2

@@ -3,6 +3,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "svf_device.h"
@@ -135,6 +136,17 @@ namespace {
 __global__ void set_wait_polls_kernel(uint64_t* epochs, size_t n, uint32_t high_half) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) reinterpret_cast<uint32_t*>(epochs + i)[1] = high_half;
+}
+
+// zeroes up to three byte ranges (multiples of 16) of one buffer in one launch
+struct ZeroRanges { size_t off[3], bytes[3]; };
+__global__ void zero_ranges_kernel(char* base, ZeroRanges r) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (int k = 0; k < 3; ++k) {
+    uint4* p = reinterpret_cast<uint4*>(base + r.off[k]);
+    const size_t n16 = r.bytes[k] / 16;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+  }
 }
 
 __global__ void fill_zero_kernel(uint4* p, size_t n16) {
@@ -429,6 +441,73 @@ int svf_verify_attn(const svf_shape_t* shape, const void* q, const void* K, cons
                     void* stream) {
   return verify_attn_impl(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask_or_null, sel_idx,
                           sel_cnt, out, lse_or_null, ws, ws_bytes, stream, false);
+}
+
+// ---- the entry point that allocates nothing ---------------------------------------------------------
+// Its workspace is this array (one copy per GPU, held until the process ends).  In host code the
+// array's name is only a stand-in: the device address comes from hipGetSymbolAddress, once per device.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];          // per device, set on that device's first call
+
+// Device address of `scratch` on the current device, or nullptr (with *rc set) on failure.
+void* static_scratch(int* rc) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    *rc = SVF_ERR_HIP;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      *rc = SVF_ERR_HIP;
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+size_t svf_static_workspace_bytes(void) { return kStaticScratchBytes; }
+
+int svf_verify_attn_static_ws(const svf_shape_t* shape, const void* q, const void* K, const void* V,
+                              const int32_t* block_table, const int32_t* seq_lens, const void* k_draft,
+                              const void* v_draft, const uint64_t* draft_mask_or_null, const int32_t* sel_idx,
+                              const int32_t* sel_cnt, void* out, float* lse_or_null, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!q || !K || !V || !seq_lens || !k_draft || !v_draft || !sel_idx || !sel_cnt || !out ||
+      (shape->page_size > 0 && !block_table))
+    return SVF_ERR_NULL;
+  if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(k_draft) || misaligned(v_draft) ||
+      misaligned(out))
+    return SVF_ERR_SHAPE;
+  // a shape whose workspace does not fit the array is refused
+  if (svf_workspace_bytes(shape) > kStaticScratchBytes) return SVF_ERR_WORKSPACE;
+  void* ws = static_scratch(&rc);
+  if (!ws) return rc;
+  // The array keeps what the last call left, of whatever shape: everything the kernels expect to
+  // find zero (arrival words, call counters, exchanged keys, and the tagged records, whose tags
+  // restart with the counters) is cleared first, by a fill kernel on the caller's stream.
+  const AttnPlan pl = plan_attn(*shape);
+  ZeroRanges zr;
+  zr.off[0] = pl.off_tickets;
+  zr.bytes[0] = pl.off_o - pl.off_tickets;
+  zr.off[1] = pl.off_m;
+  zr.bytes[1] = pl.off_gather - pl.off_m;
+  zr.off[2] = pl.off_xkeys;
+  zr.bytes[2] = pl.bytes - pl.off_xkeys;
+  hipLaunchKernelGGL(zero_ranges_kernel, dim3(64), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<char*>(ws), zr);
+  if (hipGetLastError() != hipSuccess) return SVF_ERR_HIP;
+  return verify_attn_impl(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask_or_null, sel_idx,
+                          sel_cnt, out, lse_or_null, ws, kStaticScratchBytes, stream, false);
 }
 
 int svf_verify_step(const svf_shape_t* shape, int mode, const void* q, const float* reps,
