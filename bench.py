@@ -71,6 +71,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=32, help="layers the CPU oracle is timed on")
     ap.add_argument("--profile-only", default="", help="run only this many steps of the timed loop (for rocprofv3)")
+    ap.add_argument("--mfma-vs-valu", action="store_true",
+                    help="time the attention of the configuration's layers with the matrix-core kernel and with the "
+                         "vector-ALU kernel (svf_diag_verify_attn) instead of the step; with --profile-only N just run "
+                         "N passes of each for the profiler")
     ap.add_argument("--analytics", action="store_true",
                     help="time the retrieval analytics (per-draft block sets, overlap, Jaccard) instead of the step")
     ap.add_argument("--variants", action="store_true",
@@ -83,6 +87,97 @@ def parse():
                     help="time the per-token rules (expert skipping, Sec. 3.5; acceptance / resampling, Sec. 2.1) instead "
                          "of the step")
     return ap.parse_args()
+
+
+def mfma_vs_valu(args):
+    """The attention launch of every layer of the configuration (blocks already selected) with the kernel
+    svf_verify_attn picks for the shape (matrix cores for bf16, d = 128) and with the vector-ALU kernel
+    forced, each as one captured HIP graph over independent layers.  One JSON line."""
+    import numpy as np
+    import torch
+    import paper_2512_21911_amd as S
+    import workloads as W
+
+    torch.cuda.set_device(0)
+    S.lib()
+    cfg = W.CONFIGS[args.cfg]
+    n_layers = args.layers or (cfg.n_layers if cfg.n_layers > 1 else 16)
+    layers = [W.make_layer(cfg, l, device="cuda") for l in range(n_layers)]
+    x0 = layers[0]
+    shape = S.make_shape(B=cfg.B, gamma=cfg.gamma, Hq=cfg.Hq, Hkv=cfg.Hkv, d=cfg.d, dtype=cfg.dtype,
+                         block_size=cfg.block_size, max_seq_len=cfg.T, k_blocks=cfg.k_blocks, k_pool=x0["k_pool"],
+                         page_size=cfg.page_size,
+                         max_pages_per_seq=(x0["block_table"].shape[1] if x0["block_table"] is not None else 0))
+    ws = S.new_workspace(shape)
+    reps = torch.zeros(cfg.B, cfg.Hkv, cfg.nb_max, cfg.d, device="cuda")
+    idx = [torch.zeros(cfg.B, cfg.Hkv, cfg.k_blocks, dtype=torch.int32, device="cuda") for _ in range(n_layers)]
+    cnt = [torch.zeros(cfg.B, cfg.Hkv, dtype=torch.int32, device="cuda") for _ in range(n_layers)]
+    for l, x in enumerate(layers):
+        S.svf_block_reps(shape, x["k_pool"], x["block_table"], x["seq_lens"], reps)
+        S.svf_score_select(shape, x["q"], reps, x["seq_lens"], idx[l], cnt[l], ws)
+    torch.cuda.synchronize()
+    outs = {k: torch.zeros(cfg.B, cfg.gamma, cfg.Hq, cfg.d, device="cuda", dtype=cfg.torch_dtype)
+            for k in (S.SVF_KERNEL_AUTO, S.SVF_KERNEL_VECTOR_ALU)}
+    wss = {k: S.new_diag_workspace(shape, k) for k in outs}
+
+    def run(kernel):
+        for l, x in enumerate(layers):
+            S.svf_diag_verify_attn(shape, kernel, x["q"], x["k_pool"], x["v_pool"], x["block_table"], x["seq_lens"],
+                                   x["k_draft"], x["v_draft"], x["draft_mask"], idx[l], cnt[l], outs[kernel], wss[kernel])
+
+    if args.profile_only:
+        for k in outs:
+            for _ in range(int(args.profile_only)):
+                run(k)
+        torch.cuda.synchronize()
+        print(json.dumps({"profile_only_passes": int(args.profile_only), "workload": cfg.name, "layers": n_layers}))
+        return
+
+    us = {}
+    for k in outs:
+        run(k)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            run(k)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            run(k)
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(args.steps):
+            graph.replay()
+        b.record()
+        torch.cuda.synchronize()
+        us[k] = a.elapsed_time(b) / args.steps * 1e3 / n_layers
+    diff = float((outs[S.SVF_KERNEL_AUTO].float() - outs[S.SVF_KERNEL_VECTOR_ALU].float()).abs().max())
+    tol = 2e-2 if cfg.dtype == "bf16" else 1e-4
+    if not diff <= tol:
+        raise SystemExit(f"bench --mfma-vs-valu: the two kernels disagree on the last layer (max-abs {diff:.3e})")
+    bytes_ = W.algorithmic_bytes(cfg, x0["seq_lens"].cpu())["verify_attn"]
+    M = cfg.gamma * (cfg.Hq // cfg.Hkv)
+    line = {"metric": f"verify-attn us/launch, matrix-core vs vector-ALU kernel ({cfg.name})",
+            "value": round(us[S.SVF_KERNEL_AUTO], 3), "unit": "us/launch", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": round(us[S.SVF_KERNEL_AUTO] * 1e-3, 6), "higher_is_better": False,
+            "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+            "config": {"workload": cfg.name, "layers": n_layers, "query_rows_per_kv_head": M, "launch": "hipgraph"},
+            "roofline": {"bound": "hbm", "kernel": "verify_attn_mfma_kernel (sel_idx resolved in the kernel)",
+                         "achieved": round(bytes_ / (us[S.SVF_KERNEL_AUTO] * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS,
+                         "unit": "GB/s", "frac": round(bytes_ / (us[S.SVF_KERNEL_AUTO] * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                         "traffic": None, "algorithmic_bytes_per_launch": bytes_,
+                         "avg_launch_us": round(us[S.SVF_KERNEL_AUTO], 3)},
+            "cpu_baseline": None,
+            "extra": {"matrix_core_kernel_us": round(us[S.SVF_KERNEL_AUTO], 3),
+                      "vector_alu_kernels_us": round(us[S.SVF_KERNEL_VECTOR_ALU], 3),
+                      "vector_alu_over_matrix_core": round(us[S.SVF_KERNEL_VECTOR_ALU] / us[S.SVF_KERNEL_AUTO], 2),
+                      "max_abs_difference_of_outputs": diff}}
+    print(json.dumps(line))
 
 
 def analytics(args):
@@ -529,6 +624,9 @@ def main():
     import workloads as W
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.mfma_vs_valu:
+        mfma_vs_valu(args)
+        return
     if args.analytics:
         analytics(args)
         return

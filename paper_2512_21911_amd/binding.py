@@ -63,7 +63,7 @@ _lib = None
 
 EXPORTS = ["svf_version", "svf_strerror", "svf_budget_blocks", "svf_workspace_bytes", "svf_workspace_init",
            "svf_block_reps", "svf_score_select", "svf_verify_attn", "svf_verify_step", "svf_workspace_set_wait_polls",
-           "svf_static_workspace_bytes", "svf_verify_attn_static_ws",
+           "svf_static_workspace_bytes", "svf_verify_attn_static_ws", "svf_diag_workspace_bytes", "svf_diag_verify_attn",
            "svf_mask_words", "svf_analytics_workspace_bytes", "svf_select_per_draft", "svf_masks_from_selection",
            "svf_overlap_by_distance", "svf_jaccard_adjacent", "svf_topk_anchors",
            "svf_block_summaries", "svf_retrieve", "svf_ffn_workspace_bytes", "svf_sparse_ffn",
@@ -85,6 +85,10 @@ def lib() -> ctypes.CDLL:
         L.svf_static_workspace_bytes.argtypes = []
         L.svf_verify_attn_static_ws.restype = ctypes.c_int
         L.svf_verify_attn_static_ws.argtypes = [shp] + [vp] * 13
+        L.svf_diag_workspace_bytes.restype = ctypes.c_size_t
+        L.svf_diag_workspace_bytes.argtypes = [shp, ctypes.c_int]
+        L.svf_diag_verify_attn.restype = ctypes.c_int
+        L.svf_diag_verify_attn.argtypes = [shp, ctypes.c_int] + [vp] * 13 + [ctypes.c_size_t, vp]
         L.svf_workspace_set_wait_polls.restype = ctypes.c_int
         L.svf_workspace_set_wait_polls.argtypes = [shp, vp, ctypes.c_size_t, ctypes.c_int, vp]
         L.svf_mask_words.restype = i32
@@ -224,6 +228,24 @@ def svf_verify_attn_static_ws(shape, q, K, V, block_table, seq_lens, k_draft, v_
                                            _ptr(seq_lens), _ptr(k_draft), _ptr(v_draft), _ptr(draft_mask),
                                            _ptr(sel_idx), _ptr(sel_cnt), _ptr(out), _ptr(lse), _stream()),
            "svf_verify_attn_static_ws")
+
+
+SVF_KERNEL_AUTO, SVF_KERNEL_VECTOR_ALU = 0, 1
+
+
+def new_diag_workspace(shape, kernel, device="cuda") -> torch.Tensor:
+    n = int(lib().svf_diag_workspace_bytes(ctypes.byref(shape), int(kernel)))
+    if n == 0:
+        raise SvfError(-2, "svf_diag_workspace_bytes")
+    return torch.zeros(n, dtype=torch.uint8, device=device)
+
+
+def svf_diag_verify_attn(shape, kernel, q, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask, sel_idx, sel_cnt,
+                         out, ws, lse=None):
+    _check(lib().svf_diag_verify_attn(ctypes.byref(shape), int(kernel), _ptr(q), _ptr(K), _ptr(V), _ptr(block_table),
+                                      _ptr(seq_lens), _ptr(k_draft), _ptr(v_draft), _ptr(draft_mask), _ptr(sel_idx),
+                                      _ptr(sel_cnt), _ptr(out), _ptr(lse), _ptr(ws), ws.numel(), _stream()),
+           "svf_diag_verify_attn")
 
 
 def svf_static_workspace_bytes() -> int:

@@ -86,12 +86,12 @@ int hip_code(hipError_t e) { return e == hipSuccess ? SVF_OK : SVF_ERR_HIP; }
 
 // Workspace layout: [tickets | partial o | partial m, l / records | gather list | exchanged keys | epoch words],
 // then (svf_workspace_bytes) the block scores of a selection whose caller does not ask for them
-AttnPlan plan_attn(const svf_shape_t& s) {
+AttnPlan plan_attn(const svf_shape_t& s, bool allow_mfma) {
   AttnPlan pl;
   const int G = s.Hq / s.Hkv;
   pl.M = s.gamma * G;
   pl.Mpad = (pl.M + 31) / 32 * 32;
-  pl.mfma = mfma_supported(s);
+  pl.mfma = allow_mfma && mfma_supported(s);
   if (pl.mfma) {
     pl.n_splits = mfma_rows_mode(s) ? mfma_rows_splits(s) : mfma_splits(s);
   } else {
@@ -355,7 +355,8 @@ static int verify_attn_impl(const svf_shape_t* shape, const void* q, const void*
                             const int32_t* block_table, const int32_t* seq_lens, const void* k_draft,
                             const void* v_draft, const uint64_t* draft_mask_or_null, const int32_t* sel_idx,
                             const int32_t* sel_cnt, void* out, float* lse_or_null, void* ws, size_t ws_bytes,
-                            void* stream, bool use_gather, const float* reps_to_select_from = nullptr) {
+                            void* stream, bool use_gather, const float* reps_to_select_from = nullptr,
+                            bool allow_mfma = true) {
   int rc = check_shape(shape);
   if (rc) return rc;
   if (!q || !K || !V || !seq_lens || !k_draft || !v_draft || !sel_idx || !sel_cnt || !out ||
@@ -366,7 +367,8 @@ static int verify_attn_impl(const svf_shape_t* shape, const void* q, const void*
     return SVF_ERR_SHAPE;
   rc = check_ws(shape, ws, ws_bytes);
   if (rc) return rc;
-  const AttnPlan pl = plan_attn(*shape);
+  const AttnPlan pl = plan_attn(*shape, allow_mfma);
+  if (!allow_mfma && ws_bytes < pl.bytes) return SVF_ERR_WORKSPACE;
   char* w = static_cast<char*>(ws);
   AttnParams p;
   p.kv = layout_of(*shape);
@@ -508,6 +510,24 @@ int svf_verify_attn_static_ws(const svf_shape_t* shape, const void* q, const voi
   if (hipGetLastError() != hipSuccess) return SVF_ERR_HIP;
   return verify_attn_impl(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask_or_null, sel_idx,
                           sel_cnt, out, lse_or_null, ws, kStaticScratchBytes, stream, false);
+}
+
+// ---- diagnostics (include/svf_diag.h): the attention with the kernel chosen by the caller ---------
+size_t svf_diag_workspace_bytes(const svf_shape_t* shape, int kernel) {
+  if (check_shape(shape) != SVF_OK || (kernel != 0 && kernel != 1)) return 0;
+  const size_t own = plan_attn(*shape, kernel == 0).bytes + scores_bytes(*shape);
+  const size_t usual = svf_workspace_bytes(shape);
+  return own > usual ? own : usual;
+}
+
+int svf_diag_verify_attn(const svf_shape_t* shape, int kernel, const void* q, const void* K, const void* V,
+                         const int32_t* block_table, const int32_t* seq_lens, const void* k_draft,
+                         const void* v_draft, const uint64_t* draft_mask_or_null, const int32_t* sel_idx,
+                         const int32_t* sel_cnt, void* out, float* lse_or_null, void* ws, size_t ws_bytes,
+                         void* stream) {
+  if (kernel != 0 && kernel != 1) return SVF_ERR_SHAPE;
+  return verify_attn_impl(shape, q, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask_or_null, sel_idx,
+                          sel_cnt, out, lse_or_null, ws, ws_bytes, stream, false, nullptr, kernel == 0);
 }
 
 int svf_verify_step(const svf_shape_t* shape, int mode, const void* q, const float* reps,

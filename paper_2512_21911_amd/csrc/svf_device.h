@@ -259,6 +259,6 @@ struct AttnPlan {
   size_t off_o, off_m, off_l, off_tickets, off_gather, off_xkeys, off_epochs, bytes;
   size_t groups;             // (sequence, KV head, row group) triples: entries of tickets / epochs
 };
-AttnPlan plan_attn(const svf_shape_t& s);
+AttnPlan plan_attn(const svf_shape_t& s, bool allow_mfma = true);
 
 }  // namespace svf
