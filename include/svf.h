@@ -150,6 +150,14 @@ int svf_score_select(const svf_shape_t* shape, const void* q, const float* reps,
  * draft query (b, i, j) attends to all tokens of the blocks sel_idx[b][j / G][0..sel_cnt)
  * that lie below seq_lens[b], and to the drafts t allowed by its mask, under one softmax
  * with scale sm_scale; out = sum of softmax weights times values.  lse_or_null is optional.
+ * A query row that sees no key at all (no selected token and a draft mask without its own bit)
+ * gets out = 0 and lse = -inf.
+ * Arithmetic of the bf16 path (d = 128): products of bf16 inputs accumulate in fp32; softmax
+ * weights are rounded to bf16 before they multiply V; when the selected tokens are cut into
+ * several splits (long budgets), each split's output, normalised by its own denominator, is
+ * rounded to bf16 once before the splits are summed in fp32 in split order.  The result is the
+ * same bits from call to call and does not depend on how the workgroups happen to be scheduled.
+ * The fp32 path and other head dimensions keep everything in fp32.
  */
 int svf_verify_attn(const svf_shape_t* shape, const void* q, const void* K, const void* V,
                     const int32_t* block_table, const int32_t* seq_lens,

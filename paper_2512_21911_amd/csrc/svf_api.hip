@@ -112,7 +112,7 @@ AttnPlan plan_attn(const svf_shape_t& s, bool allow_mfma) {
   pl.off_o = off;
   off += align_up(pairs * pl.n_splits * pl.Mpad * s.d * (pl.mfma ? sizeof(uint16_t) : sizeof(float)));
   // maxima and denominators: two fp32 arrays for the vector-ALU kernel; 16 bytes per split and row
-  // for the matrix-core kernels (a tagged record, or an (m, l) pair in the many-rows kernel)
+  // for the matrix-core kernels (a tagged record)
   pl.off_m = off;
   pl.off_l = off + pairs * pl.n_splits * pl.Mpad * sizeof(float);
   off += align_up((pl.mfma ? 4 : 2) * pairs * pl.n_splits * pl.Mpad * sizeof(float));
@@ -388,7 +388,6 @@ static int verify_attn_impl(const svf_shape_t* shape, const void* q, const void*
   p.part_o = reinterpret_cast<float*>(w + pl.off_o);
   p.part_m = reinterpret_cast<float*>(w + pl.off_m);
   p.part_l = reinterpret_cast<float*>(w + pl.off_l);
-  p.part_ml = p.part_m;
   p.part_rec = reinterpret_cast<uint32_t*>(p.part_m);
   p.gather = (use_gather && pl.gather) ? reinterpret_cast<const uint64_t*>(w + pl.off_gather) : nullptr;
   p.gather_groups = pl.gather_groups;

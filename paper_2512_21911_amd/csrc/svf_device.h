@@ -96,13 +96,11 @@ struct AttnParams {
   // split partials.  Vector-ALU kernel: fp32 unnormalised outputs [B][Hkv][S][Mpad][d] with their
   // running maxima (log2 domain) and denominators in part_m / part_l.  Matrix-core kernels: outputs
   // normalised by their own denominator and rounded to bf16, [B][Hkv][S][Mpad][d] 2-byte elements
-  // in part_o; the many-rows kernel keeps (maximum, denominator) pairs in part_ml, the kernel for up
-  // to two row groups 16-byte records (maximum, tag, denominator, tag) in part_rec, valid for the
-  // call whose tag both halves carry.  part_m, part_ml and part_rec name the same region.
+  // in part_o, and 16-byte records (maximum, tag, denominator, tag) in part_rec, valid for the call
+  // whose tag both halves carry.  part_m and part_rec name the same region.
   float* part_o;
   float* part_m;               // [B][Hkv][S][Mpad]
   float* part_l;               // [B][Hkv][S][Mpad]
-  float* part_ml;              // [B][Hkv][S][Mpad][2]
   uint32_t* part_rec;          // [B][Hkv][S][Mpad][4]
   // per (pair, row group) eight 64-bit words: [0], [1] arrival word of calls with an even / odd
   // tag (bits 15:0 arrivals, bits 31:16 slices given up), [2] arrival counter of the kernels that

@@ -42,12 +42,21 @@
 // kRescaleGap.  P is rounded to bf16 (hardware RNE) for the second product; accumulators fp32.
 //
 // Merge.  The computing wavefronts combine through LDS (log-sum-exp rule).  With one split the
-// workgroup writes out / lse itself.  Otherwise it writes a partial (normalised output in bf16,
-// (m, l) in fp32) through to device-coherent memory, and the last workgroup to arrive for that
-// group (atomic ticket) merges all splits in split order.  The ticket also counts arrivals per
-// XCD: if every partial was written through the L2 the merging workgroup reads from, loads that
-// bypass only the per-CU cache are enough; otherwise it first performs a device-scope acquire.
-// Workgroup ids are mapped so that all splits of a group share id mod 8 (one XCD).
+// workgroup writes out / lse itself.  Otherwise every workgroup of a (pair, row group) stores a
+// partial (normalised output in bf16, (m, l) in fp32 inside a 16-byte record that carries the
+// call's tag twice) and then merges a slice of the rows itself: two of its wavefronts prefetch
+// the other splits' partials for that slice, wait (a bounded number of polls) until every
+// record shows the tag, and sum in split order, taking the own split from LDS.  No workgroup
+// waits for all others and none is the designated merger; a slice whose wait ran out is marked
+// in the group's arrival word and merged by whichever workgroup arrives last.  The tag is the
+// group's call counter plus one, kept in the workspace and advanced by the workgroup that
+// arrives last, so the kernel needs no clearing between calls.
+//
+// Scope of the exchange.  Workgroup ids are mapped so that all splits of a group share id mod 8,
+// which the dispatcher places on one XCD; each workgroup also adds its XCD number to a
+// per-group counter, and only if every arrival so far came from the XCD it runs on does it
+// store its partial with plain stores (acknowledged by that XCD's L2, where the readers' L1-
+// bypassing loads are served).  Otherwise partials and records are written through to memory.
 #include <hip/hip_bf16.h>
 
 #include "svf_device.h"
@@ -208,24 +217,12 @@ __device__ __forceinline__ void wait_vmcnt_upto16(int n) {
   }
 }
 
-// Loads of a partial by the merging workgroup when the data is known to sit in, or behind,
-// this XCD's L2: only the per-CU cache has to be bypassed (sc0).  Issued by hand; the values are
-// not valid until merge_loads_wait() has been given the registers.
-__device__ __forceinline__ u32x4 load16_bypass_l1(const void* p) {
-  u32x4 v;
-  asm volatile("global_load_dwordx4 %0, %1, off sc0" : "=v"(v) : "v"(p) : "memory");
-  return v;
-}
-__device__ __forceinline__ u32x2 load8_bypass_l1(const void* p) {
-  u32x2 v;
-  asm volatile("global_load_dwordx2 %0, %1, off sc0" : "=v"(v) : "v"(p) : "memory");
-  return v;
-}
-__device__ __forceinline__ void merge_loads_wait(u32x4 (&o)[8], u32x2& ml) {
-  asm volatile("s_waitcnt vmcnt(0)"
-               : "+v"(o[0]), "+v"(o[1]), "+v"(o[2]), "+v"(o[3]), "+v"(o[4]), "+v"(o[5]), "+v"(o[6]), "+v"(o[7]), "+v"(ml)
-               :
-               : "memory");
+// Lane i ^ 4 of every lane i (two row rotations, each written to the banks of four lanes it is
+// right for: banks 0 and 2 take lane i + 4, banks 1 and 3 lane i - 4).
+__device__ __forceinline__ uint32_t swap_lanes_xor4(uint32_t x) {
+  int t = __builtin_amdgcn_update_dpp((int)x, (int)x, 0x12C, 0xf, 0x5, false);    // row_ror:12
+  t = __builtin_amdgcn_update_dpp(t, (int)x, 0x124, 0xf, 0xA, false);             // row_ror:4
+  return (uint32_t)t;
 }
 // Lane N of every row of sixteen lanes, to all lanes of that row.
 template <int N>
@@ -384,12 +381,10 @@ __device__ __forceinline__ void process_tile(uint32_t stage, const bf16x8 (&qf)[
   }
 }
 
-// Final merge of a group's split partials by its last workgroup (512 threads): sixteen threads
-// per row, 8 channels each.  All splits, the workgroup's own included, are read back in split
-// order, so the result does not depend on which workgroup happened to arrive last; the loads of
-// kMergeBatch splits are in flight before the first is used.  A split's (m, l) is loaded by one
-// of the row's sixteen threads and handed round inside the row.
-template <bool LOCAL>
+// Merge of a group's split partials by one workgroup (512 threads), used behind the rows
+// kernel: sixteen threads per row, 8 channels each.  All splits are read in split order; the
+// loads of kMergeBatch splits are in flight before the first is used.  A split's (m, l) is
+// loaded by one of the row's sixteen threads and handed round inside the row.
 __device__ __forceinline__ void merge_splits(const AttnParams& p, int64_t g_row, int64_t orow, bool row_ok, int cg) {
   constexpr int kMergeBatch = 8;
   const uint16_t* part_o = reinterpret_cast<const uint16_t*>(p.part_o);
@@ -400,20 +395,17 @@ __device__ __forceinline__ void merge_splits(const AttnParams& p, int64_t g_row,
   for (int s0 = 0; s0 < p.n_splits; s0 += kMergeBatch) {
     u32x4 t[kMergeBatch];
     u32x2 ml;                        // of split s0 + cg mod 8
-    // (straight-line code between the hand-issued loads and their wait)
     {
       const int64_t pr = g_row + (int64_t)min(s0 + (cg & (kMergeBatch - 1)), p.n_splits - 1) * p.Mpad;
-      if (LOCAL) ml = load8_bypass_l1(p.part_ml + 2 * pr);
-      else ml = *reinterpret_cast<const u32x2*>(p.part_ml + 2 * pr);
+      const u32x4 rec = *reinterpret_cast<const u32x4*>(p.part_rec + 4 * pr);     // (maximum, tag, denominator, tag)
+      ml = u32x2{rec[0], rec[2]};
     }
 #pragma unroll
     for (int u = 0; u < kMergeBatch; ++u) {
       // entries past the last split (index clamped) get weight 0 below
       const int64_t pr = g_row + (int64_t)min(s0 + u, p.n_splits - 1) * p.Mpad;
-      if (LOCAL) t[u] = load16_bypass_l1(part_o + pr * kD + cg * 8);
-      else t[u] = *reinterpret_cast<const u32x4*>(part_o + pr * kD + cg * 8);
+      t[u] = *reinterpret_cast<const u32x4*>(part_o + pr * kD + cg * 8);
     }
-    if (LOCAL) merge_loads_wait(t, ml);
     uint32_t mbits[kMergeBatch], lbits[kMergeBatch];
     row_lanes_upto<kMergeBatch - 1>(ml[0], mbits);
     row_lanes_upto<kMergeBatch - 1>(ml[1], lbits);
@@ -1553,14 +1545,24 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       }
     } else {
       pr_rec = ((int64_t)pair * S + split) * p.Mpad + orow_row;
-      uint16_t* dst = reinterpret_cast<uint16_t*>(p.part_o) + pr_rec * kD + c16 * 16;
+      // Each of the two store instructions covers whole 128-byte lines (the eight threads of a row
+      // write eight consecutive 16-byte chunks; threads c and c ^ 4 trade their second chunk): the
+      // L2 then passes complete lines on instead of twice as many half-written ones.
+      const bool low = c16 < 4;
+      u32x4 got;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) got[c] = swap_lanes_xor4(o1[c]);
+      const u32x4 first = low ? o0 : got, second = low ? got : o0;
+      uint16_t* dst = reinterpret_cast<uint16_t*>(p.part_o) + pr_rec * kD;
+      uint16_t* dst0 = dst + (low ? 2 * c16 : 2 * c16 - 7) * 8;
+      uint16_t* dst1 = dst + (low ? 2 * c16 + 9 : 2 * c16) * 8;
       const bool one_xcd = sm_one_xcd != 0;               // (the same for the whole workgroup)
       if (one_xcd) {
-        store_l2_16(dst, o0);
-        store_l2_16(dst + 8, o1);
+        store_l2_16(dst0, first);
+        store_l2_16(dst1, second);
       } else {
-        store_coherent16(dst, o0);
-        store_coherent16(dst + 8, o1);
+        store_coherent16(dst0, first);
+        store_coherent16(dst1, second);
       }
       if (r >= lo && r < hi) {
         *reinterpret_cast<u32x4*>(own_o + (r - lo) * kRowBytes + c16 * 32) = o0;
@@ -1688,11 +1690,12 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
 // fetches the four-token group w: one K and one V load) into a ring of nine 16 KB stages; one
 // barrier per tile (after each wavefront has seen its own two loads land).  No combination through
 // LDS at the end: every wavefront writes its rows itself: the output if there is one split, else
-// a partial that merge_rows_kernel combines.
+// a partial; the partials are merged by the group's workgroups themselves (up to 16 splits) or by
+// merge_rows_kernel.
 constexpr int kRowStages = kWaves + 1;
-constexpr int kRowWindow = 3;                // tiles between two barriers; divides kRowStages
-static_assert(kRowStages % kRowWindow == 0, "a window must map onto whole stages of the ring");
+constexpr int kRowWindow = 3;                // most tiles between two barriers
 constexpr int kMaxRowTiles = 64;             // tiles per workgroup: one gather entry per lane
+constexpr int kMaxSplitsMergedInKernel = 16; // one bit per split in the upper half of the arrival word's low 32 bits
 
 // What a wavefront of the rows kernel needs to fetch its part of a tile.
 struct RowTileIssue {
@@ -1702,11 +1705,10 @@ struct RowTileIssue {
   int64_t dv_c, dv_d;
   uint64_t gent;                 // lane u: gather entry of (u-th tile, this wavefront's group)
   int split, S, tiles_d, gamma, wave, lane;
-  uint32_t lrow, cx, tok_bytes, drow_bytes, nv_lds;
+  uint32_t lrow, cx, tok_bytes, drow_bytes;
 };
 
-// This wavefront's two loads of the workgroup's i-th tile (slots 4 * wave .. 4 * wave + 3), and the
-// number of real tokens among them, left in LDS for everybody.
+// This wavefront's two loads of the workgroup's i-th tile (slots 4 * wave .. 4 * wave + 3).
 __device__ __forceinline__ void issue_row_tile(const RowTileIssue& c, int i) {
   const int t = c.split + i * c.S;
   const int st = i % kRowStages;
@@ -1740,13 +1742,14 @@ __device__ __forceinline__ void issue_row_tile(const RowTileIssue& c, int i) {
   const uint32_t off = r * row_bytes + ((c.cx ^ (uint32_t)((4 * c.wave) & 15)) << 4);
   __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(kb + off), SVF_LDS_PTR(dst + c.wave * 1024), 16, 0, 2);
   __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(vb + off), SVF_LDS_PTR(dst + kTileBytes + c.wave * 1024), 16, 0, 2);
-  if (c.lane == 0) lds_write4(c.nv_lds + (uint32_t)(st * kWaves + c.wave) * 4u, (uint32_t)nv);
 }
 
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnParams p, int pairs) {
   __shared__ __attribute__((aligned(1024))) unsigned char smem[kRowStages * kStageBytes];
-  __shared__ __attribute__((aligned(16))) int32_t s_nv[kRowStages][kWaves];   // valid rows per four-token group
+  // per (tile of the workgroup, four-token group): bit s set = slot s of the group holds a real token
+  __shared__ __attribute__((aligned(8))) unsigned char s_group_valid[kMaxRowTiles][kWaves];
+  __shared__ int sm_last;
   __shared__ int32_t s_sel[MODE == kSelect ? kMaxSelectBlocks : 1];
   __shared__ int s_exchange_failed;
 
@@ -1811,12 +1814,14 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   if (MODE != kGather) L = clamped_len(p.seq_lens, b + vzero, p.max_seq_len);
   if (MODE == kSelect) issue_first_score_batch(p, rl, pair, split, tid);
   int cnt;
-  uint32_t tag = 0;
+  // the group's epoch word: this call's tag is its low half plus one, its high half the wait budget
+  uint64_t epoch_word = 0;
+  if (MODE != kSelect) epoch_word = p.epochs[xgroup + vzero];
   if (MODE == kSelect) {
+    epoch_word = rl.epoch_word;
     const Retrieved rt = retrieve_blocks(p, rl, smem, s_sel, &s_exchange_failed, L, pair, split, xgroup, tid, lane, wave, []() {});
     L = rt.L;
     cnt = rt.cnt;
-    tag = rt.tag;
     if (split == S - 1 && zs == 0) publish_selection(p, s_sel, cnt, pair, tid);
     if (e_ok) {
       gent = gather_entry_of(p, s_sel, rt, rl, e_u, b, h);
@@ -1849,6 +1854,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   const int tiles = tiles_d + (n_prefix + kTile - 1) / kTile;
   int n_my = 0;
   if (split < tiles) n_my = min((tiles - split + S - 1) / S, kMaxRowTiles);
+  n_my = __builtin_amdgcn_readfirstlane(n_my);             // (the same for the whole workgroup)
 
   const int lrow = lane >> 4;
   const uint32_t cx = (uint32_t)((lane & 15) ^ lrow);
@@ -1857,7 +1863,6 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   const int64_t dv_c = Vc - Kc, dv_d = Vd - Kd;
   const char* const kd_pair = Kd + (((int64_t)b * p.gamma) * p.Hkv + h) * kRowBytes;
   const int64_t orow_pair = (int64_t)b * p.gamma * p.Hq + h * p.G;
-  const uint32_t nv_lds = (uint32_t)(uintptr_t)SVF_LDS_PTR(&s_nv[0][0]);
 
   RowTileIssue ic;
   ic.smem = smem;
@@ -1876,7 +1881,6 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   ic.cx = cx;
   ic.tok_bytes = tok_bytes;
   ic.drow_bytes = drow_bytes;
-  ic.nv_lds = nv_lds;
 
   float m_run = -INFINITY, l_run = 0.f;
   floatx16 oacc[4];
@@ -1889,57 +1893,72 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   if (!p.draft_mask) rmask = qi >= 63 ? ~0ull : ((2ull << qi) - 1ull);
   if (!row_valid) rmask = 0;
 
-  // ---- main loop: nine stages, tiles taken three at a time -----------------------------------------
-  // One barrier per window of kRowWindow tiles rather than per tile: behind a barrier all eight
-  // wavefronts are in the same phase (all reading LDS, then all on the matrix cores, then all in
-  // the softmax); over three tiles they drift apart and one wavefront's MFMA runs under the other's
-  // vector work.  The stages of the window before take the next tiles.
+  // Which slots of each tile hold a real token: wavefront w knows it for group w of every tile
+  // (lane u: the workgroup's u-th tile); the groups' four-bit masks meet in LDS once, and lane u
+  // keeps the 32-bit mask of tile u for the loop below (one v_readlane per tile there).
+  uint32_t valid_of_tile = 0;
+  {
+    const int t_u = split + lane * S;
+    int nv_u = 0;
+    if (lane < n_my) nv_u = t_u < tiles_d ? min(max(p.gamma - (t_u * kTile + 4 * wave), 0), 4) : (int)(gent >> kGatherCountShift);
+    s_group_valid[lane][wave] = (unsigned char)((1u << nv_u) - 1u);
+    __syncthreads();
+    const u32x2 gv = *reinterpret_cast<const u32x2*>(&s_group_valid[lane][0]);
+    // byte n of the pair of words = mask of group n: squeeze the eight low nibbles together
+    const uint32_t a = gv[0] | (gv[0] >> 4), c = gv[1] | (gv[1] >> 4);
+    valid_of_tile = ((a & 0xffu) | ((a >> 8) & 0xff00u)) | (((c & 0xffu) | ((c >> 8) & 0xff00u)) << 16);
+  }
+
+  // ---- main loop: nine stages, tiles taken in windows of one, two, then three ------------------------
+  // One barrier per window rather than per tile: behind a barrier all eight wavefronts are in the
+  // same phase (all reading LDS, then all on the matrix cores, then all in the softmax); over three
+  // tiles they drift apart and one wavefront's MFMA runs under the other's vector work.  The first
+  // windows are short so that the arithmetic starts when the first tile is in, not the third.  Of
+  // the two wavefronts of a SIMD one is given priority: they then take turns by themselves instead
+  // of reaching for the same unit at the same time.  Stages of tiles that everybody has left take
+  // the next tiles.
+  if (wave < kWaves / 2) __builtin_amdgcn_s_setprio(1);
   int issued = 0;
   for (; issued < min(n_my, kRowStages); ++issued) issue_row_tile(ic, issued);
-  for (int i0 = 0; i0 < n_my; i0 += kRowWindow) {
-    const int nw = min(kRowWindow, n_my - i0);
+  for (int i0 = 0, nw = 0; i0 < n_my; i0 += nw) {
+    nw = min(i0 == 0 ? 1 : (i0 == 1 ? 2 : kRowWindow), n_my - i0);
     // this wavefront's loads of the window's tiles have landed (two loads per tile, issued in
     // order); the counts of the groups it fetched are on their way to LDS
     wait_vmcnt_upto16(2 * (issued - (i0 + nw)));
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    // everybody is done with the window before
-    if (i0 >= kRowWindow) {
+    // everybody is done with the tiles in front of this window (at most kRowWindow more than at
+    // the barrier before)
 #pragma unroll
-      for (int k = 0; k < kRowWindow; ++k)
-        if (issued < n_my) {
-          issue_row_tile(ic, issued);
-          ++issued;
-        }
-    }
+    for (int k = 0; k < kRowWindow; ++k)
+      if (issued < n_my && issued < i0 + kRowStages) {
+        issue_row_tile(ic, issued);
+        ++issued;
+      }
     for (int k = 0; k < nw; ++k) {
       const int i = i0 + k;
       const int t = split + i * S;
       const int st = i % kRowStages;
-      u32x4 nvq[2];
-      nvq[0] = lds_read16<0>(nv_lds + (uint32_t)st * (kWaves * 4));
-      nvq[1] = lds_read16<16>(nv_lds + (uint32_t)st * (kWaves * 4));
-      lds_wait2(nvq);
-      uint32_t valid = 0;
-#pragma unroll
-      for (int n = 0; n < 8; ++n) valid |= ((1u << nvq[n >> 2][n & 3]) - 1u) << (4 * n);
-      valid = (uint32_t)__builtin_amdgcn_readfirstlane((int)valid);
+      const uint32_t valid = (uint32_t)__builtin_amdgcn_readlane((int)valid_of_tile, i);
       if (has_rows) {
         const int draft_base = t < tiles_d ? t * kTile : -1;
         uint32_t allowed = valid;
         if (draft_base >= 0) allowed &= (uint32_t)(rmask >> (draft_base & 63));
         const bool all_visible = draft_base < 0 && valid == 0xffffffffu;
-        const uint32_t stage = (uint32_t)(uintptr_t)SVF_LDS_PTR(smem + st * kStageBytes);
+        // (one scalar, so that every fragment address is one addition away from it)
+        uint32_t stage = (uint32_t)(uintptr_t)SVF_LDS_PTR(smem + st * kStageBytes);
+        asm volatile("" : "+s"(stage));
         process_tile(stage, qf, allowed, all_visible, p.scale_log2, l32, g, m_run, l_run, oacc);
       }
     }
   }
+  __builtin_amdgcn_s_setprio(0);
   // the other wavefronts may still be reading the last window's stages
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  if (!has_rows) return;             // no barrier from here on
+  if (S == 1 && !has_rows) return;   // (with one split: no barrier from here on)
 
   // ---- this wavefront's 32 rows: output or partial ------------------------------------------------
   // The normalised rows go through LDS once (bf16, [row][128 channels], 16-byte chunk c of row r
@@ -1948,7 +1967,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   // and no load is in flight.
   l_run = halves_sum(l_run);
   const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
-  {
+  if (has_rows) {
     const int last_st = n_my > 0 ? (n_my - 1) % kRowStages : 0;
     unsigned char* mine = smem + ((last_st + 1 + wave) % kRowStages) * kStageBytes;
 #pragma unroll
@@ -1982,9 +2001,72 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
       p.lse[orow_pair + (int64_t)qi * p.Hq + qj] = (m_run + log2f(l_run)) * 0.6931471805599453f;
     return;
   }
-  if (g == 0) store_coherent2(p.part_ml + 2 * (((int64_t)pair * S + split) * p.Mpad + row), m_run, l_run);
-  // (the splits are merged by merge_rows_kernel, launched behind this one: merging 32 rows x S
-  // splits by the one wavefront that happens to arrive last costs ten times what 512 threads need)
+  // ---- several splits: records, then the merge ------------------------------------------------------
+  // Once its partial rows have been acknowledged the wavefront writes a record per row (maximum,
+  // tag, denominator, tag; tag = this call's).  Up to 16 splits are then merged here, by all the
+  // group's workgroups: workgroup `split` takes the row groups rg with rg mod S == split of its
+  // set, pairs of wavefronts eight rows of a row group each, after a bounded wait for the other
+  // splits' records (the protocol of verify_attn_mfma_kernel: a slice whose wait ran out is marked
+  // in the group's arrival word and merged by the workgroup that arrives last; every wait ends).
+  // More splits than that are merged by merge_rows_kernel behind this kernel.
+  const uint32_t tag = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)epoch_word) + 1u;
+  if (has_rows) {
+    wait_vmcnt<0>();
+    if (g == 0) {
+      const u32x4 rec = {__float_as_uint(m_run), tag, __float_as_uint(l_run), tag};
+      store_coherent16(p.part_rec + (((int64_t)pair * S + split) * p.Mpad + row) * 4, rec);
+    }
+  }
+  if (S > kMaxSplitsMergedInKernel) return;            // (uniform)
+  const int wait_polls = wait_polls_of(__builtin_amdgcn_readfirstlane((int)(uint32_t)(epoch_word >> 32)));
+  uint64_t* const arrivals = p.tickets + (int64_t)xgroup * kTicketWords + (tag & 1u);
+  __syncthreads();                                     // every wavefront's records are on their way
+  uint64_t prev = 0;
+  if (tid == 0) prev = __hip_atomic_fetch_add(arrivals, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const int nrg = min(kWaves, p.Mpad / 32 - zs * kWaves);      // row groups of this set
+  const int mt = (wave & 1) * 64 + lane;                       // thread of the wavefront pair
+  const int r_lo = 8 * (wave >> 1);                            // the pair's rows of a row group
+  const OwnRows nothing_in_lds = {nullptr, nullptr, 0, -1};
+  uint32_t todo = split < nrg ? 1u << split : 0u;
+  int budget = wait_polls;
+  bool gave_up = false;
+  for (int round = 0; round < 2; ++round) {
+    while (todo != 0u || gave_up) {
+      int x = split;
+      if (!gave_up) {
+        x = __builtin_ctz(todo);
+        todo &= todo - 1u;
+        bool ok = true;
+        for (int mrg = x; ok && mrg < nrg; mrg += S)
+          ok = merge_rows<8>(p, r_lo, r_lo + 8, budget, tag, pair, (zs * kWaves + mrg) * 32, orow_pair, mt, nothing_in_lds);
+        gave_up = !ok;
+      }
+      if (gave_up) {
+        gave_up = false;
+        uint64_t seen = 0;
+        if (lane == 0)
+          seen = __hip_atomic_fetch_or(arrivals, 1ull << (16 + x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)seen) & 0xffffu;
+        // everybody has arrived, the last arriver may not have seen the mark: keep waiting (it ends)
+        if (arrived == (uint32_t)S) {
+          todo |= 1u << x;
+          budget = kLastResortPolls;
+        }
+      }
+    }
+    if (round == 0) {
+      __syncthreads();
+      if (tid == 0) {
+        const bool last = (prev & 0xffffull) == (uint64_t)(S - 1);
+        sm_last = last ? (int)((uint32_t)(prev >> 16) & 0xffffu) : 0;
+        if (last) finish_call(p, xgroup, tag);
+      }
+      __syncthreads();
+      // (only in the last arriver, and only after a starved wait somewhere in the group)
+      todo = (uint32_t)sm_last;
+      budget = kLastResortPolls;
+    }
+  }
 }
 
 // Merge of the rows kernel's split partials: one workgroup per (pair, row group), sixteen threads
@@ -2009,7 +2091,7 @@ __global__ __launch_bounds__(kThreads) void merge_rows_kernel(AttnParams p, int 
     const int64_t xg = (int64_t)(rg / kWaves) * pairs + pair;
     finish_call(p, xg, *reinterpret_cast<const uint32_t*>(p.epochs + xg) + 1u);
   }
-  merge_splits<false>(p, g_row, orow, rok, cg);
+  merge_splits(p, g_row, orow, rok, cg);
 }
 
 }  // namespace
@@ -2114,8 +2196,8 @@ hipError_t launch_verify_attn_mfma(const AttnParams& p, hipStream_t st) {
     else if (p.gather) hipLaunchKernelGGL(verify_attn_mfma_rows_kernel<kGather>, grid, dim3(kThreads), 0, st, p, pairs);
     else hipLaunchKernelGGL(verify_attn_mfma_rows_kernel<kResolve>, grid, dim3(kThreads), 0, st, p, pairs);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || p.n_splits == 1) return e;
-    const int advance_tags = p.reps != nullptr && p.n_splits >= 2;
+    if (e != hipSuccess || p.n_splits <= kMaxSplitsMergedInKernel) return e;
+    const int advance_tags = p.reps != nullptr;
     hipLaunchKernelGGL(merge_rows_kernel, dim3((unsigned)pairs, (unsigned)row_groups), dim3(kThreads), 0, st, p, pairs,
                        advance_tags);
     return hipGetLastError();

@@ -360,14 +360,7 @@ def test_repeated_calls_are_bit_stable():
         assert torch.equal(run.out.view(torch.int16), out0.view(torch.int16))
 
 
-@pytest.mark.parametrize("cfg_id,T", [(3, 8192), (5, 65536), (4, 131072), (3, 32768), (2, 8192)])
-def test_same_bits_whatever_the_workgroups_wait_for_each_other(cfg_id, T):
-    """The workgroups of a group wait for each other twice, with a bounded number of polls: for the
-    block keys of the shared scoring (anchor layers), and for the split partials before each merges
-    its slice of the rows.  A budget of zero or one poll sends some or all of them down the other
-    paths (score everything oneself; leave the slice to the workgroup that arrives last): the same
-    bits in every step mode, call after call (the tags move on)."""
-    cfg = W.shrink(W.CONFIGS[cfg_id], T) if T < W.CONFIGS[cfg_id].T else W.CONFIGS[cfg_id]
+def same_bits_whatever_the_wait(cfg):
     x = W.make_layer(cfg)
     run = DeviceRun(cfg, to_gpu(x))
     run.block_reps().score_select().verify_attn().sync()
@@ -399,6 +392,34 @@ def test_same_bits_whatever_the_workgroups_wait_for_each_other(cfg_id, T):
     S.svf_workspace_init(run.ws)
     run.verify_step(S.SVF_STEP_ANCHOR).sync()
     assert torch.equal(run.out.view(torch.int16), out0.view(torch.int16))
+
+
+@pytest.mark.parametrize("cfg_id,T", [(3, 8192), (5, 65536), (4, 131072), (3, 32768), (2, 8192)])
+def test_same_bits_whatever_the_workgroups_wait_for_each_other(cfg_id, T):
+    """The workgroups of a group wait for each other twice, with a bounded number of polls: for the
+    block keys of the shared scoring (anchor layers), and for the split partials before each merges
+    its slice of the rows.  A budget of zero or one poll sends some or all of them down the other
+    paths (score everything oneself; leave the slice to the workgroup that arrives last): the same
+    bits in every step mode, call after call (the tags move on)."""
+    same_bits_whatever_the_wait(W.shrink(W.CONFIGS[cfg_id], T) if T < W.CONFIGS[cfg_id].T else W.CONFIGS[cfg_id])
+
+
+# The kernel for many query rows merges up to 16 splits itself, by the same protocol: nine splits of
+# three row groups; four splits of three row groups (a workgroup without a slice); four splits of
+# eight row groups (two row groups per slice); eight splits of two sets of eight row groups; the
+# 60-node tree over the full-size cache (eight splits of eight row groups).
+ROWS_WAIT = {
+    "nine_splits": EDGE["rows_gamma24_tree"],
+    "more_splits_than_row_groups": EDGE["rows_ring_of_stages"],
+    "two_row_groups_per_slice": small(B=8, Hq=32, Hkv=8, gamma=60, tree_depth=6, T=4096, k_blocks=32, min_len=3000),
+    "two_sets_of_eight": small(B=8, Hq=16, Hkv=2, gamma=64, T=2048, k_blocks=8),
+    "tree60_full_cache": dataclasses.replace(W.CONFIGS[3], name="cfg3_tree60", gamma=60, tree_depth=6, n_layers=1),
+}
+
+
+@pytest.mark.parametrize("name", sorted(ROWS_WAIT))
+def test_many_rows_same_bits_whatever_the_workgroups_wait_for_each_other(name):
+    same_bits_whatever_the_wait(ROWS_WAIT[name])
 
 
 def test_budget_helper_matches_oracle():
