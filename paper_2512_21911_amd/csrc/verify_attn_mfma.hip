@@ -1693,7 +1693,16 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
 // a partial; the partials are merged by the group's workgroups themselves (up to 16 splits) or by
 // merge_rows_kernel.
 constexpr int kRowStages = kWaves + 1;
-constexpr int kRowWindow = 3;                // most tiles between two barriers
+#ifndef SVF_ROW_WINDOW
+#define SVF_ROW_WINDOW 3
+#endif
+constexpr int kRowWindow = SVF_ROW_WINDOW;   // most tiles between two barriers
+#ifndef SVF_ROW_AHEAD
+#define SVF_ROW_AHEAD 3
+#endif
+constexpr int kRowAhead = SVF_ROW_AHEAD;     // tiles requested beyond the window at hand
+// (the tiles of a window are requested at the barrier of the window before, at the latest)
+static_assert(kRowAhead >= kRowWindow && kRowWindow + kRowAhead <= kRowStages, "tiles in flight must cover the next window and fit the ring");
 constexpr int kMaxRowTiles = 64;             // tiles per workgroup: one gather entry per lane
 constexpr int kMaxSplitsMergedInKernel = 16; // one bit per split in the upper half of the arrival word's low 32 bits
 
@@ -1918,12 +1927,15 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   // of reaching for the same unit at the same time.  Stages of tiles that everybody has left take
   // the next tiles.
   if (wave < kWaves / 2) __builtin_amdgcn_s_setprio(1);
+  // Only the first tiles are requested up front and the others as the windows advance (the window
+  // at hand plus kRowAhead tiles are in flight): with every tile of every workgroup requested at
+  // once, a workgroup's first tile is served no sooner than most of the launch's bytes.
   int issued = 0;
-  for (; issued < min(n_my, kRowStages); ++issued) issue_row_tile(ic, issued);
+  for (; issued < min(n_my, kRowAhead); ++issued) issue_row_tile(ic, issued);
   for (int i0 = 0, nw = 0; i0 < n_my; i0 += nw) {
-    nw = min(i0 == 0 ? 1 : (i0 == 1 ? 2 : kRowWindow), n_my - i0);
+    nw = min(min(i0 == 0 ? 1 : (i0 == 1 ? 2 : kRowWindow), kRowWindow), n_my - i0);
     // this wavefront's loads of the window's tiles have landed (two loads per tile, issued in
-    // order); the counts of the groups it fetched are on their way to LDS
+    // order; the window's tiles were all requested at the barrier before, or up front)
     wait_vmcnt_upto16(2 * (issued - (i0 + nw)));
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
@@ -1932,7 +1944,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
     // the barrier before)
 #pragma unroll
     for (int k = 0; k < kRowWindow; ++k)
-      if (issued < n_my && issued < i0 + kRowStages) {
+      if (issued < n_my && issued < i0 + nw + kRowAhead && issued < i0 + kRowStages) {
         issue_row_tile(ic, issued);
         ++issued;
       }
@@ -2119,9 +2131,13 @@ int mfma_splits(const svf_shape_t& s) {
 }
 
 // More than two row groups: one workgroup takes up to eight of them (see the rows kernel).
+#ifndef SVF_ROWS_FROM
+#define SVF_ROWS_FROM 3
+#endif
+constexpr int kRowsModeFrom = SVF_ROWS_FROM;
 bool mfma_rows_mode(const svf_shape_t& s) {
   const int M = s.gamma * (s.Hq / s.Hkv);
-  return (M + 31) / 32 >= 3;
+  return (M + 31) / 32 >= kRowsModeFrom;
 }
 
 // Splits per (sequence, KV head, set of eight row groups) of the rows kernel: cover the compute
@@ -2189,7 +2205,7 @@ hipError_t launch_retrieve_only(const AttnParams& p, hipStream_t st) {
 hipError_t launch_verify_attn_mfma(const AttnParams& p, hipStream_t st) {
   const int row_groups = (p.M + 31) / 32;
   const int pairs = p.B * p.Hkv;
-  if (row_groups >= 3) {
+  if (row_groups >= kRowsModeFrom) {
     const dim3 grid((unsigned)(kXcds * p.n_splits), (unsigned)((pairs + kXcds - 1) / kXcds),
                     (unsigned)((row_groups + kWaves - 1) / kWaves));
     if (p.reps) hipLaunchKernelGGL(verify_attn_mfma_rows_kernel<kSelect>, grid, dim3(kThreads), 0, st, p, pairs);
