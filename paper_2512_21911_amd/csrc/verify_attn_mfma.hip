@@ -1701,6 +1701,11 @@ constexpr int kRowWindow = SVF_ROW_WINDOW;   // most tiles between two barriers
 #define SVF_ROW_AHEAD 3
 #endif
 constexpr int kRowAhead = SVF_ROW_AHEAD;     // tiles requested beyond the window at hand
+#ifndef SVF_ROW_FIRST
+#define SVF_ROW_FIRST 3
+#endif
+constexpr int kRowFirst = SVF_ROW_FIRST;     // tiles requested before the first window
+static_assert(kRowFirst >= 1 && kRowFirst <= kRowStages, "the first window is one tile");
 // (the tiles of a window are requested at the barrier of the window before, at the latest)
 static_assert(kRowAhead >= kRowWindow && kRowWindow + kRowAhead <= kRowStages, "tiles in flight must cover the next window and fit the ring");
 constexpr int kMaxRowTiles = 64;             // tiles per workgroup: one gather entry per lane
@@ -1931,7 +1936,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   // at hand plus kRowAhead tiles are in flight): with every tile of every workgroup requested at
   // once, a workgroup's first tile is served no sooner than most of the launch's bytes.
   int issued = 0;
-  for (; issued < min(n_my, kRowAhead); ++issued) issue_row_tile(ic, issued);
+  for (; issued < min(n_my, kRowFirst); ++issued) issue_row_tile(ic, issued);
   for (int i0 = 0, nw = 0; i0 < n_my; i0 += nw) {
     nw = min(min(i0 == 0 ? 1 : (i0 == 1 ? 2 : kRowWindow), kRowWindow), n_my - i0);
     // this wavefront's loads of the window's tiles have landed (two loads per tile, issued in
@@ -1942,12 +1947,11 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
     asm volatile("" ::: "memory");
     // everybody is done with the tiles in front of this window (at most kRowWindow more than at
     // the barrier before)
-#pragma unroll
-    for (int k = 0; k < kRowWindow; ++k)
-      if (issued < n_my && issued < i0 + nw + kRowAhead && issued < i0 + kRowStages) {
-        issue_row_tile(ic, issued);
-        ++issued;
-      }
+#pragma unroll 1
+    while (issued < n_my && issued < i0 + nw + kRowAhead && issued < i0 + kRowStages) {
+      issue_row_tile(ic, issued);
+      ++issued;
+    }
     for (int k = 0; k < nw; ++k) {
       const int i = i0 + k;
       const int t = split + i * S;
