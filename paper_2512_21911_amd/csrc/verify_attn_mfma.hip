@@ -35,8 +35,8 @@
 // Math.  Both products run on the matrix cores in transposed form so that a query row lives
 // in a fixed lane (lane mod 32) from the first MFMA to the final store:
 //   S^T[token][row] = K[token][:] . Q[row][:]           A = K tile (LDS, 16-byte reads), B = Q (registers)
-//   O^T[dim][row]  += V^T[dim][token] P^T[token][row]   A = V tile (LDS, 8-byte reads + byte
-//                                                       permutes = transpose), B = P (registers)
+//   O^T[dim][row]  += V^T[dim][token] P^T[token][row]   A = V tile (LDS, transposing 8-byte reads),
+//                                                       B = P (registers)
 // Softmax runs in the log2 domain in fp32 with one cross-lane step per tile (lanes l, l+32);
 // the rescale of O is a per-lane scalar, applied only when the maximum moved by more than
 // kRescaleGap.  P is rounded to bf16 (hardware RNE) for the second product; accumulators fp32.
@@ -105,6 +105,17 @@ template <int OFF>
 __device__ __forceinline__ u32x2 lds_read8(uint32_t addr) {
   u32x2 v;
   asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+// Transposing LDS read (ds_read_b64_tr_b16), issued by hand.  Within every group of 16 lanes, lane
+// i receives as element j (of four 16-bit elements) element i % 4 of the 8 bytes that lane
+// 4 * j + i / 4 of the group addresses.  So if lane L addresses channels c0 + 4 * (L % 4) .. + 3 of
+// the row of token t0 + L / 4, lane i ends up with channel c0 + i of tokens t0 .. t0 + 3: four
+// k-slots of a matrix-core A operand whose row is a channel, with no register shuffling.
+template <int OFF>
+__device__ __forceinline__ u32x2 lds_read8_tr(uint32_t addr) {
+  u32x2 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
   return v;
 }
 // Waits for all LDS reads; the registers pass through the statement so that no use of them can
@@ -280,10 +291,13 @@ __device__ __forceinline__ void process_tile(uint32_t stage, const bf16x8 (&qf)[
   // K fragment of k-step ks: row l32, 16-byte chunk 2*ks + g at swizzled position
   const uint32_t kbase = stage + l32 * kRowBytes;
   const uint32_t kx = (uint32_t)((g ^ (l32 & 15)) << 4);
-  // V rows: k-slot e of lane group g is token 8*(e/4) + 4*g + e%4 (+16 for the second half);
-  // this lane reads dims 4*l32 .. 4*l32+3 of it: chunk l32/2 (swizzled), half l32%2
-  const uint32_t vbase = stage + kTileBytes + ((l32 & 1) << 3);
-  const uint32_t vc = (uint32_t)(l32 >> 1);
+  // V^T fragments by transposing reads: A row m (= lane mod 32) of the nt-th product is channel
+  // 32 * nt + m; k-slot e of lane group g is token 8*(e/4) + 4*g + e%4 (+16 for the second k-step).
+  // This lane addresses, for piece h of a k-step, token 8*h + 4*g + (lane%16)/4 and the four
+  // channels 32*nt + 16*((lane/16)%2) + 4*(lane%4): 16-byte chunk 4*nt + vc, half vh.
+  const uint32_t vtok = (uint32_t)(4 * g + ((l32 & 15) >> 2));
+  const uint32_t vc = (uint32_t)(2 * ((l32 >> 4) & 1) + ((l32 & 3) >> 1));
+  const uint32_t vbase = stage + kTileBytes + vtok * kRowBytes + ((uint32_t)(l32 & 1) << 3);
 
   // S^T = K Q^T : token = lane mod 32 (A rows), query row = lane mod 32 (B columns)
   floatx16 sacc;
@@ -300,12 +314,12 @@ __device__ __forceinline__ void process_tile(uint32_t stage, const bf16x8 (&qf)[
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[k4]), qf[4 * half + k4], sacc,
                                                      0, 0, 0);
   }
-  // first half of the V rows: in flight while the softmax runs
+  // the V^T fragments of the first k-step: in flight while the softmax runs.  x[2 * nt + h]
   u32x2 x[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const uint32_t tok = (uint32_t)(8 * (e >> 2) + 4 * g + (e & 3));
-    x[e] = lds_read8<0>(vbase + tok * kRowBytes + ((vc ^ tok) << 4));
+    const uint32_t tok = vtok + 8u * (uint32_t)(e & 1);
+    x[e] = lds_read8_tr<0>(vbase + (uint32_t)(e & 1) * (8u * kRowBytes) + (((4u * (uint32_t)(e >> 1) + vc) ^ tok) << 4));
   }
 
   // online softmax; value v of a lane is token 8*(v/4) + 4*g + v%4 of the tile.
@@ -355,27 +369,21 @@ __device__ __forceinline__ void process_tile(uint32_t stage, const bf16x8 (&qf)[
     pf[ks2] = __builtin_bit_cast(bf16x8, w);
   }
 
-  // O^T += V^T P^T : A row i = lane mod 32 carries dims 4*i + nt; k-slot e of lane group g is
-  // token 16*ks2 + 8*(e/4) + 4*g + e%4.  x[e] holds dims 4*i .. 4*i+3 of that token.
+  // O^T += V^T P^T : A row m = lane mod 32 of product nt is channel 32*nt + m; k-slot e of lane
+  // group g is token 16*ks2 + 8*(e/4) + 4*g + e%4.  x[2*nt + h] holds k-slots 4*h .. 4*h+3.
 #pragma unroll
   for (int ks2 = 0; ks2 < 2; ++ks2) {
     if (ks2 == 1) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const uint32_t tok = (uint32_t)(8 * (e >> 2) + 4 * g + (e & 3));
-        x[e] = lds_read8<16 * kRowBytes>(vbase + tok * kRowBytes + ((vc ^ tok) << 4));
+        const uint32_t tok = vtok + 8u * (uint32_t)(e & 1);
+        x[e] = lds_read8_tr<16 * kRowBytes>(vbase + (uint32_t)(e & 1) * (8u * kRowBytes) + (((4u * (uint32_t)(e >> 1) + vc) ^ tok) << 4));
       }
     }
     lds_wait8(x);
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt) {
-      u32x4 w;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t a = nt < 2 ? x[2 * j][0] : x[2 * j][1];
-        const uint32_t c2 = nt < 2 ? x[2 * j + 1][0] : x[2 * j + 1][1];
-        w[j] = __builtin_amdgcn_perm(c2, a, (nt & 1) ? 0x07060302u : 0x05040100u);
-      }
+      const u32x4 w = {x[2 * nt][0], x[2 * nt][1], x[2 * nt + 1][0], x[2 * nt + 1][1]};
       oacc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), pf[ks2], oacc[nt], 0, 0, 0);
     }
   }
@@ -1431,12 +1439,12 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
 
   // ---- combine the computing wavefronts through LDS ---------------------------------------------
   // Wavefront w parks its fp32 output, as it stands (relative to its own running maximum), in its
-  // own stage as [32 rows][32 float4] straight out of the accumulator registers: float4 k * 8 +
-  // g * 4 + nt of a row holds accumulator nt, values 4k .. 4k + 3, i.e. channels 32k + 16g + 4j + nt
-  // (j = 0 .. 3), at position (that index) ^ row, which keeps the row-per-lane writes and the reads
-  // off each other's banks.  After the one barrier wavefronts 0 .. 3 (256 threads: eight per row,
-  // sixteen consecutive channels each = the four float4 with the same k, g) bring the slices to
-  // the common maximum while they add them.
+  // own stage as [32 rows][32 float4] straight out of the accumulator registers: float4 nt * 8 +
+  // k * 2 + g of a row holds accumulator nt, values 4k .. 4k + 3, i.e. channels 32 nt + 8k + 4g +
+  // 0 .. 3, which is channel block (that index): float4 j = channels 4j .. 4j + 3, at position j ^
+  // row, which keeps the row-per-lane writes and the reads off each other's banks.  After the one
+  // barrier wavefronts 0 .. 3 (256 threads: eight per row, sixteen consecutive channels = four
+  // consecutive float4 each) bring the slices to the common maximum while they add them.
   l_run = halves_sum(l_run);
   if (computes) {
     if (g == 0) {
@@ -1448,7 +1456,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     for (int k = 0; k < 4; ++k)
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt)
-        mine[l32 * 32 + ((k * 8 + g * 4 + nt) ^ l32)] =
+        mine[l32 * 32 + ((nt * 8 + k * 2 + g) ^ l32)] =
             make_float4(oacc[nt][4 * k], oacc[nt][4 * k + 1], oacc[nt][4 * k + 2], oacc[nt][4 * k + 3]);
   }
   if (tid == kMergeWave0 * 64) sm_own_ready = 0;
@@ -1521,10 +1529,10 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt) {
         const float4 t = reinterpret_cast<const float4*>(smem + w * kStageBytes)[r * 32 + ((c16 * 4 + nt) ^ r)];
-        racc[nt] = __builtin_fmaf(t.x, fw[w], racc[nt]);
-        racc[4 + nt] = __builtin_fmaf(t.y, fw[w], racc[4 + nt]);
-        racc[8 + nt] = __builtin_fmaf(t.z, fw[w], racc[8 + nt]);
-        racc[12 + nt] = __builtin_fmaf(t.w, fw[w], racc[12 + nt]);
+        racc[4 * nt] = __builtin_fmaf(t.x, fw[w], racc[4 * nt]);
+        racc[4 * nt + 1] = __builtin_fmaf(t.y, fw[w], racc[4 * nt + 1]);
+        racc[4 * nt + 2] = __builtin_fmaf(t.z, fw[w], racc[4 * nt + 2]);
+        racc[4 * nt + 3] = __builtin_fmaf(t.w, fw[w], racc[4 * nt + 3]);
       }
     const float inv = lw > 0.f ? __builtin_amdgcn_rcpf(lw) : 0.f;
     u32x4 o0, o1;
@@ -1987,11 +1995,14 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
     const int last_st = n_my > 0 ? (n_my - 1) % kRowStages : 0;
     unsigned char* mine = smem + ((last_st + 1 + wave) % kRowStages) * kStageBytes;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int i = 8 * (v >> 2) + 4 * g + (v & 3);            // dims 4*i .. 4*i+3
-      const u32x2 w = {pack_bf16(oacc[0][v] * inv, oacc[1][v] * inv), pack_bf16(oacc[2][v] * inv, oacc[3][v] * inv)};
-      *reinterpret_cast<u32x2*>(mine + l32 * kRowBytes + ((((i >> 1) ^ (l32 & 15)) << 4) | ((i & 1) << 3))) = w;
-    }
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        // accumulator nt, values 4k .. 4k + 3: channels 32 nt + 8k + 4g + 0 .. 3 (half g of chunk 4 nt + k)
+        const u32x2 w = {pack_bf16(oacc[nt][4 * k] * inv, oacc[nt][4 * k + 1] * inv),
+                         pack_bf16(oacc[nt][4 * k + 2] * inv, oacc[nt][4 * k + 3] * inv)};
+        *reinterpret_cast<u32x2*>(mine + l32 * kRowBytes + ((((4 * nt + k) ^ (l32 & 15)) << 4) | (g << 3))) = w;
+      }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
