@@ -929,6 +929,9 @@ def main():
                   "step_us_median": step_stats["median"], "step_us_min": step_stats["min"],
                   "step_us_p90": step_stats["p90"],
                   "near_ties": near_ties,
+                  # bounded waits between workgroups that ran out in all launches on the step's workspace so far
+                  # (warm-up, timed and per-replay runs): the fallbacks give the same bits but cost microseconds
+                  "wait_fallbacks": dict(zip(("exchange", "merge"), S.svf_diag_wait_fallbacks(shape, ws))),
                   "copy_same_bytes_us_per_launch": round(copy_us, 3),
                   "step_us_stream_launches": round(ms_step_eager * 1e3, 2),
                   "anchor_layer_us": round(anchor_us, 3),

@@ -30,6 +30,16 @@ int svf_diag_verify_attn(const svf_shape_t* shape, int kernel, const void* q, co
                          const int32_t* sel_cnt, void* out, float* lse_or_null, void* ws, size_t ws_bytes,
                          void* stream);
 
+/*
+ * How often the bounded waits between the workgroups of a group ran out since the workspace was
+ * last cleared (svf_workspace_init): counts[0] = workgroups that scored all blocks themselves after
+ * waiting in vain for the others' block keys (anchor layers), counts[1] = wavefronts that left their
+ * slice of the rows to the workgroup arriving last after waiting in vain for the others' partial
+ * results.  The results are the same bits either way; a fallback costs time (microseconds per
+ * launch), which is what this is for.  `counts`: two uint64 in device memory, written on `stream`.
+ */
+int svf_diag_wait_fallbacks(const svf_shape_t* shape, const void* ws, size_t ws_bytes, uint64_t* counts, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -63,7 +63,7 @@ _lib = None
 
 EXPORTS = ["svf_version", "svf_strerror", "svf_budget_blocks", "svf_workspace_bytes", "svf_workspace_init",
            "svf_block_reps", "svf_score_select", "svf_verify_attn", "svf_verify_step", "svf_workspace_set_wait_polls",
-           "svf_static_workspace_bytes", "svf_verify_attn_static_ws", "svf_diag_workspace_bytes", "svf_diag_verify_attn",
+           "svf_static_workspace_bytes", "svf_verify_attn_static_ws", "svf_diag_workspace_bytes", "svf_diag_verify_attn", "svf_diag_wait_fallbacks",
            "svf_mask_words", "svf_analytics_workspace_bytes", "svf_select_per_draft", "svf_masks_from_selection",
            "svf_overlap_by_distance", "svf_jaccard_adjacent", "svf_topk_anchors",
            "svf_block_summaries", "svf_retrieve", "svf_ffn_workspace_bytes", "svf_sparse_ffn",
@@ -87,6 +87,8 @@ def lib() -> ctypes.CDLL:
         L.svf_verify_attn_static_ws.argtypes = [shp] + [vp] * 13
         L.svf_diag_workspace_bytes.restype = ctypes.c_size_t
         L.svf_diag_workspace_bytes.argtypes = [shp, ctypes.c_int]
+        L.svf_diag_wait_fallbacks.restype = ctypes.c_int
+        L.svf_diag_wait_fallbacks.argtypes = [shp, vp, ctypes.c_size_t, vp, vp]
         L.svf_diag_verify_attn.restype = ctypes.c_int
         L.svf_diag_verify_attn.argtypes = [shp, ctypes.c_int] + [vp] * 13 + [ctypes.c_size_t, vp]
         L.svf_workspace_set_wait_polls.restype = ctypes.c_int
@@ -238,6 +240,14 @@ def new_diag_workspace(shape, kernel, device="cuda") -> torch.Tensor:
     if n == 0:
         raise SvfError(-2, "svf_diag_workspace_bytes")
     return torch.zeros(n, dtype=torch.uint8, device=device)
+
+
+def svf_diag_wait_fallbacks(shape, ws):
+    """(exchange fallbacks, merge fallbacks) counted in `ws` since it was last cleared; synchronises."""
+    counts = torch.zeros(2, dtype=torch.int64, device=ws.device)
+    _check(lib().svf_diag_wait_fallbacks(ctypes.byref(shape), _ptr(ws), ws.numel(), _ptr(counts), _stream()),
+           "svf_diag_wait_fallbacks")
+    return tuple(int(v) for v in counts.cpu())
 
 
 def svf_diag_verify_attn(shape, kernel, q, K, V, block_table, seq_lens, k_draft, v_draft, draft_mask, sel_idx, sel_cnt,

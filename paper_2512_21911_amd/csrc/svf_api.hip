@@ -511,7 +511,38 @@ int svf_verify_attn_static_ws(const svf_shape_t* shape, const void* q, const voi
                           sel_cnt, out, lse_or_null, ws, kStaticScratchBytes, stream, false);
 }
 
-// ---- diagnostics (include/svf_diag.h): the attention with the kernel chosen by the caller ---------
+// ---- diagnostics (include/svf_diag.h) ---------------------------------------------------------------
+namespace {
+// sums the statistics words of all groups into out[0] (exchange) and out[1] (merge); one workgroup
+__global__ void sum_fallbacks_kernel(const uint64_t* tickets, size_t groups, uint64_t* out) {
+  __shared__ unsigned long long acc[2];
+  if (threadIdx.x < 2) acc[threadIdx.x] = 0ull;
+  __syncthreads();
+  unsigned long long a = 0ull, b = 0ull;
+  for (size_t i = threadIdx.x; i < groups; i += blockDim.x) {
+    a += tickets[i * svf::kTicketWords + svf::kTicketExchangeFallbacks];
+    b += tickets[i * svf::kTicketWords + svf::kTicketMergeFallbacks];
+  }
+  atomicAdd(&acc[0], a);
+  atomicAdd(&acc[1], b);
+  __syncthreads();
+  if (threadIdx.x < 2) out[threadIdx.x] = acc[threadIdx.x];
+}
+}  // namespace
+
+int svf_diag_wait_fallbacks(const svf_shape_t* shape, const void* ws, size_t ws_bytes, uint64_t* counts, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  rc = check_ws(shape, ws, ws_bytes);
+  if (rc) return rc;
+  if (!counts) return SVF_ERR_NULL;
+  const AttnPlan pl = plan_attn(*shape);
+  const uint64_t* tickets = reinterpret_cast<const uint64_t*>(static_cast<const char*>(ws) + pl.off_tickets);
+  hipLaunchKernelGGL(sum_fallbacks_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), tickets, pl.groups, counts);
+  return hip_code(hipGetLastError());
+}
+
+// the attention with the kernel chosen by the caller
 size_t svf_diag_workspace_bytes(const svf_shape_t* shape, int kernel) {
   if (check_shape(shape) != SVF_OK || (kernel != 0 && kernel != 1)) return 0;
   const size_t own = plan_attn(*shape, kernel == 0).bytes + scores_bytes(*shape);

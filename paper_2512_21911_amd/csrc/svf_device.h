@@ -54,6 +54,9 @@ constexpr int kGatherCountShift = 56;
 constexpr uint64_t kGatherOffsetMask = (1ull << kGatherCountShift) - 1ull;
 constexpr int kMaxGatherBlocks = 1024;   // block budgets above this do without a gather list
 constexpr int kTicketWords = 8;          // 64-bit words per (pair, row group) in AttnParams::tickets
+// (statistics only, svf_diag_wait_fallbacks: they count up until the workspace is cleared)
+constexpr int kTicketExchangeFallbacks = 3;   // workgroups that scored all blocks themselves after a starved key exchange
+constexpr int kTicketMergeFallbacks = 6;      // wavefronts that gave a slice of rows up to the last arriver
 constexpr int kDefaultWaitPolls = 64;    // polls a workgroup spends waiting for the others of its group
 constexpr int kMaxWaitPolls = 4096;
 
@@ -105,7 +108,8 @@ struct AttnParams {
   // per (pair, row group) eight 64-bit words: [0], [1] arrival word of calls with an even / odd
   // tag (bits 15:0 arrivals, bits 31:16 slices given up), [2] arrival counter of the kernels that
   // reset it themselves, [4], [5] (even / odd tag) where the group's workgroups run: eight 8-bit
-  // counters, one per XCD, to which every workgroup adds one when it starts; the others unused
+  // counters, one per XCD, to which every workgroup adds one when it starts; [3], [6] statistics
+  // (kTicketExchangeFallbacks, kTicketMergeFallbacks); [7] unused
   uint64_t* tickets;
   const uint64_t* gather;      // [B][Hkv][gather_groups] gather list matching sel_idx, or NULL
   int32_t gather_groups;

@@ -976,6 +976,10 @@ __device__ __forceinline__ Retrieved retrieve_blocks(const AttnParams& p, Retrie
     if (mine1 && !need1) s_keys[j1] = got1;
     __syncthreads();
     score_alone = *s_exchange_failed != 0;
+    // (for the statistics of svf_diag_wait_fallbacks: no answer needed)
+    if (score_alone && tid == 0)
+      __hip_atomic_fetch_add(p.tickets + (int64_t)xgroup * kTicketWords + kTicketExchangeFallbacks, 1ull, __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
   }
   if (!R.share_scores) meanwhile();
   if (score_alone) {                                   // (the same for the whole workgroup)
@@ -1665,8 +1669,10 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       if (gave_up) {
         gave_up = false;
         uint64_t seen = 0;
-        if (lane == 0)
+        if (lane == 0) {
           seen = __hip_atomic_fetch_or(arrivals, 1ull << (16 + x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_fetch_add(arrivals - (tag & 1u) + kTicketMergeFallbacks, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         const uint32_t arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)seen) & 0xffffu;
         // everybody has arrived, the last arriver may not have seen the mark: keep waiting (it ends)
         if (arrived == (uint32_t)S) {
@@ -2071,8 +2077,10 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
       if (gave_up) {
         gave_up = false;
         uint64_t seen = 0;
-        if (lane == 0)
+        if (lane == 0) {
           seen = __hip_atomic_fetch_or(arrivals, 1ull << (16 + x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_fetch_add(arrivals - (tag & 1u) + kTicketMergeFallbacks, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         const uint32_t arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)seen) & 0xffffu;
         // everybody has arrived, the last arriver may not have seen the mark: keep waiting (it ends)
         if (arrived == (uint32_t)S) {

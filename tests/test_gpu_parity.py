@@ -367,6 +367,7 @@ def same_bits_whatever_the_wait(cfg):
     out0, lse0, idx0, cnt0 = run.out.clone(), run.lse.clone(), run.sel_idx.clone(), run.sel_cnt.clone()
     for polls in (0, 1, 2, 64, -1):
         S.svf_workspace_set_wait_polls(run.shape, run.ws, polls)
+        before = S.svf_diag_wait_fallbacks(run.shape, run.ws)
         for rep in range(3):                       # the tag moves on from call to call
             for mode in (S.SVF_STEP_ANCHOR, S.SVF_STEP_REUSE_GATHER, S.SVF_STEP_REUSE):
                 run.out.fill_(float("nan"))
@@ -378,6 +379,14 @@ def same_bits_whatever_the_wait(cfg):
                 assert torch.equal(run.sel_idx, idx0) and torch.equal(run.sel_cnt, cnt0), f"polls={polls} mode={mode}"
                 assert torch.equal(run.out.view(torch.int16), out0.view(torch.int16)), f"polls={polls} mode={mode}"
                 assert torch.equal(run.lse.view(torch.int32), lse0.view(torch.int32)), f"polls={polls} mode={mode}"
+        # the library counts the waits that ran out; without patience every wait between workgroups does
+        after = S.svf_diag_wait_fallbacks(run.shape, run.ws)
+        assert after[0] >= before[0] and after[1] >= before[1]
+        if polls == 0:                             # (every shape tested this way has several splits)
+            assert after[1] > before[1], "no merge fallback counted although nobody waits"
+            print(f"\n[{cfg.name}] polls=0: exchange fallbacks +{after[0] - before[0]}, merge fallbacks +{after[1] - before[1]}")
+        if polls in (64, -1):
+            print(f"\n[{cfg.name}] polls={polls}: exchange fallbacks +{after[0] - before[0]}, merge fallbacks +{after[1] - before[1]}")
     # many calls in a row, no host synchronisation in between: tags keep moving, nothing stale is taken
     for polls in (-1, 1):
         S.svf_workspace_set_wait_polls(run.shape, run.ws, polls)
@@ -388,8 +397,10 @@ def same_bits_whatever_the_wait(cfg):
         torch.cuda.synchronize()
         assert torch.equal(run.sel_idx, idx0)
         assert all(torch.equal(o.view(torch.int16), out0.view(torch.int16)) for o in outs), f"polls={polls}"
-    # clearing the workspace restores the default budget and a fresh call counter
+    # clearing the workspace restores the default budget, a fresh call counter and empty statistics
     S.svf_workspace_init(run.ws)
+    torch.cuda.synchronize()
+    assert S.svf_diag_wait_fallbacks(run.shape, run.ws) == (0, 0)
     run.verify_step(S.SVF_STEP_ANCHOR).sync()
     assert torch.equal(run.out.view(torch.int16), out0.view(torch.int16))
 
