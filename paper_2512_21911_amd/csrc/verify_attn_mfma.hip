@@ -235,6 +235,10 @@ __device__ __forceinline__ uint32_t swap_lanes_xor4(uint32_t x) {
   t = __builtin_amdgcn_update_dpp(t, (int)x, 0x124, 0xf, 0xA, false);             // row_ror:4
   return (uint32_t)t;
 }
+// Where float4 j (0 .. 31) of a parked row sits, before the exclusive-or with the row: the two low
+// bits of j go to the top, so that the eight threads that read j = 4c + n (c = 0 .. 7, same n) of a
+// row at once hit eight different 16-byte bank groups.
+__device__ __forceinline__ int parked_position(int j) { return (j >> 2) | ((j & 3) << 3); }
 // Lane N of every row of sixteen lanes, to all lanes of that row.
 template <int N>
 __device__ __forceinline__ uint32_t row_lane(uint32_t x) {
@@ -1445,8 +1449,9 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   // Wavefront w parks its fp32 output, as it stands (relative to its own running maximum), in its
   // own stage as [32 rows][32 float4] straight out of the accumulator registers: float4 nt * 8 +
   // k * 2 + g of a row holds accumulator nt, values 4k .. 4k + 3, i.e. channels 32 nt + 8k + 4g +
-  // 0 .. 3, which is channel block (that index): float4 j = channels 4j .. 4j + 3, at position j ^
-  // row, which keeps the row-per-lane writes and the reads off each other's banks.  After the one
+  // 0 .. 3, which is channel block (that index): float4 j = channels 4j .. 4j + 3, at position
+  // parked_position(j) ^ row, which keeps the writes (32 rows, one j per instruction) and the reads
+  // (eight threads of a row, j = 4c .. 4c + 3 each) off each other's banks.  After the one
   // barrier wavefronts 0 .. 3 (256 threads: eight per row, sixteen consecutive channels = four
   // consecutive float4 each) bring the slices to the common maximum while they add them.
   l_run = halves_sum(l_run);
@@ -1460,7 +1465,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     for (int k = 0; k < 4; ++k)
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt)
-        mine[l32 * 32 + ((nt * 8 + k * 2 + g) ^ l32)] =
+        mine[l32 * 32 + (parked_position(nt * 8 + k * 2 + g) ^ l32)] =
             make_float4(oacc[nt][4 * k], oacc[nt][4 * k + 1], oacc[nt][4 * k + 2], oacc[nt][4 * k + 3]);
   }
   if (tid == kMergeWave0 * 64) sm_own_ready = 0;
@@ -1532,7 +1537,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     for (int w = 0; w < kSlices; ++w)
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt) {
-        const float4 t = reinterpret_cast<const float4*>(smem + w * kStageBytes)[r * 32 + ((c16 * 4 + nt) ^ r)];
+        const float4 t = reinterpret_cast<const float4*>(smem + w * kStageBytes)[r * 32 + (parked_position(c16 * 4 + nt) ^ r)];
         racc[4 * nt] = __builtin_fmaf(t.x, fw[w], racc[4 * nt]);
         racc[4 * nt + 1] = __builtin_fmaf(t.y, fw[w], racc[4 * nt + 1]);
         racc[4 * nt + 2] = __builtin_fmaf(t.z, fw[w], racc[4 * nt + 2]);
