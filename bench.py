@@ -894,7 +894,7 @@ def main():
     if cfg.dtype != "bf16" or cfg.d != 128:
         kernel_name = "verify_attn_valu_kernel"
     elif cfg.gamma * (cfg.Hq // cfg.Hkv) > 64:     # more than two groups of 32 query rows per KV head
-        kernel_name = "verify_attn_mfma_rows_kernel + merge_rows_kernel (reuse layer)"
+        kernel_name = "verify_attn_mfma_rows_kernel (reuse layer, split merge inside)"
     else:
         kernel_name = "verify_attn_mfma_kernel (reuse layer)"
     line = {

@@ -49,7 +49,7 @@ def poison_outputs(runs, cfg):
 @pytest.mark.parametrize("T,n_layers,tree", [(4096, 4, 0), (32768, 2, 0), (4096, 4, 24)])
 def test_step_graph_replays_match_eager_calls(T, n_layers, tree):
     cfg = W.shrink(W.CONFIGS[3], T) if T < W.CONFIGS[3].T else W.CONFIGS[3]
-    if tree:        # a draft tree: the many-rows kernel, whose splits are merged by a second launch
+    if tree:        # a draft tree: the many-rows kernel
         cfg = dataclasses.replace(cfg, name=cfg.name + "_tree", gamma=tree, tree_depth=4)
     runs = build_layers(cfg, n_layers)
     step(cfg, runs)
