@@ -98,6 +98,9 @@ def test_null_alignment_and_workspace_checks():
     assert L.svf_workspace_set_wait_polls(ctypes.byref(sh), ok, need, 4097, None) == -2
     assert L.svf_workspace_set_wait_polls(ctypes.byref(sh), null, need, 8, None) == -6     # no workspace
     assert L.svf_workspace_set_wait_polls(ctypes.byref(sh), ok, need - 256, 8, None) == -6
+    assert L.svf_diag_wait_fallbacks(ctypes.byref(sh), null, need, ok, None) == -6          # no workspace
+    assert L.svf_diag_wait_fallbacks(ctypes.byref(sh), ok, need - 256, ok, None) == -6
+    assert L.svf_diag_wait_fallbacks(ctypes.byref(sh), ok, need, null, None) == -1           # nowhere to put the counts
     assert L.svf_score_select(ctypes.byref(sh), ok, ok, ok, ok, ok, null, ok, need - 256, None) == -6
     assert L.svf_workspace_init(null, 256, None) == -1
     assert L.svf_workspace_init(ctypes.c_void_p(0x10010), 256, None) == -6
