@@ -1,5 +1,7 @@
 """The entry point that allocates nothing (workspace in a static device array) against
 svf_verify_attn: the same bits, on two calls in a row, the second with a smaller input."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -41,6 +43,9 @@ def test_static_workspace_entry_point_matches_on_two_calls_in_a_row():
     run_both(small)
     run_both(big)                                          # and back: the array is cleared per call
     run_both(W.CONFIGS[1])                                 # fp32: the vector-ALU kernels and their merge launch
+    # a 24-node draft tree: the many-rows kernel, whose splits meet through the same words of the array
+    run_both(dataclasses.replace(W.shrink(W.CONFIGS[3], 8192), name="cfg3_8k_tree24", gamma=24, tree_depth=4))
+    run_both(small)
 
 
 def test_static_workspace_entry_point_refuses_what_does_not_fit():
