@@ -1712,18 +1712,9 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
 // a partial; the partials are merged by the group's workgroups themselves (up to 16 splits) or by
 // merge_rows_kernel.
 constexpr int kRowStages = kWaves + 1;
-#ifndef SVF_ROW_WINDOW
-#define SVF_ROW_WINDOW 3
-#endif
-constexpr int kRowWindow = SVF_ROW_WINDOW;   // most tiles between two barriers
-#ifndef SVF_ROW_AHEAD
-#define SVF_ROW_AHEAD 3
-#endif
-constexpr int kRowAhead = SVF_ROW_AHEAD;     // tiles requested beyond the window at hand
-#ifndef SVF_ROW_FIRST
-#define SVF_ROW_FIRST 3
-#endif
-constexpr int kRowFirst = SVF_ROW_FIRST;     // tiles requested before the first window
+constexpr int kRowWindow = 3;                // most tiles between two barriers
+constexpr int kRowAhead = 3;                 // tiles requested beyond the window at hand
+constexpr int kRowFirst = 3;                 // tiles requested before the first window
 static_assert(kRowFirst >= 1 && kRowFirst <= kRowStages, "the first window is one tile");
 // (the tiles of a window are requested at the barrier of the window before, at the latest)
 static_assert(kRowAhead >= kRowWindow && kRowWindow + kRowAhead <= kRowStages, "tiles in flight must cover the next window and fit the ring");
@@ -2159,10 +2150,7 @@ int mfma_splits(const svf_shape_t& s) {
 }
 
 // More than two row groups: one workgroup takes up to eight of them (see the rows kernel).
-#ifndef SVF_ROWS_FROM
-#define SVF_ROWS_FROM 3
-#endif
-constexpr int kRowsModeFrom = SVF_ROWS_FROM;
+constexpr int kRowsModeFrom = 3;
 bool mfma_rows_mode(const svf_shape_t& s) {
   const int M = s.gamma * (s.Hq / s.Hkv);
   return (M + 31) / 32 >= kRowsModeFrom;
