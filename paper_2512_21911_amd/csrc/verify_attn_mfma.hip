@@ -1818,6 +1818,19 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   RetrievalLoads rl;
   if (MODE == kSelect)
     rl = issue_retrieval_loads(p, b, h, pair, split, xgroup, (split + zs * S) % kScoreBatch, tid, vzero);
+  // gather entries: lane u holds (the workgroup's u-th tile, group = this wavefront).  With a gather
+  // list they and the pair's block count are all the first tile requests wait for: they are loaded
+  // ahead of the query fragments (loads come back in the order issued), and the first tiles are
+  // requested while the fragments are still on their way.
+  const int tc_u = split + lane * S - tiles_d;                 // cache tile index of this lane's tile
+  const int e_u = tc_u * 8 + wave;
+  const bool e_ok = tc_u >= 0 && e_u < p.gather_groups;
+  uint64_t gent = 0;
+  int cnt_raw = 0;
+  if (MODE == kGather) {
+    if (e_ok) gent = p.gather[(int64_t)pair * p.gather_groups + e_u];
+    cnt_raw = p.sel_cnt[pair + vzero];
+  }
   bf16x8 qf[8];
   {
     const __hip_bfloat16* qrow = static_cast<const __hip_bfloat16*>(p.q) +
@@ -1827,13 +1840,6 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   }
   uint64_t rmask = 0;
   if (p.draft_mask) rmask = p.draft_mask[p.mask_per_batch ? (int64_t)b * p.gamma + qi : qi];
-
-  // gather entries: lane u holds (the workgroup's u-th tile, group = this wavefront)
-  const int tc_u = split + lane * S - tiles_d;                 // cache tile index of this lane's tile
-  const int e_u = tc_u * 8 + wave;
-  const bool e_ok = tc_u >= 0 && e_u < p.gather_groups;
-  uint64_t gent = 0;
-  if (MODE == kGather && e_ok) gent = p.gather[(int64_t)pair * p.gather_groups + e_u];
   int L = 0;
   if (MODE != kGather) L = clamped_len(p.seq_lens, b + vzero, p.max_seq_len);
   if (MODE == kSelect) issue_first_score_batch(p, rl, pair, split, tid);
@@ -1853,7 +1859,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
     }
     __syncthreads();                 // the last reads of the staged page table are done
   } else {
-    cnt = __builtin_amdgcn_readfirstlane(min(max(p.sel_cnt[pair + vzero], 0), p.k_blocks));
+    if (MODE != kGather) cnt_raw = p.sel_cnt[pair + vzero];
+    cnt = __builtin_amdgcn_readfirstlane(min(max(cnt_raw, 0), p.k_blocks));
     if (MODE == kResolve && tc_u >= 0 && 4 * e_u < cnt * p.block_size) {
       // sel_idx -> page table -> address, one tile per lane
       const int slot0 = 4 * e_u;
@@ -1913,7 +1920,12 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
 #pragma unroll
     for (int v = 0; v < 16; ++v) oacc[nt][v] = 0.f;
 
-  wait_vmcnt<0>();
+  // (with a gather list nothing is waited for here: what the first requests need is in, the rest is
+  // waited for where it is used, behind those requests)
+  if (MODE != kGather) wait_vmcnt<0>();
+  int issued = 0;
+  if (MODE == kGather)
+    for (; issued < min(n_my, kRowFirst); ++issued) issue_row_tile(ic, issued);
   if (!p.draft_mask) rmask = qi >= 63 ? ~0ull : ((2ull << qi) - 1ull);
   if (!row_valid) rmask = 0;
 
@@ -1926,7 +1938,10 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
     int nv_u = 0;
     if (lane < n_my) nv_u = t_u < tiles_d ? min(max(p.gamma - (t_u * kTile + 4 * wave), 0), 4) : (int)(gent >> kGatherCountShift);
     s_group_valid[lane][wave] = (unsigned char)((1u << nv_u) - 1u);
-    __syncthreads();
+    // (a barrier of LDS traffic only: tile requests and query fragments may be in flight)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     const u32x2 gv = *reinterpret_cast<const u32x2*>(&s_group_valid[lane][0]);
     // byte n of the pair of words = mask of group n: squeeze the eight low nibbles together
     const uint32_t a = gv[0] | (gv[0] >> 4), c = gv[1] | (gv[1] >> 4);
@@ -1945,7 +1960,6 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   // Only the first tiles are requested up front and the others as the windows advance (the window
   // at hand plus kRowAhead tiles are in flight): with every tile of every workgroup requested at
   // once, a workgroup's first tile is served no sooner than most of the launch's bytes.
-  int issued = 0;
   for (; issued < min(n_my, kRowFirst); ++issued) issue_row_tile(ic, issued);
   for (int i0 = 0, nw = 0; i0 < n_my; i0 += nw) {
     nw = min(min(i0 == 0 ? 1 : (i0 == 1 ? 2 : kRowWindow), kRowWindow), n_my - i0);
