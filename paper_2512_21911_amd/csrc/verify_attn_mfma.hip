@@ -1473,17 +1473,20 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     sm_one_xcd = counts_xcds && where == (uint64_t)p.n_splits << (8 * xcc_id()) ? 1 : 0;
   __syncthreads();
 
-  if (MODE == kSelect) {
-    // The selection and the gather list for the layers that reuse them go out here: a barrier
-    // waits for the acknowledgement of every store issued before it, and the next wait of that
-    // kind is the one the partial's own stores need anyway.  The workgroup with the least other
-    // work publishes the selection (s_sel is not a stage).
+  // The selection and the gather list for the layers that reuse them go out behind the stream
+  // (a store in front of it would be one more thing the stream's first wait has to see
+  // acknowledged): here by the wavefronts that do not combine, and by wavefronts 0 .. 3 only once
+  // their partial and its records are out, so that the wait for the partial's acknowledgement
+  // is not a wait for these stores as well.  The workgroup with the least other work publishes the
+  // selection (s_sel is not a stage).
+  auto publish_retrieval = [&]() {
     if (split == p.n_splits - 1 && rg == 0) publish_selection(p, s_sel, cnt, pair, tid);
     const int tc = gw + (lane >> 3) * NW - tiles_d;
     const int e = tc * 8 + (lane & 7);
     if (rg == 0 && lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups)
       p.gather_out[(int64_t)pair * p.gather_groups + e] = gent;
-  }
+  };
+  if (MODE == kSelect && wave >= 4) publish_retrieval();
 
   // ---- what happens to the workgroup's result --------------------------------------------------------
   // One split: wavefronts 0 .. 3 write out / lse.  Otherwise the splits of a group are merged by
@@ -1607,6 +1610,7 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       }
       if (tid == 0) prev = __hip_atomic_fetch_add(arrivals, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    if (MODE == kSelect) publish_retrieval();
   }
   if (single) return;
 
