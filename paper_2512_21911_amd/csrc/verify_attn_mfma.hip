@@ -1856,11 +1856,9 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
     const Retrieved rt = retrieve_blocks(p, rl, smem, s_sel, &s_exchange_failed, L, pair, split, xgroup, tid, lane, wave, []() {});
     L = rt.L;
     cnt = rt.cnt;
-    if (split == S - 1 && zs == 0) publish_selection(p, s_sel, cnt, pair, tid);
-    if (e_ok) {
-      gent = gather_entry_of(p, s_sel, rt, rl, e_u, b, h);
-      if (zs == 0) p.gather_out[(int64_t)pair * p.gather_groups + e_u] = gent;
-    }
+    // (the selection and the gather entries are written out behind the tile loop: a store in front
+    // of it would be one more thing the loop's first wait has to see acknowledged)
+    if (e_ok) gent = gather_entry_of(p, s_sel, rt, rl, e_u, b, h);
     __syncthreads();                 // the last reads of the staged page table are done
   } else {
     if (MODE != kGather) cnt_raw = p.sel_cnt[pair + vzero];
@@ -2002,6 +2000,10 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
+  if (MODE == kSelect) {             // for the layers that reuse this retrieval (s_sel is not a stage)
+    if (split == S - 1 && zs == 0) publish_selection(p, s_sel, cnt, pair, tid);
+    if (e_ok && zs == 0) p.gather_out[(int64_t)pair * p.gather_groups + e_u] = gent;
+  }
   if (S == 1 && !has_rows) return;   // (with one split: no barrier from here on)
 
   // ---- this wavefront's 32 rows: output or partial ------------------------------------------------
