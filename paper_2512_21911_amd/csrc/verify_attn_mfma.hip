@@ -712,12 +712,14 @@ constexpr int kMaxSelectBlocks = 1024;   // blocks per sequence the in-kernel re
 // The final placement needs one more barrier: position of a kept block = blocks above the
 // threshold before it + min(equal blocks before it, equal blocks wanted).  sel[0 .. cnt) ends up
 // ascending.  Requires 1 <= cnt <= nb; all threads of the workgroup must call.
+// first_counted: the caller has already counted every key's top digit into hist[0] and passed a
+// barrier since (the keys were counted as they came in): the first pass starts at its scan.
 struct SelectScratch {
   uint32_t hist[4][256];
   uint32_t seg[2 * kWaves][2];     // per (key slot, wavefront): blocks above / equal to the threshold
 };
 __device__ __forceinline__ void workgroup_select(const uint32_t* keys, SelectScratch* sc, int nb, int cnt,
-                                                 int32_t* sel, int tid, int lane, int wave) {
+                                                 int32_t* sel, int tid, int lane, int wave, bool first_counted) {
   const bool has0 = tid < nb, has1 = tid + kThreads < nb;
   const uint32_t k0 = has0 ? keys[tid] : 0u, k1 = has1 ? keys[tid + kThreads] : 0u;
   uint32_t prefix = 0, need = (uint32_t)cnt;
@@ -725,9 +727,11 @@ __device__ __forceinline__ void workgroup_select(const uint32_t* keys, SelectScr
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
     const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
-    if (has0 && (k0 & hi_mask) == prefix) atomicAdd(&sc->hist[pass][(k0 >> shift) & 0xff], 1u);
-    if (has1 && (k1 & hi_mask) == prefix) atomicAdd(&sc->hist[pass][(k1 >> shift) & 0xff], 1u);
-    __syncthreads();
+    if (!(pass == 0 && first_counted)) {             // (uniform)
+      if (has0 && (k0 & hi_mask) == prefix) atomicAdd(&sc->hist[pass][(k0 >> shift) & 0xff], 1u);
+      if (has1 && (k1 & hi_mask) == prefix) atomicAdd(&sc->hist[pass][(k1 >> shift) & 0xff], 1u);
+      __syncthreads();
+    }
     // lane l owns bins 255 - 4l (in .w) down to 252 - 4l (in .x): higher bins in lower lanes
     const uint4 hq = *reinterpret_cast<const uint4*>(&sc->hist[pass][252 - 4 * lane]);
     const uint32_t own = hq.x + hq.y + hq.z + hq.w;
@@ -936,6 +940,8 @@ __device__ __forceinline__ Retrieved retrieve_blocks(const AttnParams& p, Retrie
   for (int i = 0; i < kScoreChunks; ++i) qv[i] = *reinterpret_cast<const float4*>(s_q0 + sub * 4 + i * 4 * kScoreLanes);
   // scores the rows in R.r (passes first, first + stride, ...): keys go to LDS and, if published,
   // tagged to the group's exchange array through a write-through store
+  // (publish: also counted into the first histogram of the selection, like the keys that come in
+  // from the other workgroups below, so that the barrier behind the exchange is the first pass's)
   auto score_batch = [&](int first, int stride, bool rotate, bool publish) {
 #pragma unroll
     for (int u = 0; u < kScoreBatch; ++u) {
@@ -946,8 +952,10 @@ __device__ __forceinline__ Retrieved retrieve_blocks(const AttnParams& p, Retrie
         if (sub == 0 && j < nb) {
           const uint32_t key = (j < p.n_sink || j >= nb - p.n_local) ? 0xffffffffu : score_key(v + 0.0f);
           s_keys[j] = key;
-          if (publish)
+          if (publish) {
             __hip_atomic_store(xk + j, (uint64_t)key | ((uint64_t)tag << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            atomicAdd(&s_sc->hist[0][key >> 24], 1u);
+          }
         }
       }
     }
@@ -967,11 +975,19 @@ __device__ __forceinline__ Retrieved retrieve_blocks(const AttnParams& p, Retrie
     for (int it = 0; it < poll_budget; ++it) {
       if (need0) {
         const uint64_t w = __hip_atomic_load(xk + j0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((uint32_t)(w >> 32) == tag) { got0 = (uint32_t)w; need0 = false; }
+        if ((uint32_t)(w >> 32) == tag) {
+          got0 = (uint32_t)w;
+          need0 = false;
+          atomicAdd(&s_sc->hist[0][got0 >> 24], 1u);
+        }
       }
       if (need1) {
         const uint64_t w = __hip_atomic_load(xk + j1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((uint32_t)(w >> 32) == tag) { got1 = (uint32_t)w; need1 = false; }
+        if ((uint32_t)(w >> 32) == tag) {
+          got1 = (uint32_t)w;
+          need1 = false;
+          atomicAdd(&s_sc->hist[0][got1 >> 24], 1u);
+        }
       }
       if (!__any(need0 || need1)) break;
     }
@@ -987,6 +1003,10 @@ __device__ __forceinline__ Retrieved retrieve_blocks(const AttnParams& p, Retrie
   }
   if (!R.share_scores) meanwhile();
   if (score_alone) {                                   // (the same for the whole workgroup)
+    // (a starved exchange has left some keys counted: the selection counts for itself; everybody is
+    // past the barrier behind the exchange, and the barrier below comes before the selection's adds)
+    if (R.share_scores)
+      for (int i = tid; i < 256; i += kThreads) s_sc->hist[0][i] = 0;
     const bool loaded = !R.share_scores;               // the up-front batch was this one
     for (int f = 0; f * 64 < nb; f += kScoreBatch) {
       if (!(loaded && f == 0)) load_score_batch(p, rp, jrow, f, 1, true, R.rot, R.r);
@@ -994,7 +1014,7 @@ __device__ __forceinline__ Retrieved retrieve_blocks(const AttnParams& p, Retrie
     }
     __syncthreads();                                   // (after an exchange the barrier above has done this)
   }
-  if (out.cnt > 0) workgroup_select(s_keys, s_sc, nb, out.cnt, s_sel, tid, lane, wave);
+  if (out.cnt > 0) workgroup_select(s_keys, s_sc, nb, out.cnt, s_sel, tid, lane, wave, !score_alone);
   __syncthreads();
   return out;
 }
