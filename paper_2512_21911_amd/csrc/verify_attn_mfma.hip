@@ -767,15 +767,31 @@ __device__ __forceinline__ void workgroup_select(const uint32_t* keys, SelectScr
     sc->seg[kWaves + wave][1] = (uint32_t)__popcll(eq1);
   }
   __syncthreads();
-  uint32_t gt_before = 0, eq_before = 0;             // over the segments in front of (first key, this wavefront)
-  for (int w = 0; w < wave; ++w) { gt_before += sc->seg[w][0]; eq_before += sc->seg[w][1]; }
+  // Counts over the segments in front of a wavefront's keys: lane s of every wavefront reads
+  // segment s (both counts in one word: neither sum exceeds 1024), a prefix sum over the sixteen
+  // lanes, and the wavefront picks the entries in front of its own two segments - one LDS round
+  // trip instead of one per segment.
+  uint32_t packed = 0;
+  if (lane < 2 * kWaves) {
+    const uint2 sg = *reinterpret_cast<const uint2*>(&sc->seg[lane][0]);
+    packed = sg.x | (sg.y << 16);
+  }
+  packed += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)packed, 0x111, 0xf, 0xf, true);   // row_shr:1
+  packed += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)packed, 0x112, 0xf, 0xf, true);   // row_shr:2
+  packed += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)packed, 0x114, 0xf, 0xf, true);   // row_shr:4
+  packed += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)packed, 0x118, 0xf, 0xf, true);   // row_shr:8
+  static_assert(2 * kWaves == 16, "one row of sixteen lanes holds the segments");
+  const uint32_t before0 = wave > 0 ? (uint32_t)__builtin_amdgcn_readlane((int)packed, wave - 1) : 0u;
+  uint32_t gt_before = before0 & 0xffffu, eq_before = before0 >> 16;
   {
     const uint32_t e = eq_before + (uint32_t)__popcll(eq0 & below);
     const bool is_gt = (gt0 >> lane) & 1ull, is_eq = (eq0 >> lane) & 1ull;
     if (is_gt || (is_eq && e < need)) sel[gt_before + (uint32_t)__popcll(gt0 & below) + min(e, need)] = tid;
   }
   if (nb > kThreads) {
-    for (int w = wave; w < kWaves + wave; ++w) { gt_before += sc->seg[w][0]; eq_before += sc->seg[w][1]; }
+    const uint32_t before1 = (uint32_t)__builtin_amdgcn_readlane((int)packed, kWaves + wave - 1);
+    gt_before = before1 & 0xffffu;
+    eq_before = before1 >> 16;
     const uint32_t e = eq_before + (uint32_t)__popcll(eq1 & below);
     const bool is_gt = (gt1 >> lane) & 1ull, is_eq = (eq1 >> lane) & 1ull;
     if (is_gt || (is_eq && e < need)) sel[gt_before + (uint32_t)__popcll(gt1 & below) + min(e, need)] = tid + kThreads;
