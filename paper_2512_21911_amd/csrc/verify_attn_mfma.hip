@@ -508,6 +508,12 @@ struct MergeLane {
   float m_acc, l_acc;
   u32x4 rec;          // record of split c0 + cl % 16 of this row
   Chunk t0[8], t1[8]; // fetched outputs of splits c0 .. c0 + 7 and c0 + 8 .. c0 + 15
+  // what the two batches weigh (formed while their outputs are on their way): the factor that
+  // brings the running sums to the batch's maximum, that maximum, the splits' weights, and the own
+  // split's output from LDS
+  float fa0, fa1, mb0, mb1;
+  float w0[8], w1[8];
+  Chunk own_chunk;
 };
 
 // This workgroup's own partial of the rows it merges, left in LDS by the threads that formed it:
@@ -564,50 +570,66 @@ __device__ __forceinline__ float chunk_value(const typename ChunkOf<CH>::type& t
   return (c & 1) ? bf16_hi(t[c >> 1]) : bf16_lo(t[c >> 1]);
 }
 
-// Splits c0 + B0 .. c0 + B0 + 7 into the running merge.
+// Splits c0 + B0 .. c0 + B0 + 7 into the running merge, in two steps.  batch_weights() needs the
+// records only (and the own split's maximum and denominator from LDS): it runs while the outputs
+// are being fetched, and is free of branches, because the compiler does not know that the
+// registers of a hand-issued load are in flight (see merge_fetch_weigh).  m_before: the running
+// maximum in front of the batch.
 template <int CH, int B0>
-__device__ __forceinline__ void finish_batch(const AttnParams& p, MergeLane<CH>& L, typename ChunkOf<CH>::type (&t)[8], int c0,
-                                             const OwnRows& own) {
+__device__ __forceinline__ void batch_weights(MergeLane<CH>& L, int c0, const OwnRows& own, float m_before, float (&w)[8],
+                                              float& fa, float& mb_out) {
   const int ou = own.split - c0 - B0;                  // (uniform) the own split's place in this batch
-  uint32_t mrec = L.rec[0], lrec = L.rec[2];
+  const bool from_lds = ou >= 0 && ou < 8;
+  // the own split's partial comes from LDS: its (maximum, denominator) into the lane that holds
+  // that split's record, its output in place of what is fetched (the reads are unconditional: own.o
+  // and own.ml always point into LDS)
+  const int orow = min(max(L.row - own.lo, 0), 31);
+  const typename ChunkOf<CH>::type oc =
+      *reinterpret_cast<const typename ChunkOf<CH>::type*>(own.o + orow * kRowBytes + L.cl * (CH * 2));
+  const uint32_t om = __float_as_uint(own.ml[2 * orow]), ol = __float_as_uint(own.ml[2 * orow + 1]);
+  L.own_chunk = (B0 == 0 || from_lds) ? oc : L.own_chunk;        // (the own split lies in one batch at most)
+  const bool here = from_lds && (L.cl & 15) == B0 + ou;
+  const uint32_t mrec = here ? om : L.rec[0], lrec = here ? ol : L.rec[2];
+  uint32_t mbits[8], lbits[8];
+  row_lanes_from<B0, 7>(mrec, mbits);
+  row_lanes_from<B0, 7>(lrec, lbits);
+  float mb = m_before;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) mb = fmaxf(mb, __uint_as_float(mbits[u]));
+  // (a row that no split saw a token for: every maximum is -inf; exp2(-inf - 0) = 0 for all of them)
+  const float ref = mb == -INFINITY ? 0.f : mb;
+  fa = fast_exp2(m_before - ref);
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    // weight of split s: exp2(m_s - m) * l_s, applied to its normalised output
+    w[u] = fast_exp2(__uint_as_float(mbits[u]) - ref) * __uint_as_float(lbits[u]);
+    asm volatile("" : "+v"(w[u]));                     // formed here, not behind the wait for the outputs
+  }
+  mb_out = mb;
+}
+
+template <int CH, int B0>
+__device__ __forceinline__ void batch_accumulate(MergeLane<CH>& L, typename ChunkOf<CH>::type (&t)[8], int c0, const OwnRows& own,
+                                                 const float (&w)[8], float fa, float mb) {
+  const int ou = own.split - c0 - B0;
   if (ou >= 0 && ou < 8) {
-    // the own split's partial comes from LDS: its (maximum, denominator) into the lane that holds
-    // that split's record, its output in place of what was fetched
-    const int orow = min(max(L.row - own.lo, 0), 31);
-    const typename ChunkOf<CH>::type oc =
-        *reinterpret_cast<const typename ChunkOf<CH>::type*>(own.o + orow * kRowBytes + L.cl * (CH * 2));
-    if ((L.cl & 15) == B0 + ou) {
-      mrec = __float_as_uint(own.ml[2 * orow]);
-      lrec = __float_as_uint(own.ml[2 * orow + 1]);
-    }
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       // (eight separate comparisons: folded into one store with a run-time index they would move
       // the fetched outputs from registers to scratch memory)
       int o = ou;
       asm volatile("" : "+s"(o));
-      if (o == u) t[u] = oc;
+      if (o == u) t[u] = L.own_chunk;
     }
   }
-  uint32_t mbits[8], lbits[8];
-  row_lanes_from<B0, 7>(mrec, mbits);
-  row_lanes_from<B0, 7>(lrec, lbits);
-  float mb = L.m_acc;
-#pragma unroll
-  for (int u = 0; u < 8; ++u) mb = fmaxf(mb, __uint_as_float(mbits[u]));
-  // (a row that no split saw a token for: every maximum is -inf; exp2(-inf - 0) = 0 for all of them)
-  const float ref = mb == -INFINITY ? 0.f : mb;
-  const float fa = fast_exp2(L.m_acc - ref);
   L.l_acc *= fa;
 #pragma unroll
   for (int c = 0; c < CH; ++c) L.acc[c] *= fa;
 #pragma unroll
   for (int u = 0; u < 8; ++u) {
-    // weight of split s: exp2(m_s - m) * l_s, applied to its normalised output
-    const float w = fast_exp2(__uint_as_float(mbits[u]) - ref) * __uint_as_float(lbits[u]);
-    L.l_acc += w;
+    L.l_acc += w[u];
 #pragma unroll
-    for (int c = 0; c < CH; ++c) L.acc[c] += w * chunk_value<CH>(t[u], c);
+    for (int c = 0; c < CH; ++c) L.acc[c] += w[u] * chunk_value<CH>(t[u], c);
   }
   L.m_acc = mb;
 }
@@ -648,32 +670,33 @@ __device__ __forceinline__ void chunks_wait16(T (&a)[8], T (&b)[8]) {
                : "memory");
 }
 
-// Splits c0 .. c0 + 15 of the lane's row: waits for their records (bounded), then fetches their
-// outputs.  False for the whole wavefront when a record was still missing.
+// Splits c0 .. c0 + 15 of the lane's row, once their records are in (poll_records): fetches their
+// outputs and, while those are on their way, forms the weights.  The own split's rows, if LDS holds
+// them, must be complete.
 template <int CH>
-__device__ __forceinline__ bool merge_fetch(const AttnParams& p, MergeLane<CH>& L, int pair, int row0, int c0, uint32_t tag,
-                                            int budget, int own_split) {
+__device__ __forceinline__ void merge_fetch_weigh(const AttnParams& p, MergeLane<CH>& L, int pair, int row0, int c0,
+                                                  const OwnRows& own) {
   const int S = p.n_splits;
-  const int64_t g_row = (int64_t)pair * S * p.Mpad + row0 + L.row;
   const uint32_t voff = (uint32_t)(((row0 + L.row) * kD + L.cl * CH) * 2);
-  if (!poll_records(p, L, g_row, c0, tag, budget, own_split)) return false;
   // (straight-line code between every hand-issued load and its wait: the compiler does not know
   // that the registers are still in flight, and a copy it places at a branch or a join in between
   // would copy what was there before)
   if (c0 + 8 < S) {
     fetch_batch<CH, 0>(p, L.t0, pair, voff, c0);
     fetch_batch<CH, 8>(p, L.t1, pair, voff, c0);
+    batch_weights<CH, 0>(L, c0, own, L.m_acc, L.w0, L.fa0, L.mb0);
+    batch_weights<CH, 8>(L, c0, own, L.mb0, L.w1, L.fa1, L.mb1);
     chunks_wait16(L.t0, L.t1);
   } else {
     fetch_batch<CH, 0>(p, L.t0, pair, voff, c0);
+    batch_weights<CH, 0>(L, c0, own, L.m_acc, L.w0, L.fa0, L.mb0);
     chunks_wait(L.t0);
   }
-  return true;
 }
 template <int CH>
 __device__ __forceinline__ void merge_finish(const AttnParams& p, MergeLane<CH>& L, int c0, const OwnRows& own) {
-  finish_batch<CH, 0>(p, L, L.t0, c0, own);
-  if (c0 + 8 < p.n_splits) finish_batch<CH, 8>(p, L, L.t1, c0, own);
+  batch_accumulate<CH, 0>(L, L.t0, c0, own, L.w0, L.fa0, L.mb0);
+  if (c0 + 8 < p.n_splits) batch_accumulate<CH, 8>(L, L.t1, c0, own, L.w1, L.fa1, L.mb1);
 }
 
 // Merges rows lo <= r < hi of the row group (all passes, all splits) and writes them out.  Returns
@@ -687,7 +710,9 @@ __device__ __forceinline__ bool merge_rows(const AttnParams& p, int lo, int hi, 
     init_lane(L, mt, r0, hi);
     if (!__any(L.active)) continue;
     for (int c0 = 0; c0 < p.n_splits; c0 += 16) {
-      if (!merge_fetch(p, L, pair, row0, c0, tag, budget, own.split)) return false;
+      const int64_t g_row = (int64_t)pair * p.n_splits * p.Mpad + row0 + L.row;
+      if (!poll_records(p, L, g_row, c0, tag, budget, own.split)) return false;
+      merge_fetch_weigh(p, L, pair, row0, c0, own);
       merge_finish(p, L, c0, own);
     }
     store_merged(p, L, row0, orow_pair);
@@ -1653,18 +1678,19 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   const bool merger = wave == kMergeWave0 || wave == kMergeWave0 + 1;
   const int mt = tid - kMergeWave0 * 64;
   const bool ch4 = R <= 4;                                   // 4 channels per merging thread, else 8
-  // one pass over the rows and one batch of records: the other splits' partials are fetched now
+  // one pass over the rows and one batch of records: the other splits' records are waited for now
   const bool prefetch = S <= 16 && R <= (ch4 ? 4 : 8) && lo < 32;
   MergeLane<4> L4;
   MergeLane<8> L8;
-  bool fetched = false;
+  bool records_in = false;
   if (merger && prefetch) {
+    const int64_t g_row0 = (int64_t)pair * S * p.Mpad + row0;
     if (ch4) {
       init_lane(L4, mt, lo, hi);
-      fetched = !__any(L4.active) || merge_fetch(p, L4, pair, row0, 0, tag, wait_polls, split);
+      records_in = !__any(L4.active) || poll_records(p, L4, g_row0 + L4.row, 0, tag, wait_polls, split);
     } else {
       init_lane(L8, mt, lo, hi);
-      fetched = !__any(L8.active) || merge_fetch(p, L8, pair, row0, 0, tag, wait_polls, split);
+      records_in = !__any(L8.active) || poll_records(p, L8, g_row0 + L8.row, 0, tag, wait_polls, split);
     }
   }
   if (merger) {
@@ -1684,16 +1710,20 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   bool gave_up = false;
   if (merger && prefetch) {
     todo = 0u;
-    if (!fetched) {
+    if (!records_in) {
       gave_up = true;
     } else {
+      // the other splits' outputs are fetched; their weights (and the own split's, from LDS) are
+      // formed in the meantime
       const OwnRows own = {own_o, own_ml, lo, split};
       if (ch4) {
         if (__any(L4.active)) {
+          merge_fetch_weigh(p, L4, pair, row0, 0, own);
           merge_finish(p, L4, 0, own);
           store_merged(p, L4, row0, orow_pair);
         }
       } else if (__any(L8.active)) {
+        merge_fetch_weigh(p, L8, pair, row0, 0, own);
         merge_finish(p, L8, 0, own);
         store_merged(p, L8, row0, orow_pair);
       }
@@ -2111,7 +2141,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   const int nrg = min(kWaves, p.Mpad / 32 - zs * kWaves);      // row groups of this set
   const int mt = (wave & 1) * 64 + lane;                       // thread of the wavefront pair
   const int r_lo = 8 * (wave >> 1);                            // the pair's rows of a row group
-  const OwnRows nothing_in_lds = {nullptr, nullptr, 0, -1};
+  // (what the merge reads of them without looking at it must still be LDS addresses)
+  const OwnRows nothing_in_lds = {smem, reinterpret_cast<const float*>(smem), 0, -1};
   uint32_t todo = split < nrg ? 1u << split : 0u;
   int budget = wait_polls;
   bool gave_up = false;
