@@ -514,6 +514,7 @@ struct MergeLane {
   float fa0, fa1, mb0, mb1;
   float w0[8], w1[8];
   Chunk own_chunk;
+  int64_t orow;       // where the merged row goes (row of out / lse), worked out in the same shadow
 };
 
 // This workgroup's own partial of the rows it merges, left in LDS by the threads that formed it:
@@ -613,18 +614,23 @@ __device__ __forceinline__ void batch_accumulate(MergeLane<CH>& L, typename Chun
                                                  const float (&w)[8], float fa, float mb) {
   const int ou = own.split - c0 - B0;
   if (ou >= 0 && ou < 8) {
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      // (eight separate comparisons: folded into one store with a run-time index they would move
-      // the fetched outputs from registers to scratch memory)
-      int o = ou;
-      asm volatile("" : "+s"(o));
-      if (o == u) t[u] = L.own_chunk;
+    // (a tree of uniform branches with one assignment at each leaf: a store with a run-time index
+    // would move the fetched outputs from registers to scratch memory, eight selects cost eight
+    // times as much behind the wait)
+    if (ou & 4) {
+      if (ou & 2) { if (ou & 1) t[7] = L.own_chunk; else t[6] = L.own_chunk; }
+      else { if (ou & 1) t[5] = L.own_chunk; else t[4] = L.own_chunk; }
+    } else {
+      if (ou & 2) { if (ou & 1) t[3] = L.own_chunk; else t[2] = L.own_chunk; }
+      else { if (ou & 1) t[1] = L.own_chunk; else t[0] = L.own_chunk; }
     }
   }
-  L.l_acc *= fa;
+  // (in front of the very first batch the sums are zero and stay zero: 0 x fa = +0)
+  if (!(B0 == 0 && c0 == 0)) {
+    L.l_acc *= fa;
 #pragma unroll
-  for (int c = 0; c < CH; ++c) L.acc[c] *= fa;
+    for (int c = 0; c < CH; ++c) L.acc[c] *= fa;
+  }
 #pragma unroll
   for (int u = 0; u < 8; ++u) {
     L.l_acc += w[u];
@@ -648,11 +654,16 @@ __device__ __forceinline__ void init_lane(MergeLane<CH>& L, int mt, int r0, int 
 
 // The merged row goes out (CH channels per thread) with its log-sum-exp.
 template <int CH>
-__device__ __forceinline__ void store_merged(const AttnParams& p, const MergeLane<CH>& L, int row0, int64_t orow_pair) {
+__device__ __forceinline__ void merged_row_address(const AttnParams& p, MergeLane<CH>& L, int row0, int64_t orow_pair) {
   const int grow = row0 + L.row;
-  if (!L.active || grow >= p.M) return;
   const int oi = (int)(((uint64_t)(uint32_t)grow * p.g_magic) >> 32), oj = grow - oi * p.G;
-  const int64_t orow = orow_pair + (int64_t)oi * p.Hq + oj;
+  L.orow = (L.active && grow < p.M) ? orow_pair + (int64_t)oi * p.Hq + oj : -1;
+  asm volatile("" : "+v"(L.orow));                       // worked out here, not behind the wait for the outputs
+}
+template <int CH>
+__device__ __forceinline__ void store_merged(const AttnParams& p, const MergeLane<CH>& L) {
+  const int64_t orow = L.orow;
+  if (orow < 0) return;
   const float inv = L.l_acc > 0.f ? __builtin_amdgcn_rcpf(L.l_acc) : 0.f;   // a row that saw no key at all: zero, lse = -inf
   typename ChunkOf<CH>::type o;
 #pragma unroll
@@ -675,7 +686,7 @@ __device__ __forceinline__ void chunks_wait16(T (&a)[8], T (&b)[8]) {
 // them, must be complete.
 template <int CH>
 __device__ __forceinline__ void merge_fetch_weigh(const AttnParams& p, MergeLane<CH>& L, int pair, int row0, int c0,
-                                                  const OwnRows& own) {
+                                                  const OwnRows& own, int64_t orow_pair) {
   const int S = p.n_splits;
   const uint32_t voff = (uint32_t)(((row0 + L.row) * kD + L.cl * CH) * 2);
   // (straight-line code between every hand-issued load and its wait: the compiler does not know
@@ -686,10 +697,12 @@ __device__ __forceinline__ void merge_fetch_weigh(const AttnParams& p, MergeLane
     fetch_batch<CH, 8>(p, L.t1, pair, voff, c0);
     batch_weights<CH, 0>(L, c0, own, L.m_acc, L.w0, L.fa0, L.mb0);
     batch_weights<CH, 8>(L, c0, own, L.mb0, L.w1, L.fa1, L.mb1);
+    merged_row_address(p, L, row0, orow_pair);
     chunks_wait16(L.t0, L.t1);
   } else {
     fetch_batch<CH, 0>(p, L.t0, pair, voff, c0);
     batch_weights<CH, 0>(L, c0, own, L.m_acc, L.w0, L.fa0, L.mb0);
+    merged_row_address(p, L, row0, orow_pair);
     chunks_wait(L.t0);
   }
 }
@@ -712,10 +725,10 @@ __device__ __forceinline__ bool merge_rows(const AttnParams& p, int lo, int hi, 
     for (int c0 = 0; c0 < p.n_splits; c0 += 16) {
       const int64_t g_row = (int64_t)pair * p.n_splits * p.Mpad + row0 + L.row;
       if (!poll_records(p, L, g_row, c0, tag, budget, own.split)) return false;
-      merge_fetch_weigh(p, L, pair, row0, c0, own);
+      merge_fetch_weigh(p, L, pair, row0, c0, own, orow_pair);
       merge_finish(p, L, c0, own);
     }
-    store_merged(p, L, row0, orow_pair);
+    store_merged(p, L);
   }
   return true;
 }
@@ -1718,14 +1731,14 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       const OwnRows own = {own_o, own_ml, lo, split};
       if (ch4) {
         if (__any(L4.active)) {
-          merge_fetch_weigh(p, L4, pair, row0, 0, own);
+          merge_fetch_weigh(p, L4, pair, row0, 0, own, orow_pair);
           merge_finish(p, L4, 0, own);
-          store_merged(p, L4, row0, orow_pair);
+          store_merged(p, L4);
         }
       } else if (__any(L8.active)) {
-        merge_fetch_weigh(p, L8, pair, row0, 0, own);
+        merge_fetch_weigh(p, L8, pair, row0, 0, own, orow_pair);
         merge_finish(p, L8, 0, own);
-        store_merged(p, L8, row0, orow_pair);
+        store_merged(p, L8);
       }
     }
   }
