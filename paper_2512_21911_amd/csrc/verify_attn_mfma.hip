@@ -474,6 +474,15 @@ __device__ __forceinline__ u32x4 load_record_now(const void* p) {
   asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
   return v;
 }
+// The same, and a word of LDS read in the load's shadow (lds_word keeps its value in lanes that are off).
+__device__ __forceinline__ u32x4 load_record_now(const void* p, uint32_t lds_addr, uint32_t& lds_word) {
+  u32x4 v;
+  asm volatile("ds_read_b32 %1, %3\n\tglobal_load_dwordx4 %0, %2, off sc1\n\ts_waitcnt vmcnt(0) lgkmcnt(0)"
+               : "=v"(v), "+v"(lds_word)
+               : "v"(p), "v"(lds_addr)
+               : "memory");
+  return v;
+}
 __device__ __forceinline__ void load_chunk(u32x2& v, uint64_t base, uint32_t off) {
   asm volatile("global_load_dwordx2 %0, %1, %2 sc1" : "=v"(v) : "v"(off), "s"(base) : "memory");
 }
@@ -529,23 +538,29 @@ struct OwnRows {
 // Waits (at most `budget` polls) until the records of splits c0 .. c0 + 15 of the lane's row carry
 // the tag; the own split's record is not waited for when its partial comes from LDS.  Returns false
 // for the whole wavefront when some record is still missing.
+// watch / watched_for (optional): the LDS word at address `watch` is read along with every poll;
+// *watch_hit tells whether it was seen to hold `watched_for` (what the caller waits for next: by
+// the time the records are in, it has usually happened, and no further look is needed).
 template <int CH>
 __device__ __forceinline__ bool poll_records(const AttnParams& p, MergeLane<CH>& L, int64_t g_row, int c0, uint32_t tag,
-                                             int budget, int own_split) {
+                                             int budget, int own_split, uint32_t watch = 0, uint32_t watched_for = 0,
+                                             bool* watch_hit = nullptr) {
   const int S = p.n_splits;
   const int sp = c0 + (L.cl & 15);
   const uint32_t* recp = p.part_rec + (g_row + (int64_t)min(sp, S - 1) * p.Mpad) * 4;
   // (past the last split: a record that weighs nothing)
   L.rec = u32x4{sp < S ? 0u : 0xff800000u, 0u, 0u, 0u};
   bool pending = L.active && sp < S && sp != own_split;
+  uint32_t word = ~watched_for;
   for (int it = 0;; ++it) {
-    if (!__any(pending)) return true;
-    if (it >= budget) return false;
+    if (!__any(pending) || it >= budget) break;
     if (pending) {
-      L.rec = load_record_now(recp);
+      L.rec = watch_hit ? load_record_now(recp, watch, word) : load_record_now(recp);
       pending = !(L.rec[1] == tag && L.rec[3] == tag);
     }
   }
+  if (watch_hit) *watch_hit = __any(word == watched_for);
+  return !__any(pending);
 }
 
 // Requests the outputs of splits c0 + B0 .. c0 + B0 + 7 of the lane's row (past the last split: the
@@ -1696,19 +1711,21 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   MergeLane<4> L4;
   MergeLane<8> L8;
   bool records_in = false;
+  // the own rows are in LDS once wavefronts 0 .. 3 have all said so (they wait for nobody); the
+  // polls for the records look at that counter as well
+  const uint32_t ready = (uint32_t)(uintptr_t)SVF_LDS_PTR(&sm_own_ready);
+  bool own_rows_in = false;
   if (merger && prefetch) {
     const int64_t g_row0 = (int64_t)pair * S * p.Mpad + row0;
     if (ch4) {
       init_lane(L4, mt, lo, hi);
-      records_in = !__any(L4.active) || poll_records(p, L4, g_row0 + L4.row, 0, tag, wait_polls, split);
+      records_in = !__any(L4.active) || poll_records(p, L4, g_row0 + L4.row, 0, tag, wait_polls, split, ready, 4u, &own_rows_in);
     } else {
       init_lane(L8, mt, lo, hi);
-      records_in = !__any(L8.active) || poll_records(p, L8, g_row0 + L8.row, 0, tag, wait_polls, split);
+      records_in = !__any(L8.active) || poll_records(p, L8, g_row0 + L8.row, 0, tag, wait_polls, split, ready, 4u, &own_rows_in);
     }
   }
-  if (merger) {
-    // the own rows are in LDS once wavefronts 0 .. 3 have all said so (they wait for nobody)
-    const uint32_t ready = (uint32_t)(uintptr_t)SVF_LDS_PTR(&sm_own_ready);
+  if (merger && !own_rows_in) {
     for (int it = 0; it < kLastResortPolls; ++it) {
       uint32_t n;
       asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(n) : "v"(ready) : "memory");
