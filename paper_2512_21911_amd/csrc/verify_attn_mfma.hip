@@ -44,9 +44,10 @@
 // Merge.  The computing wavefronts combine through LDS (log-sum-exp rule).  With one split the
 // workgroup writes out / lse itself.  Otherwise every workgroup of a (pair, row group) stores a
 // partial (normalised output in bf16, (m, l) in fp32 inside a 16-byte record that carries the
-// call's tag twice) and then merges a slice of the rows itself: two of its wavefronts prefetch
-// the other splits' partials for that slice, wait (a bounded number of polls) until every
-// record shows the tag, and sum in split order, taking the own split from LDS.  No workgroup
+// call's tag twice) and then merges a slice of the rows itself: two of its wavefronts wait (a
+// bounded number of polls) until every record of the other splits' rows of that slice shows the
+// tag, fetch those partials (forming the weights while they are on their way), and sum in split
+// order, taking the own split from LDS.  No workgroup
 // waits for all others and none is the designated merger; a slice whose wait ran out is marked
 // in the group's arrival word and merged by whichever workgroup arrives last.  The tag is the
 // group's call counter plus one, kept in the workspace and advanced by the workgroup that
