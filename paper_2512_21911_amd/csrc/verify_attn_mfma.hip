@@ -1328,9 +1328,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     L = rt.L;
     cnt = rt.cnt;
     // gather entries of this wavefront's tiles (lane 8u + n: group n of its u-th tile), kept for
-    // the loads below; they are written out for the layers that reuse the selection, and the
-    // selection itself, behind the combination of the wavefronts: a store in front of the stream
-    // would be one more thing the stream's first wait has to see acknowledged
+    // the loads below and written out for the layers that reuse the selection, together with the
+    // selection itself, right in front of the stream
     {
       const int tc = gw + (lane >> 3) * NW - tiles_d;                          // cache tile index
       const int e = tc * 8 + (lane & 7);
@@ -1468,6 +1467,17 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   // (draining the counter here keeps later register reuse from being mistaken for a hazard
   // against the stream); with one, the query fragments may still be on their way.
   if (MODE != kGather) wait_vmcnt<0>();
+  // The selection and the gather list for the layers that reuse them: stored here, in front of the
+  // stream (their acknowledgements come back long before the first tile does; stored behind the
+  // stream instead, an anchor launch took 0.14 us longer).  The workgroup with the least other work
+  // publishes the selection (s_sel is not a stage).
+  if (MODE == kSelect) {
+    if (split == p.n_splits - 1 && rg == 0) publish_selection(p, s_sel, cnt, pair, tid);
+    const int tc = gw + (lane >> 3) * NW - tiles_d;
+    const int e = tc * 8 + (lane & 7);
+    if (rg == 0 && lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups)
+      p.gather_out[(int64_t)pair * p.gather_groups + e] = gent;
+  }
   if (!p.draft_mask) rmask = qi >= 63 ? ~0ull : ((2ull << qi) - 1ull);     // linear causal drafts
   if (!row_valid) rmask = 0;
 
@@ -1562,21 +1572,6 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
   if (wave == kWaves - 1 && lane == 0)
     sm_one_xcd = counts_xcds && where == (uint64_t)p.n_splits << (8 * xcc_id()) ? 1 : 0;
   __syncthreads();
-
-  // The selection and the gather list for the layers that reuse them go out behind the stream
-  // (a store in front of it would be one more thing the stream's first wait has to see
-  // acknowledged): here by the wavefronts that do not combine, and by wavefronts 0 .. 3 only once
-  // their partial and its records are out, so that the wait for the partial's acknowledgement
-  // is not a wait for these stores as well.  The workgroup with the least other work publishes the
-  // selection (s_sel is not a stage).
-  auto publish_retrieval = [&]() {
-    if (split == p.n_splits - 1 && rg == 0) publish_selection(p, s_sel, cnt, pair, tid);
-    const int tc = gw + (lane >> 3) * NW - tiles_d;
-    const int e = tc * 8 + (lane & 7);
-    if (rg == 0 && lane < 8 * kMaxTiles && tc >= 0 && e < p.gather_groups)
-      p.gather_out[(int64_t)pair * p.gather_groups + e] = gent;
-  };
-  if (MODE == kSelect && wave >= 4) publish_retrieval();
 
   // ---- what happens to the workgroup's result --------------------------------------------------------
   // One split: wavefronts 0 .. 3 write out / lse.  Otherwise the splits of a group are merged by
@@ -1700,7 +1695,6 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       }
       if (tid == 0) prev = __hip_atomic_fetch_add(arrivals, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (MODE == kSelect) publish_retrieval();
   }
   if (single) return;
 
@@ -1953,10 +1947,11 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
     const Retrieved rt = retrieve_blocks(p, rl, smem, s_sel, &s_exchange_failed, L, pair, split, xgroup, tid, lane, wave, []() {});
     L = rt.L;
     cnt = rt.cnt;
-    // (the selection and the gather entries are written out behind the tile loop: a store in front
-    // of it would be one more thing the loop's first wait has to see acknowledged)
     if (e_ok) gent = gather_entry_of(p, s_sel, rt, rl, e_u, b, h);
     __syncthreads();                 // the last reads of the staged page table are done
+    // for the layers that reuse this retrieval (s_sel is not a stage): stored in front of the tile loop
+    if (split == S - 1 && zs == 0) publish_selection(p, s_sel, cnt, pair, tid);
+    if (e_ok && zs == 0) p.gather_out[(int64_t)pair * p.gather_groups + e_u] = gent;
   } else {
     if (MODE != kGather) cnt_raw = p.sel_cnt[pair + vzero];
     cnt = __builtin_amdgcn_readfirstlane(min(max(cnt_raw, 0), p.k_blocks));
@@ -2097,10 +2092,6 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  if (MODE == kSelect) {             // for the layers that reuse this retrieval (s_sel is not a stage)
-    if (split == S - 1 && zs == 0) publish_selection(p, s_sel, cnt, pair, tid);
-    if (e_ok && zs == 0) p.gather_out[(int64_t)pair * p.gather_groups + e_u] = gent;
-  }
   if (S == 1 && !has_rows) return;   // (with one split: no barrier from here on)
 
   // ---- this wavefront's 32 rows: output or partial ------------------------------------------------
