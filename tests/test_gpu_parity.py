@@ -289,6 +289,41 @@ def test_exact_ties_lowest_index_wins():
     assert (run.sel_idx.cpu().numpy() == np.array([0, 1, 2, 15])).all()
 
 
+@pytest.mark.parametrize("T,n_sink,n_local", [(32768, 0, 0), (65536, 0, 0), (65536, 1, 2), (40000, 2, 1)])
+def test_ties_in_the_anchor_launch_lowest_index_wins(T, n_sink, n_local):
+    """Sec. 3.1 top-N rule with equal scores (the lowest block index wins), through the retrieval
+    that runs inside the anchor layer's attention launch: 512 and up to 1024 blocks (one and two
+    keys per thread of the selecting workgroup), all scores equal and scores equal in runs.  The
+    ids must be those of svf_score_select on the same representatives, and for all-equal scores
+    the closed form: forced blocks, then the lowest indices."""
+    cfg = W.CONFIGS[3].scaled(T=T, n_sink=n_sink, n_local=n_local)
+    x = W.make_layer(cfg)
+    run = DeviceRun(cfg, to_gpu(x), poison=False)
+    nb = -(-T // cfg.block_size)
+    k = run.shape.k_blocks
+    # (a) every score ties
+    run.reps.fill_(0.25)
+    run.verify_step(S.SVF_STEP_ANCHOR).sync()
+    forced = list(range(n_sink)) + list(range(nb - n_local, nb))
+    free = [j for j in range(nb) if j not in forced][: k - len(forced)]
+    want = np.array(sorted(forced + free), dtype=np.int32)
+    got = run.sel_idx.cpu().numpy()
+    assert (got == want[None, None, :]).all()
+    assert (run.sel_cnt.cpu().numpy() == k).all()
+    # (b) runs of equal scores: representative j = level(j) in every channel, so that the score is
+    # level(j) x (sum of the mean query's channels); whatever that sum's sign, ties abound and the
+    # threshold falls inside a run
+    levels = torch.tensor([((j * 7) % 5) * 0.125 for j in range(cfg.nb_max)], device="cuda")
+    run.reps.copy_(levels[None, None, :, None].expand_as(run.reps))
+    run.verify_step(S.SVF_STEP_ANCHOR).sync()
+    fused_idx, fused_cnt = run.sel_idx.clone(), run.sel_cnt.clone()
+    run.score_select().sync()
+    assert torch.equal(fused_idx, run.sel_idx) and torch.equal(fused_cnt, run.sel_cnt)
+    sc = run.scores.cpu().double().numpy()
+    idx, cnt = O.select_blocks(sc, x["seq_lens"], cfg.block_size, cfg.k_blocks, n_sink, n_local)
+    assert (fused_idx.cpu().numpy() == idx).all() and (fused_cnt.cpu().numpy() == cnt).all()
+
+
 # ------------------------------------------------------------------ properties that hold at any size
 
 def test_constant_values_give_constant_output():
