@@ -2046,11 +2046,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   // One barrier per window rather than per tile: behind a barrier all eight wavefronts are in the
   // same phase (all reading LDS, then all on the matrix cores, then all in the softmax); over three
   // tiles they drift apart and one wavefront's MFMA runs under the other's vector work.  The first
-  // windows are short so that the arithmetic starts when the first tile is in, not the third.  Of
-  // the two wavefronts of a SIMD one is given priority: they then take turns by themselves instead
-  // of reaching for the same unit at the same time.  Stages of tiles that everybody has left take
-  // the next tiles.
-  if (wave < kWaves / 2) __builtin_amdgcn_s_setprio(1);
+  // windows are short so that the arithmetic starts when the first tile is in, not the third.
+  // Stages of tiles that everybody has left take the next tiles.
   // Only the first tiles are requested up front and the others as the windows advance (the window
   // at hand plus kRowAhead tiles are in flight): with every tile of every workgroup requested at
   // once, a workgroup's first tile is served no sooner than most of the launch's bytes.
@@ -2087,7 +2084,6 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
       }
     }
   }
-  __builtin_amdgcn_s_setprio(0);
   // the other wavefronts may still be reading the last window's stages
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();
