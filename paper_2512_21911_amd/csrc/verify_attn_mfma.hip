@@ -119,6 +119,29 @@ __device__ __forceinline__ u32x2 lds_read8_tr(uint32_t addr) {
   asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
   return v;
 }
+// The eight transposing reads of one k-step of the second product.  Piece e = 2 nt + h is chunk
+// 4 nt + vc of the token rows vtok + 8 h (+ 16 KS2), at the swizzled position (4 nt + vc) ^ token.
+// With L = vc ^ (vtok & 3) (bits 0, 1), g = bit 2 of vtok and h = bit 3 of the token that is
+//   16 L + 64 ((nt & 1) ^ g) + 128 ((nt >> 1) ^ h),
+// and 64 ((nt & 1) ^ g) = 64 (nt & 1) + 64 g for even nt, 64 (nt & 1) - 64 g for odd nt: two
+// per-lane addresses (even / odd nt) and an immediate per piece, instead of an XOR and an addition
+// per piece in every tile.
+template <int E, int KS2>
+__device__ __forceinline__ u32x2 lds_read_vt_piece(uint32_t even, uint32_t odd) {
+  constexpr int nt = E >> 1, h = E & 1;
+  return lds_read8_tr<64 * (nt & 1) + 128 * ((nt >> 1) ^ h) + h * 8 * kRowBytes + KS2 * 16 * kRowBytes>((nt & 1) ? odd : even);
+}
+template <int KS2>
+__device__ __forceinline__ void lds_read_vt(u32x2 (&x)[8], uint32_t even, uint32_t odd) {
+  x[0] = lds_read_vt_piece<0, KS2>(even, odd);
+  x[1] = lds_read_vt_piece<1, KS2>(even, odd);
+  x[2] = lds_read_vt_piece<2, KS2>(even, odd);
+  x[3] = lds_read_vt_piece<3, KS2>(even, odd);
+  x[4] = lds_read_vt_piece<4, KS2>(even, odd);
+  x[5] = lds_read_vt_piece<5, KS2>(even, odd);
+  x[6] = lds_read_vt_piece<6, KS2>(even, odd);
+  x[7] = lds_read_vt_piece<7, KS2>(even, odd);
+}
 // Waits for all LDS reads; the registers pass through the statement so that no use of them can
 // be scheduled above the wait.
 template <typename T>
@@ -303,6 +326,8 @@ __device__ __forceinline__ void process_tile(uint32_t stage, const bf16x8 (&qf)[
   const uint32_t vtok = (uint32_t)(4 * g + ((l32 & 15) >> 2));
   const uint32_t vc = (uint32_t)(2 * ((l32 >> 4) & 1) + ((l32 & 3) >> 1));
   const uint32_t vbase = stage + kTileBytes + vtok * kRowBytes + ((uint32_t)(l32 & 1) << 3);
+  const uint32_t vswz = (vc ^ (vtok & 3u)) << 4;
+  const uint32_t v_even = vbase + vswz + ((uint32_t)g << 6), v_odd = vbase + vswz - ((uint32_t)g << 6);
 
   // S^T = K Q^T : token = lane mod 32 (A rows), query row = lane mod 32 (B columns)
   floatx16 sacc;
@@ -321,11 +346,7 @@ __device__ __forceinline__ void process_tile(uint32_t stage, const bf16x8 (&qf)[
   }
   // the V^T fragments of the first k-step: in flight while the softmax runs.  x[2 * nt + h]
   u32x2 x[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const uint32_t tok = vtok + 8u * (uint32_t)(e & 1);
-    x[e] = lds_read8_tr<0>(vbase + (uint32_t)(e & 1) * (8u * kRowBytes) + (((4u * (uint32_t)(e >> 1) + vc) ^ tok) << 4));
-  }
+  lds_read_vt<0>(x, v_even, v_odd);
 
   // online softmax; value v of a lane is token 8*(v/4) + 4*g + v%4 of the tile.
   // Invisible tokens drop out by setting their raw score to -inf (the scale is positive).
@@ -378,13 +399,7 @@ __device__ __forceinline__ void process_tile(uint32_t stage, const bf16x8 (&qf)[
   // group g is token 16*ks2 + 8*(e/4) + 4*g + e%4.  x[2*nt + h] holds k-slots 4*h .. 4*h+3.
 #pragma unroll
   for (int ks2 = 0; ks2 < 2; ++ks2) {
-    if (ks2 == 1) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const uint32_t tok = vtok + 8u * (uint32_t)(e & 1);
-        x[e] = lds_read8_tr<16 * kRowBytes>(vbase + (uint32_t)(e & 1) * (8u * kRowBytes) + (((4u * (uint32_t)(e >> 1) + vc) ^ tok) << 4));
-      }
-    }
+    if (ks2 == 1) lds_read_vt<1>(x, v_even, v_odd);
     lds_wait8(x);
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt) {
