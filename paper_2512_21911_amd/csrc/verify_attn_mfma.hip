@@ -1447,6 +1447,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
     // groups' counts as they pass through scalar registers)
     uint32_t valid = 0;
     unsigned char* vdst = dst + kTileBytes;
+    // (one multiplication per tile, not one per group: min(row, k) x bytes = min(row x bytes, k x bytes))
+    const uint32_t lrow_off = (uint32_t)lrow * row_bytes;
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
       const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)base, src0 + n);
@@ -1457,8 +1459,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_kernel(AttnParams p
       const char* kb = reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
       const char* vb = kb + (fd ? dv_d : dv_c);
       // rows past the group's last valid row re-read that row
-      const uint32_t r = min((uint32_t)lrow, (uint32_t)max(nvn - 1, 0));
-      const uint32_t off = r * row_bytes + ((cx ^ (uint32_t)((4 * n) & 15)) << 4);
+      const uint32_t last_off = (uint32_t)max(nvn - 1, 0) * (uint32_t)__builtin_amdgcn_readfirstlane((int)row_bytes);
+      const uint32_t off = min(lrow_off, last_off) + ((cx ^ (uint32_t)((4 * n) & 15)) << 4);
       if (skip_void_groups && nvn == 0) continue;        // (wave-uniform)
       __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(kb + off), SVF_LDS_PTR(dst + n * 1024), 16, 0, 2);
       __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(vb + off), SVF_LDS_PTR(vdst + n * 1024), 16, 0, 2);
@@ -1840,6 +1842,7 @@ struct RowTileIssue {
   uint64_t gent;                 // lane u: gather entry of (u-th tile, this wavefront's group)
   int split, S, tiles_d, gamma, wave, lane;
   uint32_t lrow, cx, tok_bytes, drow_bytes;
+  uint32_t lrow_tok_off, lrow_draft_off;     // lrow x tok_bytes, lrow x drow_bytes
 };
 
 // This wavefront's two loads of the workgroup's i-th tile (slots 4 * wave .. 4 * wave + 3).
@@ -1872,8 +1875,10 @@ __device__ __forceinline__ void issue_row_tile(const RowTileIssue& c, int i) {
   }
   const uint64_t fd = (uint64_t)0 - (uint64_t)from_draft;
   const char* vb = kb + (int64_t)(((uint64_t)c.dv_d & fd) | ((uint64_t)c.dv_c & ~fd));
-  const uint32_t r = min(c.lrow, (uint32_t)max(nv - 1, 0));
-  const uint32_t off = r * row_bytes + ((c.cx ^ (uint32_t)((4 * c.wave) & 15)) << 4);
+  // (min(row, k) x bytes = min(row x bytes, k x bytes): the lane's product is formed once)
+  const uint32_t dt = 0u - (uint32_t)(t < c.tiles_d);          // (a draft tile: its rows lie drow_bytes apart)
+  const uint32_t lrow_off = (c.lrow_draft_off & dt) | (c.lrow_tok_off & ~dt);
+  const uint32_t off = min(lrow_off, (uint32_t)max(nv - 1, 0) * row_bytes) + ((c.cx ^ (uint32_t)((4 * c.wave) & 15)) << 4);
   __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(kb + off), SVF_LDS_PTR(dst + c.wave * 1024), 16, 0, 2);
   __builtin_amdgcn_global_load_lds(SVF_GLOBAL_PTR(vb + off), SVF_LDS_PTR(dst + kTileBytes + c.wave * 1024), 16, 0, 2);
 }
@@ -2021,6 +2026,8 @@ __global__ __launch_bounds__(kThreads) void verify_attn_mfma_rows_kernel(AttnPar
   ic.cx = cx;
   ic.tok_bytes = tok_bytes;
   ic.drow_bytes = drow_bytes;
+  ic.lrow_tok_off = (uint32_t)lrow * tok_bytes;
+  ic.lrow_draft_off = (uint32_t)lrow * drow_bytes;
 
   float m_run = -INFINITY, l_run = 0.f;
   floatx16 oacc[4];
